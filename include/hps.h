@@ -1,0 +1,177 @@
+/*
+ * hps.h -- C ABI of the HBM-resident parameter server's mini-batch pull/push path
+ *          for one MI355X (gfx950).
+ *
+ * What is modelled (paper: "Distributed Hierarchical GPU Parameter Server for
+ * Massive Scale Deep Learning Ads Systems", MLSys 2020):
+ *   - Section 4.1 "Local GPU hash table": an open-addressing hash table in HBM,
+ *     capacity fixed at construction (no device allocation afterwards), integrity
+ *     under parallel updates kept by GPU atomics; operations insert, get, accumulate.
+ *   - Algorithm 1: insert the working parameters, then for each mini-batch pull the
+ *     referenced parameters, train, push the updates back; after the batch the host
+ *     tier collects the table's content.
+ *   - Section 3 "Workflow": the union of the parameters a batch references.
+ * This library is one GPU's local share of that (no inter-GPU partition/exchange).
+ *
+ * A pull (i) sorts the mini-batch's uint64 feature keys into ascending unique keys
+ * plus, per occurrence, the rank of its key, (ii) looks every unique key up in the
+ * table, inserting a deterministic initial row for keys not yet present, and
+ * (iii) sums the embedding rows of each bag (example x slot).  A push sums the
+ * upstream gradients of the pooled bags per unique key and takes one Adagrad step
+ * on every touched row, in place.
+ *
+ * Conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller (for example a
+ *     torch tensor's data_ptr()); the library never allocates or frees device
+ *     memory.  `storage` holds the table for its whole life, `workspace` holds the
+ *     context of the outstanding pull.  Both must be 256-byte aligned.
+ *   - Pointers named h_* are host memory.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
+ *     on it and return without waiting, except where stated.
+ *   - Return value: HPS_OK or a negative hps_status.  Errors that only the device
+ *     can see (table full, reserved key) are recorded in a sticky device-side
+ *     status word; the kernels of later calls do nothing while it is set, and it
+ *     is reported by hps_stats() and cleared by hps_clear_error().
+ *   - The key 0xFFFFFFFFFFFFFFFF marks an empty slot and is not a legal key.
+ *   - One pull may be outstanding per table; a new pull replaces it.
+ *   - Calls on one table must be issued on one stream at a time (or be ordered by
+ *     the caller); the table is not internally synchronised across streams.
+ */
+#ifndef HPS_H_
+#define HPS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hps_table hps_table; /* opaque host object, owned by the library */
+
+typedef enum {
+  HPS_OK = 0,
+  HPS_EINVAL = -1,    /* bad argument (null/misaligned pointer, size out of range) */
+  HPS_EFULL = -2,     /* more keys than the table's capacity                        */
+  HPS_ERESERVED = -3, /* the reserved key appeared in the input                     */
+  HPS_ESTATE = -4,    /* push without an outstanding pull, or similar misuse        */
+  HPS_EDEVICE = -5,   /* a HIP call failed / no usable GPU                          */
+  HPS_ENOMEM = -6     /* storage or workspace buffer too small                      */
+} hps_status;
+
+typedef enum {
+  /* G' = G + mean_j(g_j^2), one accumulator per row;  w_j -= lr * g_j / (sqrt(G') + eps) */
+  HPS_OPT_ADAGRAD_ROWWISE = 0,
+  /* G_j' = G_j + g_j^2, one accumulator per element;  w_j -= lr * g_j / (sqrt(G_j') + eps) */
+  HPS_OPT_ADAGRAD_ELEMENTWISE = 1
+} hps_opt_kind;
+
+typedef struct {
+  int32_t kind;       /* hps_opt_kind */
+  float lr;
+  float eps;
+  float init_acc;     /* accumulator value of a newly created row                  */
+  float init_range;   /* new weights are uniform on [-init_range, init_range)      */
+  uint64_t init_seed; /* new row = function of (key, init_seed) only               */
+} hps_optimizer;
+
+typedef struct {
+  uint64_t size;            /* keys currently stored                               */
+  uint64_t capacity;        /* maximum number of keys                              */
+  uint64_t n_slots;         /* slots of the open-addressing array (capacity / 0.7) */
+  uint64_t last_n_keys;     /* key occurrences of the last pull                    */
+  uint64_t last_n_unique;   /* unique keys of the last pull                        */
+  uint64_t last_n_inserted; /* keys the last pull (or insert) created              */
+  int32_t error;            /* sticky device status (0 or a negative hps_status)   */
+  int32_t pull_outstanding; /* 1 between a pull and its push                       */
+} hps_stats_t;
+
+/* Bytes of device memory the table needs (keys, rows, accumulators, status);
+ * 0 if the arguments are invalid.  Section 4.1: capacity is fixed at construction. */
+size_t hps_table_bytes(uint64_t capacity_keys, uint32_t dim, const hps_optimizer* opt);
+
+/* Bytes of device workspace for pulls of at most max_keys key occurrences in at
+ * most max_bags bags; 0 if the arguments are invalid. */
+size_t hps_workspace_bytes(uint64_t max_keys, uint64_t max_bags, uint32_t dim);
+
+/* Section 4.1 "Local GPU hash table": builds an empty table in caller memory.
+ *   capacity_keys  maximum number of keys ever stored (1 .. 2^32 * 0.69)
+ *   dim            floats per embedding row; a multiple of 4, at most 1024
+ *   d_storage      >= hps_table_bytes() bytes; d_workspace >= hps_workspace_bytes()
+ *   max_keys       largest n_keys a pull may pass (< 2^31); max_bags likewise
+ * Enqueues the clearing of the slot array on `stream`.  *out is set on success and
+ * must be released with hps_destroy (which frees host memory only).
+ * Errors: HPS_EINVAL, HPS_ENOMEM, HPS_EDEVICE. */
+hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
+                      const hps_optimizer* opt, void* d_storage, size_t storage_bytes,
+                      void* d_workspace, size_t workspace_bytes, uint64_t max_keys,
+                      uint64_t max_bags, void* stream);
+
+/* Section 4.1 "insert" / Algorithm 1 insert_into_hashtable: bulk load of n keys.
+ *   d_weights [n, dim] or NULL, d_acc [n, acc_len] or NULL (acc_len = 1 row-wise,
+ *   dim element-wise).
+ * d_weights == NULL: an absent key gets its deterministic initial row, a present
+ * key is left untouched.  d_weights != NULL: the row is created or overwritten
+ * (accumulators from d_acc, or init_acc when d_acc is NULL); keys must then be
+ * distinct within the call.  n may exceed max_keys.  Device errors: HPS_EFULL,
+ * HPS_ERESERVED (sticky). */
+hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_weights,
+                      const float* d_acc, void* stream);
+
+/* Algorithm 1 pull_HBM-PS_kernel.
+ *   d_keys    [n_keys] feature keys of the mini-batch, bag after bag
+ *   d_offsets [n_examples * n_slots + 1] int32, CSR over the bags in (example, slot)
+ *             row-major order: offsets[0] = 0, non-decreasing, last = n_keys
+ *   d_pooled  [n_examples * n_slots, dim] float32 out: sum of the rows of each bag
+ *             (an empty bag gives zeros; a key repeated in a bag counts each time)
+ * Keys not in the table are inserted with their initial row before pooling.
+ * n_keys <= max_keys and n_examples * n_slots <= max_bags, else HPS_EINVAL.
+ * All buffers must stay valid until the work enqueued here has run; d_keys and
+ * d_offsets are not needed by the later push. */
+hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                    const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
+                    float* d_pooled, void* stream);
+
+/* Algorithm 1 push_parameters_updates_back_kernel / Algorithm 2's local accumulate.
+ *   d_pooled_grads [n_bags, dim]: gradient of the loss w.r.t. d_pooled of the
+ *   outstanding pull.
+ * Each unique key's gradient is the sum over its occurrences of its bag's
+ * gradient row; each touched row takes one optimizer step.  Ends the pull.
+ * Errors: HPS_ESTATE when no pull is outstanding. */
+hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream);
+
+/* Section 3 "union of the referenced parameters": copies the outstanding pull's
+ * ascending unique keys (d_uniq_out, room for n_keys) and per-occurrence ranks
+ * (d_inverse_out [n_keys] int32, uniq[inverse[i]] == keys[i]); either may be NULL.
+ * The unique count is hps_stats().last_n_unique. */
+hps_status hps_last_unique(hps_table* t, uint64_t* d_uniq_out, int32_t* d_inverse_out,
+                           void* stream);
+
+/* Section 4.1 "get": reads rows by key without inserting.
+ *   d_weights_out [n, dim], d_acc_out [n, acc_len], d_found_out [n] uint8;
+ *   rows of absent keys are left unwritten, found = 0. */
+hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_weights_out,
+                   float* d_acc_out, uint8_t* d_found_out, void* stream);
+
+/* Algorithm 1 pull_updates_HBM-PS: writes every stored (key, row, accumulator) in
+ * unspecified order, at most max_rows of them; *h_n_rows (host) gets the number of
+ * stored keys.  Waits for the stream.  HPS_ENOMEM if max_rows was too small (the
+ * first max_rows found are written). */
+hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, float* d_acc_out,
+                    uint64_t max_rows, uint64_t* h_n_rows, void* stream);
+
+/* Waits for the stream and fills *h_out (host). */
+hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
+
+/* Clears the sticky device status. */
+hps_status hps_clear_error(hps_table* t, void* stream);
+
+/* Frees the host object; device memory stays with the caller. */
+hps_status hps_destroy(hps_table* t);
+
+const char* hps_strerror(hps_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPS_H_ */

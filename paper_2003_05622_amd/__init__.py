@@ -1,0 +1,17 @@
+"""HBM-resident parameter server pull/push for one MI355X: Python binding of libhps.so.
+
+The binding marshals arguments only; every step of the path runs in the HIP
+kernels behind the C ABI (include/hps.h).  torch supplies device memory and the
+current stream.
+"""
+from .binding import (  # noqa: F401
+    HpsError,
+    HpsTable,
+    Optimizer,
+    Stats,
+    lib,
+    ADAGRAD_ROWWISE,
+    ADAGRAD_ELEMENTWISE,
+    OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM,
+    EXPORTS,
+)

@@ -1,0 +1,199 @@
+"""ctypes binding of the C ABI in include/hps.h (same names, argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+from .build import ensure_built
+
+OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM = 0, -1, -2, -3, -4, -5, -6
+ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
+
+EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
+           "hps_push", "hps_last_unique", "hps_get", "hps_dump", "hps_stats", "hps_clear_error",
+           "hps_destroy", "hps_strerror")
+
+
+class Optimizer(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("lr", ctypes.c_float), ("eps", ctypes.c_float),
+                ("init_acc", ctypes.c_float), ("init_range", ctypes.c_float),
+                ("init_seed", ctypes.c_uint64)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_uint64), ("capacity", ctypes.c_uint64),
+                ("n_slots", ctypes.c_uint64), ("last_n_keys", ctypes.c_uint64),
+                ("last_n_unique", ctypes.c_uint64), ("last_n_inserted", ctypes.c_uint64),
+                ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded libhps.so with argument types set.  Raises if it cannot be loaded."""
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(ensure_built())
+        u64, u32, vp, sz = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_size_t
+        st = ctypes.c_int
+        L.hps_table_bytes.restype = sz
+        L.hps_table_bytes.argtypes = [u64, u32, ctypes.POINTER(Optimizer)]
+        L.hps_workspace_bytes.restype = sz
+        L.hps_workspace_bytes.argtypes = [u64, u64, u32]
+        L.hps_create.restype = st
+        L.hps_create.argtypes = [ctypes.POINTER(vp), u64, u32, ctypes.POINTER(Optimizer), vp, sz,
+                                 vp, sz, u64, u64, vp]
+        L.hps_insert.restype = st
+        L.hps_insert.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.hps_pull.restype = st
+        L.hps_pull.argtypes = [vp, vp, u64, vp, u32, u32, vp, vp]
+        L.hps_push.restype = st
+        L.hps_push.argtypes = [vp, vp, vp]
+        L.hps_last_unique.restype = st
+        L.hps_last_unique.argtypes = [vp, vp, vp, vp]
+        L.hps_get.restype = st
+        L.hps_get.argtypes = [vp, vp, u64, vp, vp, vp, vp]
+        L.hps_dump.restype = st
+        L.hps_dump.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64), vp]
+        L.hps_stats.restype = st
+        L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
+        L.hps_clear_error.restype = st
+        L.hps_clear_error.argtypes = [vp, vp]
+        L.hps_destroy.restype = st
+        L.hps_destroy.argtypes = [vp]
+        L.hps_strerror.restype = ctypes.c_char_p
+        L.hps_strerror.argtypes = [st]
+        _lib = L
+    return _lib
+
+
+class HpsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        msg = lib().hps_strerror(status).decode()
+        super().__init__("%s: %s (%d)" % (what, msg, status))
+        self.status = status
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise HpsError(status, what)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class HpsTable:
+    """One table in HBM.  Tensors are torch CUDA tensors; keys travel as int64
+    tensors holding the uint64 bit patterns."""
+
+    def __init__(self, capacity: int, dim: int, max_keys: int, max_bags: int, *,
+                 opt: int = ADAGRAD_ROWWISE, lr: float = 0.05, eps: float = 1e-8,
+                 init_acc: float = 0.1, init_range: float = 0.01, init_seed: int = 0,
+                 device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("paper_2003_05622_amd needs a GPU: there is no CPU path")
+        self._h = None
+        L = lib()
+        self.capacity, self.dim, self.max_keys, self.max_bags = capacity, dim, max_keys, max_bags
+        self.acc_len = dim if opt == ADAGRAD_ELEMENTWISE else 1
+        self.device = torch.device(device)
+        self.opt = Optimizer(opt, lr, eps, init_acc, init_range, init_seed)
+        sb = L.hps_table_bytes(capacity, dim, ctypes.byref(self.opt))
+        wb = L.hps_workspace_bytes(max_keys, max_bags, dim)
+        if sb == 0 or wb == 0:
+            raise HpsError(EINVAL, "hps_table_bytes/hps_workspace_bytes")
+        with torch.cuda.device(self.device):
+            self.storage = torch.empty(sb, dtype=torch.uint8, device=self.device)
+            self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
+            h = ctypes.c_void_p()
+            _check(L.hps_create(ctypes.byref(h), capacity, dim, ctypes.byref(self.opt),
+                                self.storage.data_ptr(), sb, self.workspace.data_ptr(), wb,
+                                max_keys, max_bags, _stream()), "hps_create")
+        self._h = h
+        self._last_n = 0
+
+    def close(self) -> None:
+        if self._h:
+            lib().hps_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the C ABI, one method per entry point ---------------------------------------
+    def insert(self, keys, weights=None, acc=None) -> None:
+        _check(lib().hps_insert(self._h, _ptr(keys), keys.numel(), _ptr(weights), _ptr(acc),
+                                _stream()), "hps_insert")
+
+    def pull(self, keys, offsets, n_examples: int, n_slots: int, pooled=None):
+        import torch
+        n_bags = n_examples * n_slots
+        assert offsets.numel() == n_bags + 1
+        if pooled is None:
+            pooled = torch.empty((n_bags, self.dim), dtype=torch.float32, device=self.device)
+        _check(lib().hps_pull(self._h, _ptr(keys), keys.numel(), _ptr(offsets), n_examples,
+                              n_slots, _ptr(pooled), _stream()), "hps_pull")
+        self._last_n = keys.numel()
+        return pooled
+
+    def push(self, pooled_grads) -> None:
+        _check(lib().hps_push(self._h, _ptr(pooled_grads), _stream()), "hps_push")
+
+    def last_unique(self) -> Tuple["torch.Tensor", "torch.Tensor"]:
+        import torch
+        n = self._last_n
+        uniq = torch.empty(max(n, 1), dtype=torch.int64, device=self.device)
+        inv = torch.empty(max(n, 1), dtype=torch.int32, device=self.device)
+        _check(lib().hps_last_unique(self._h, _ptr(uniq), _ptr(inv), _stream()),
+               "hps_last_unique")
+        u = self.stats().last_n_unique
+        return uniq[:u], inv[:n]
+
+    def get(self, keys):
+        import torch
+        n = keys.numel()
+        w = torch.zeros((n, self.dim), dtype=torch.float32, device=self.device)
+        a = torch.zeros((n, self.acc_len), dtype=torch.float32, device=self.device)
+        f = torch.zeros(n, dtype=torch.uint8, device=self.device)
+        _check(lib().hps_get(self._h, _ptr(keys), n, _ptr(w), _ptr(a), _ptr(f), _stream()),
+               "hps_get")
+        return w, a, f.bool()
+
+    def dump(self, max_rows: Optional[int] = None):
+        import torch
+        if max_rows is None:
+            max_rows = self.stats().size
+        keys = torch.empty(max(max_rows, 1), dtype=torch.int64, device=self.device)
+        w = torch.empty((max(max_rows, 1), self.dim), dtype=torch.float32, device=self.device)
+        a = torch.empty((max(max_rows, 1), self.acc_len), dtype=torch.float32, device=self.device)
+        n = ctypes.c_uint64(0)
+        _check(lib().hps_dump(self._h, _ptr(keys), _ptr(w), _ptr(a), max_rows, ctypes.byref(n),
+                              _stream()), "hps_dump")
+        r = int(n.value)
+        return keys[:r], w[:r], a[:r]
+
+    def stats(self) -> Stats:
+        s = Stats()
+        _check(lib().hps_stats(self._h, ctypes.byref(s), _stream()), "hps_stats")
+        return s
+
+    def clear_error(self) -> None:
+        _check(lib().hps_clear_error(self._h, _stream()), "hps_clear_error")
+
+    def check(self, what: str = "device status") -> None:
+        """Raises if the sticky device status is set."""
+        e = self.stats().error
+        if e != 0:
+            raise HpsError(e, what)

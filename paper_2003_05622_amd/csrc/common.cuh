@@ -1,0 +1,117 @@
+// Shared device-side definitions of the HBM-PS pull/push kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hps {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef int32_t i32;
+
+constexpr u64 kEmptyKey = ~u64(0);   // marks a free slot; never a legal key
+constexpr u32 kNoRow = ~u32(0);      // "this key has no row" (lookup miss / table full)
+constexpr int kWave = 64;
+constexpr int kSlotsPerLine = 8;     // 8 keys of 8 bytes = one 64-byte line, probed by 8 lanes
+
+// Device-side status values mirror hps_status.
+constexpr int kErrFull = -2;
+constexpr int kErrReserved = -3;
+
+// Lives in the table's storage for the table's whole life.
+struct TableState {
+  unsigned long long size;      // keys stored
+  unsigned long long inserted;  // keys created by the last pull / insert call
+  int error;                    // sticky: 0 or a negative status
+  int pad;
+  unsigned long long dump_count;  // rows seen by the running dump
+};
+
+// Lives in the workspace; describes the outstanding pull.
+struct PullCtx {
+  u32 n_unique;        // U
+  u32 n_long;          // long segments found by the push
+  u32 n_chunk_items;   // (segment, chunk) work items of the push
+  u32 pad;
+};
+
+// SplitMix64 output function for state x (Steele, Lea, Flood 2014).  The row
+// initialiser is defined on top of it.
+__device__ __forceinline__ u64 mix64(u64 x) {
+  u64 z = x + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// Slot hash: the 64-bit finaliser of MurmurHash3 (Appleby), so that the table
+// does not rely on keys arriving well mixed.
+__device__ __forceinline__ u64 slot_hash(u64 k) {
+  k ^= k >> 33;
+  k *= 0xFF51AFD7ED558CCDull;
+  k ^= k >> 33;
+  k *= 0xC4CEB9FE1A85EC53ull;
+  k ^= k >> 33;
+  return k;
+}
+
+// Element j of key's initial row: uniform on [-a, a) from 24 random bits, as a
+// rounded product followed by a rounded difference (never fused).
+__device__ __forceinline__ float init_weight(u64 base, u32 j, float a) {
+  const u64 r = mix64(base + j);
+  const float u = __fmul_rn((float)(u32)(r >> 40), 0x1.0p-24f);
+  return __fsub_rn(__fmul_rn(u, __fmul_rn(a, 2.0f)), a);
+}
+
+__device__ __forceinline__ u32 lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ u64 lanemask_lt() {
+  const u32 l = lane_id();
+  return l == 0 ? 0ull : (~0ull >> (64 - l));
+}
+
+// Inclusive sum over the 64 lanes of a wave.
+__device__ __forceinline__ u32 wave_incl_sum(u32 v) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const u32 o = __shfl_up(v, d, kWave);
+    if ((int)lane_id() >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive sum over a block of THREADS threads (multiple of 64, at most 1024).
+// `scratch` needs THREADS/64 + 1 words of LDS.  Returns the exclusive prefix of v
+// and the block total in *total.  Contains __syncthreads().
+template <int THREADS>
+__device__ __forceinline__ u32 block_excl_sum(u32 v, u32* scratch, u32* total) {
+  constexpr int NW = THREADS / kWave;
+  const u32 incl = wave_incl_sum(v);
+  const u32 w = threadIdx.x / kWave;
+  __syncthreads();   // scratch may still be in use by a previous call
+  if (lane_id() == kWave - 1) scratch[w] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    u32 run = 0;
+    for (int i = 0; i < NW; ++i) {
+      const u32 c = scratch[i];
+      scratch[i] = run;
+      run += c;
+    }
+    scratch[NW] = run;
+  }
+  __syncthreads();
+  *total = scratch[NW];
+  return scratch[w] + incl - v;
+}
+
+__device__ __forceinline__ int load_error(const TableState* st) {
+  return __hip_atomic_load(&st->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void raise_error(TableState* st, int code) {
+  atomicCAS(&st->error, 0, code);
+}
+
+}  // namespace hps

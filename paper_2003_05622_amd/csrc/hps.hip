@@ -1,0 +1,421 @@
+// Host side of the C ABI declared in include/hps.h: argument checks, carving of
+// the caller's storage and workspace, and the kernel launch sequences of
+// insert / pull / push / get / dump.  No device memory is allocated here.
+
+#include "../../include/hps.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.cuh"
+#include "dedup.cuh"
+#include "pool.cuh"
+#include "push.cuh"
+#include "sort.cuh"
+#include "table.cuh"
+
+using namespace hps;
+
+namespace {
+
+constexpr double kLoadFactor = 0.7;
+constexpr size_t kAlign = 256;
+constexpr uint64_t kMaxSlots = 0xFFFFFFF0ull;   // row indices are 32-bit, kNoRow is reserved
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+uint64_t slots_for(uint64_t capacity) {
+  uint64_t s = (uint64_t)((double)capacity / kLoadFactor) + 1;
+  if (s < capacity + kSlotsPerLine) s = capacity + kSlotsPerLine;
+  return (s + kSlotsPerLine - 1) / kSlotsPerLine * kSlotsPerLine;
+}
+
+bool valid_opt(const hps_optimizer* o) {
+  return o && (o->kind == HPS_OPT_ADAGRAD_ROWWISE || o->kind == HPS_OPT_ADAGRAD_ELEMENTWISE) &&
+         o->init_range >= 0.f && o->eps >= 0.f;
+}
+
+bool valid_shape(uint64_t capacity, uint32_t dim) {
+  return capacity >= 1 && dim >= 4 && dim <= 1024 && dim % 4 == 0 &&
+         slots_for(capacity) <= kMaxSlots;
+}
+
+struct StorageLayout {
+  size_t keys, w, acc, state, total;
+};
+
+StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
+  StorageLayout L;
+  size_t o = 0;
+  L.keys = o;  o = align_up(o + n_slots * sizeof(uint64_t));
+  L.w = o;     o = align_up(o + n_slots * (size_t)dim * sizeof(float));
+  L.acc = o;   o = align_up(o + n_slots * (size_t)acc_len * sizeof(float));
+  L.state = o; o = align_up(o + sizeof(TableState));
+  L.total = o;
+  return L;
+}
+
+struct WorkspaceLayout {
+  size_t ctx, pairs_a, pairs_b, hist, skeys, tile_heads, uniq, rows, inverse, perm, seg_off,
+      bag_of, long_list, chunk_items, partials, total;
+  uint64_t max_long, max_items;
+};
+
+WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
+  (void)bags;
+  WorkspaceLayout L;
+  const uint64_t n1 = n ? n : 1;
+  const uint64_t sort_tiles = (n1 + kSortTile - 1) / kSortTile;
+  const uint64_t head_tiles = (n1 + kHeadTile - 1) / kHeadTile;
+  L.max_long = n1 / kLongSeg + 1;
+  L.max_items = n1 / kChunk + L.max_long + 1;
+  size_t o = 0;
+  L.ctx = o;         o = align_up(o + sizeof(PullCtx));
+  L.pairs_a = o;     o = align_up(o + n1 * 8);
+  L.pairs_b = o;     o = align_up(o + n1 * 8);
+  L.hist = o;        o = align_up(o + sort_tiles * kRadix * 4);
+  L.skeys = o;       o = align_up(o + n1 * 8);
+  L.tile_heads = o;  o = align_up(o + head_tiles * 4);
+  L.uniq = o;        o = align_up(o + n1 * 8);
+  L.rows = o;        o = align_up(o + n1 * 4);
+  L.inverse = o;     o = align_up(o + n1 * 4);
+  L.perm = o;        o = align_up(o + n1 * 4);
+  L.seg_off = o;     o = align_up(o + (n1 + 1) * 4);
+  L.bag_of = o;      o = align_up(o + n1 * 4);
+  L.long_list = o;   o = align_up(o + L.max_long * 8);
+  L.chunk_items = o; o = align_up(o + L.max_items * 8);
+  L.partials = o;    o = align_up(o + L.max_items * (size_t)dim * 4);
+  L.total = o;
+  return L;
+}
+
+int lanes_per_row(uint32_t dim) {
+  int l = 1;
+  while (l < 64 && (uint32_t)l * 4 < dim) l <<= 1;
+  return l;
+}
+
+bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+}  // namespace
+
+struct hps_table {
+  uint64_t capacity, n_slots, max_keys, max_bags;
+  uint32_t dim, acc_len;
+  hps_optimizer opt;
+  TableView view;
+  char* ws;
+  WorkspaceLayout wl;
+  int lpr;
+  bool pulled;
+  uint64_t last_n_keys, last_n_bags;
+
+  template <typename T> T* w(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+template <int LPR>
+static void launch_pool(hps_table* t, const int32_t* d_offsets, uint32_t n_bags, float* d_pooled,
+                        hipStream_t s) {
+  const unsigned blocks = (unsigned)(((uint64_t)n_bags * LPR + kPoolThreads - 1) / kPoolThreads);
+  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, d_offsets, n_bags,
+                                                 t->w<i32>(t->wl.inverse), t->w<u32>(t->wl.rows),
+                                                 d_pooled, t->w<i32>(t->wl.bag_of));
+}
+
+template <int LPR>
+static void launch_push(hps_table* t, const PushArgs& a, hipStream_t s) {
+  const uint64_t n = t->last_n_keys;
+  const unsigned seg_blocks = (unsigned)((n * LPR + kPushThreads - 1) / kPushThreads);
+  const unsigned max_long = (unsigned)(n / kLongSeg + 1);
+  const unsigned max_items = (unsigned)(n / kChunk + max_long + 1);
+  push_segments<LPR><<<seg_blocks, kPushThreads, 0, s>>>(t->view, a);
+  push_chunks<LPR><<<max_items, kPushThreads, 0, s>>>(t->view, a);
+  push_long<LPR><<<max_long, kPushThreads, 0, s>>>(t->view, a);
+}
+
+#define HPS_DISPATCH_LPR(lpr, CALL)            \
+  switch (lpr) {                               \
+    case 1: CALL(1); break;                    \
+    case 2: CALL(2); break;                    \
+    case 4: CALL(4); break;                    \
+    case 8: CALL(8); break;                    \
+    case 16: CALL(16); break;                  \
+    case 32: CALL(32); break;                  \
+    default: CALL(64); break;                  \
+  }
+
+extern "C" {
+
+const char* hps_strerror(hps_status s) {
+  switch (s) {
+    case HPS_OK: return "ok";
+    case HPS_EINVAL: return "invalid argument";
+    case HPS_EFULL: return "table full";
+    case HPS_ERESERVED: return "reserved key 0xFFFFFFFFFFFFFFFF in input";
+    case HPS_ESTATE: return "call not valid in this state";
+    case HPS_EDEVICE: return "HIP call failed or no usable GPU";
+    case HPS_ENOMEM: return "buffer too small";
+  }
+  return "unknown status";
+}
+
+size_t hps_table_bytes(uint64_t capacity_keys, uint32_t dim, const hps_optimizer* opt) {
+  if (!valid_opt(opt) || !valid_shape(capacity_keys, dim)) return 0;
+  const uint32_t acc_len = opt->kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? dim : 1;
+  return storage_layout(slots_for(capacity_keys), dim, acc_len).total;
+}
+
+size_t hps_workspace_bytes(uint64_t max_keys, uint64_t max_bags, uint32_t dim) {
+  if (max_keys >= (1ull << 31) || max_bags >= (1ull << 31) || dim < 4 || dim > 1024 || dim % 4)
+    return 0;
+  return workspace_layout(max_keys, max_bags, dim).total;
+}
+
+hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
+                      const hps_optimizer* opt, void* d_storage, size_t storage_bytes,
+                      void* d_workspace, size_t workspace_bytes, uint64_t max_keys,
+                      uint64_t max_bags, void* stream) {
+  if (!out) return HPS_EINVAL;
+  *out = nullptr;
+  if (!valid_opt(opt) || !valid_shape(capacity_keys, dim)) return HPS_EINVAL;
+  if (!d_storage || !d_workspace) return HPS_EINVAL;
+  if ((uintptr_t)d_storage % kAlign || (uintptr_t)d_workspace % kAlign) return HPS_EINVAL;
+  if (max_keys >= (1ull << 31) || max_bags >= (1ull << 31)) return HPS_EINVAL;
+  const uint32_t acc_len = opt->kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? dim : 1;
+  const uint64_t n_slots = slots_for(capacity_keys);
+  const StorageLayout sl = storage_layout(n_slots, dim, acc_len);
+  const WorkspaceLayout wl = workspace_layout(max_keys, max_bags, dim);
+  if (storage_bytes < sl.total || workspace_bytes < wl.total) return HPS_ENOMEM;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return HPS_EDEVICE; }
+
+  hps_table* t = new (std::nothrow) hps_table();
+  if (!t) return HPS_ENOMEM;
+  t->capacity = capacity_keys;
+  t->n_slots = n_slots;
+  t->max_keys = max_keys;
+  t->max_bags = max_bags;
+  t->dim = dim;
+  t->acc_len = acc_len;
+  t->opt = *opt;
+  char* base = static_cast<char*>(d_storage);
+  t->view.keys = reinterpret_cast<u64*>(base + sl.keys);
+  t->view.w = reinterpret_cast<float*>(base + sl.w);
+  t->view.acc = reinterpret_cast<float*>(base + sl.acc);
+  t->view.st = reinterpret_cast<TableState*>(base + sl.state);
+  t->view.n_lines = n_slots / kSlotsPerLine;
+  t->view.capacity = capacity_keys;
+  t->view.dim = dim;
+  t->view.acc_len = acc_len;
+  t->view.init_acc = opt->init_acc;
+  t->view.init_range = opt->init_range;
+  t->view.init_seed = opt->init_seed;
+  t->ws = static_cast<char*>(d_workspace);
+  t->wl = wl;
+  t->lpr = lanes_per_row(dim);
+  t->pulled = false;
+  t->last_n_keys = t->last_n_bags = 0;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
+  reset_state<<<1, 1, 0, s>>>(t->view.st);
+  set_ctx_empty<<<1, 1, 0, s>>>(t->w<PullCtx>(wl.ctx), t->w<u32>(wl.seg_off));
+  if (!launch_ok()) { delete t; return HPS_EDEVICE; }
+  *out = t;
+  return HPS_OK;
+}
+
+hps_status hps_destroy(hps_table* t) {
+  if (!t) return HPS_EINVAL;
+  delete t;
+  return HPS_OK;
+}
+
+hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_weights,
+                      const float* d_acc, void* stream) {
+  if (!t || (n && !d_keys) || (d_acc && !d_weights)) return HPS_EINVAL;
+  if (n >= (1ull << 31) * kProbeKeysPerBlock) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  clear_inserted<<<1, 1, 0, s>>>(t->view.st);
+  if (n) {
+    const unsigned blocks = (unsigned)((n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock);
+    if (d_weights)
+      probe_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr,
+                                                     d_weights, d_acc, nullptr, nullptr, nullptr);
+    else
+      probe_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr,
+                                                     nullptr, nullptr, nullptr, nullptr, nullptr);
+  }
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                    const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
+                    float* d_pooled, void* stream) {
+  if (!t || !d_offsets || (n_keys && !d_keys)) return HPS_EINVAL;
+  const uint64_t n_bags = (uint64_t)n_examples * n_slots;
+  if (n_keys > t->max_keys || n_bags > t->max_bags) return HPS_EINVAL;
+  if (n_bags && !d_pooled) return HPS_EINVAL;
+  if ((uintptr_t)d_keys % 8 || (uintptr_t)d_offsets % 4 || (uintptr_t)d_pooled % 16)
+    return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const WorkspaceLayout& L = t->wl;
+  PullCtx* ctx = t->w<PullCtx>(L.ctx);
+  const u32 n = (u32)n_keys;
+
+  if (n == 0) {
+    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(L.seg_off));
+    clear_inserted<<<1, 1, 0, s>>>(t->view.st);
+  } else {
+    // a1: order the occurrences by key (two 32-bit halves, 8-bit digits, low half first)
+    u64* cur = t->w<u64>(L.pairs_a);
+    u64* alt = t->w<u64>(L.pairs_b);
+    u32* hist = t->w<u32>(L.hist);
+    const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
+    const unsigned flat_blocks = (n + 255) / 256;
+    for (int half = 0; half < 2; ++half) {
+      if (half == 0)
+        pairs_from_keys<<<flat_blocks, 256, 0, s>>>(d_keys, n, 0, cur);
+      else
+        pairs_regather<<<flat_blocks, 256, 0, s>>>(d_keys, n, 32, cur);
+      for (int shift = 0; shift < 32; shift += kRadixBits) {
+        radix_hist<<<n_tiles, kSortThreads, 0, s>>>(cur, n, shift, hist, n_tiles);
+        scan_counters<<<1, 1024, 0, s>>>(hist, n_tiles * kRadix);
+        radix_scatter<<<n_tiles, kSortThreads, 0, s>>>(cur, alt, n, shift, hist, n_tiles);
+        u64* tmp = cur; cur = alt; alt = tmp;
+      }
+    }
+    // a1: unique keys, ranks, grouping
+    const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
+    u32* tile_heads = t->w<u32>(L.tile_heads);
+    heads_count<<<head_tiles, kHeadThreads, 0, s>>>(cur, d_keys, n, t->w<u64>(L.skeys), tile_heads);
+    heads_scan<<<1, 1024, 0, s>>>(tile_heads, head_tiles, n, ctx, t->w<u32>(L.seg_off));
+    clear_inserted<<<1, 1, 0, s>>>(t->view.st);
+    heads_emit<<<head_tiles, kHeadThreads, 0, s>>>(cur, t->w<u64>(L.skeys), n, tile_heads,
+                                                   t->w<u64>(L.uniq), t->w<i32>(L.inverse),
+                                                   t->w<u32>(L.perm), t->w<u32>(L.seg_off),
+                                                   t->view.st);
+    // a2: look up or insert every unique key
+    const unsigned probe_blocks = (n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock;
+    probe_keys<1><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
+                                                         &ctx->n_unique, t->w<u32>(L.rows), nullptr,
+                                                         nullptr, nullptr, nullptr, nullptr);
+  }
+  // a3: gather rows and pool per bag
+  if (n_bags) {
+#define CALL(LPR) launch_pool<LPR>(t, d_offsets, (uint32_t)n_bags, d_pooled, s)
+    HPS_DISPATCH_LPR(t->lpr, CALL)
+#undef CALL
+  }
+  if (!launch_ok()) return HPS_EDEVICE;
+  t->pulled = true;
+  t->last_n_keys = n_keys;
+  t->last_n_bags = n_bags;
+  return HPS_OK;
+}
+
+hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
+  if (!t) return HPS_EINVAL;
+  if (!t->pulled) return HPS_ESTATE;
+  if (t->last_n_bags && !d_pooled_grads) return HPS_EINVAL;
+  if ((uintptr_t)d_pooled_grads % 16) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  t->pulled = false;
+  if (t->last_n_keys == 0) return HPS_OK;
+  const WorkspaceLayout& L = t->wl;
+  PushArgs a;
+  a.seg_off = t->w<u32>(L.seg_off);
+  a.perm = t->w<u32>(L.perm);
+  a.bag_of = t->w<i32>(L.bag_of);
+  a.rows = t->w<u32>(L.rows);
+  a.grads = d_pooled_grads;
+  a.ctx = t->w<PullCtx>(L.ctx);
+  a.long_list = t->w<uint2>(L.long_list);
+  a.chunk_items = t->w<uint2>(L.chunk_items);
+  a.partials = t->w<float>(L.partials);
+  a.lr = t->opt.lr;
+  a.eps = t->opt.eps;
+  a.elementwise = t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE;
+#define CALL(LPR) launch_push<LPR>(t, a, s)
+  HPS_DISPATCH_LPR(t->lpr, CALL)
+#undef CALL
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+hps_status hps_last_unique(hps_table* t, uint64_t* d_uniq_out, int32_t* d_inverse_out,
+                           void* stream) {
+  if (!t) return HPS_EINVAL;
+  if (!t->pulled) return HPS_ESTATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint64_t n = t->last_n_keys;
+  if (n == 0) return HPS_OK;
+  // U <= n is only known on the device: copy n entries, the caller reads the first U.
+  if (d_uniq_out &&
+      hipMemcpyAsync(d_uniq_out, t->w<u64>(t->wl.uniq), n * 8, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return HPS_EDEVICE;
+  if (d_inverse_out &&
+      hipMemcpyAsync(d_inverse_out, t->w<i32>(t->wl.inverse), n * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+    return HPS_EDEVICE;
+  return HPS_OK;
+}
+
+hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_weights_out,
+                   float* d_acc_out, uint8_t* d_found_out, void* stream) {
+  if (!t || (n && (!d_keys || !d_weights_out || !d_acc_out || !d_found_out))) return HPS_EINVAL;
+  if (n >= (1ull << 31) * kProbeKeysPerBlock) return HPS_EINVAL;
+  if (n == 0) return HPS_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned blocks = (unsigned)((n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock);
+  probe_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
+                                                 nullptr, d_weights_out, d_acc_out, d_found_out);
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, float* d_acc_out,
+                    uint64_t max_rows, uint64_t* h_n_rows, void* stream) {
+  if (!t || !h_n_rows) return HPS_EINVAL;
+  if (max_rows && (!d_keys_out || !d_weights_out || !d_acc_out)) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  clear_dump_count<<<1, 1, 0, s>>>(t->view.st);
+  dump_rows<<<4096, 256, 0, s>>>(t->view, d_keys_out, d_weights_out, d_acc_out, max_rows,
+                                 &t->view.st->dump_count);
+  if (!launch_ok()) return HPS_EDEVICE;
+  unsigned long long count = 0;
+  if (hipMemcpyAsync(&count, &t->view.st->dump_count, sizeof(count), hipMemcpyDeviceToHost, s) != hipSuccess)
+    return HPS_EDEVICE;
+  if (hipStreamSynchronize(s) != hipSuccess) return HPS_EDEVICE;
+  *h_n_rows = count;
+  return count > max_rows ? HPS_ENOMEM : HPS_OK;
+}
+
+hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
+  if (!t || !h_out) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  TableState st;
+  PullCtx ctx;
+  if (hipMemcpyAsync(&st, t->view.st, sizeof(st), hipMemcpyDeviceToHost, s) != hipSuccess)
+    return HPS_EDEVICE;
+  if (hipMemcpyAsync(&ctx, t->w<PullCtx>(t->wl.ctx), sizeof(ctx), hipMemcpyDeviceToHost, s) != hipSuccess)
+    return HPS_EDEVICE;
+  if (hipStreamSynchronize(s) != hipSuccess) return HPS_EDEVICE;
+  h_out->size = st.size;
+  h_out->capacity = t->capacity;
+  h_out->n_slots = t->n_slots;
+  h_out->last_n_keys = t->last_n_keys;
+  h_out->last_n_unique = ctx.n_unique;
+  h_out->last_n_inserted = st.inserted;
+  h_out->error = st.error;
+  h_out->pull_outstanding = t->pulled ? 1 : 0;
+  return HPS_OK;
+}
+
+hps_status hps_clear_error(hps_table* t, void* stream) {
+  if (!t) return HPS_EINVAL;
+  clear_error<<<1, 1, 0, static_cast<hipStream_t>(stream)>>>(t->view.st);
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer results (unique keys, inverse indices, key sets, sizes,
+rows that were only initialised) are bit-exact; float32 results (pooled sums,
+updated weights and accumulators) within |gpu - oracle| <= 1e-6 + 1e-5 * |oracle|."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2003_05622_amd as hps
+import synth
+from oracle import OracleTable
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 1e-6, 1e-5
+
+
+def dev_keys(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).cuda()
+
+
+def host_keys(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def assert_close(got, want, what):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, what
+    err = np.abs(got - want) - (ATOL + RTOL * np.abs(want))
+    assert err.max(initial=-1.0) <= 0, "%s: worst excess %g at %s" % (
+        what, err.max(), np.unravel_index(err.argmax(), err.shape))
+
+
+def compare_tables(gt, ot, what):
+    k, w, a = gt.dump()
+    k, w, a = host_keys(k), w.cpu().numpy(), a.cpu().numpy()
+    order = np.argsort(k, kind="stable")
+    k, w, a = k[order], w[order], a[order]
+    ok, ow, oa = ot.dump()
+    assert np.array_equal(k, ok), what + ": key sets differ"
+    assert_close(w, ow, what + " weights")
+    assert_close(a, oa, what + " accumulators")
+    untouched = (oa == np.float32(ot_init_acc(ot))).all(axis=1)
+    assert np.array_equal(w[untouched].view(np.uint32), ow[untouched].view(np.uint32)), \
+        what + ": rows that were only initialised must be bit-identical"
+    assert gt.stats().size == ot.size
+
+
+def ot_init_acc(ot):
+    return ot._init_acc
+
+
+def make_pair(cfg, max_keys, opt=hps.ADAGRAD_ROWWISE):
+    kw = dict(lr=cfg.lr, eps=cfg.eps, init_acc=cfg.init_acc, init_range=cfg.init_range,
+              init_seed=cfg.init_seed)
+    gt = hps.HpsTable(cfg.capacity, cfg.dim, max_keys, cfg.n_bags, opt=opt, **kw)
+    ot = OracleTable(cfg.capacity, cfg.dim, opt=opt, **kw)
+    ot._init_acc = cfg.init_acc
+    return gt, ot
+
+
+def run_steps(cfg, steps, opt=hps.ADAGRAD_ROWWISE, check_every=1):
+    stream = synth.BatchStream(cfg)
+    mean_bag = cfg.bag_mean if cfg.bag_kind == "poisson" else cfg.bag_hi
+    max_keys = int(cfg.n_bags * mean_bag * 1.5) + 4096
+    gt, ot = make_pair(cfg, max_keys, opt)
+    pre = synth.prefill_keys(0, cfg.n_prefill)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+    for step in range(steps):
+        b = stream.next()
+        print("step", step, "N", b.n_keys, flush=True)
+        dk, do = dev_keys(b.keys), torch.from_numpy(b.offsets).cuda()
+        pooled = gt.pull(dk, do, cfg.n_examples, cfg.n_slots)
+        want = ot.pull(b.keys, b.offsets)
+        if step % check_every == 0:
+            uniq, inv = gt.last_unique()
+            ou, oi = ot.last_unique()
+            st = gt.stats()
+            assert st.error == 0
+            assert st.last_n_unique == ot.n_unique and st.last_n_inserted == ot.n_inserted
+            assert np.array_equal(host_keys(uniq), ou), "unique keys"
+            assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+            assert_close(pooled.cpu().numpy(), want, "pooled step %d" % step)
+        gt.push(torch.from_numpy(b.grads).cuda())
+        ot.push(b.grads)
+    compare_tables(gt, ot, cfg.name)
+    return gt, ot
+
+
+def test_tiny_config_full_size():
+    run_steps(synth.CONFIGS["tiny"], steps=3)
+
+
+@pytest.mark.parametrize("name,n_prefill,n_examples,n_slots", [
+    ("mid", 200_000, 128, 100),            # ~64k occurrences: several sort tiles, ragged tail
+    ("insert_heavy", 50_000, 64, 100),
+    ("large", 300_000, 96, 200),
+    ("skewed", 100_000, 256, 64),          # dim 64, hot keys with long segments
+])
+def test_scaled_configs(name, n_prefill, n_examples, n_slots):
+    cfg = synth.scaled(synth.CONFIGS[name], n_prefill=n_prefill, n_examples=n_examples,
+                       n_slots=n_slots, steps=4)
+    run_steps(cfg, steps=4)
+
+
+def test_elementwise_adagrad():
+    cfg = synth.scaled(synth.CONFIGS["mid"], n_prefill=20_000, n_examples=64, n_slots=20, steps=3)
+    run_steps(cfg, steps=3, opt=hps.ADAGRAD_ELEMENTWISE)
+
+
+def test_long_run_insert_heavy_50_steps_and_determinism():
+    cfg = synth.scaled(synth.CONFIGS["insert_heavy"], n_prefill=23_000, n_examples=8,
+                       n_slots=100, steps=50)
+    g1, _ = run_steps(cfg, steps=50, check_every=7)
+    k1, w1, a1 = g1.dump()
+    o1 = torch.argsort(k1)
+    del _
+    g2, _ = run_steps(cfg, steps=50, check_every=50)
+    k2, w2, a2 = g2.dump()
+    o2 = torch.argsort(k2)
+    assert torch.equal(k1[o1], k2[o2]) and torch.equal(w1[o1], w2[o2]) and torch.equal(a1[o1], a2[o2])
+
+
+def test_edge_cases():
+    cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=1000, n_examples=4, n_slots=4, steps=1)
+    gt, ot = make_pair(cfg, 5000)
+    pre = synth.prefill_keys(0, 1000)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+    zero_grads = torch.zeros((16, cfg.dim), device="cuda")
+    # empty batch: every bag empty
+    offs = torch.zeros(17, dtype=torch.int32, device="cuda")
+    pooled = gt.pull(torch.zeros(0, dtype=torch.int64, device="cuda"), offs, 4, 4)
+    assert torch.equal(pooled, torch.zeros_like(pooled))
+    assert gt.stats().last_n_unique == 0
+    gt.push(zero_grads)
+    # one key; all-equal keys; keys around 2^32 and 2^63; raw sequential (unmixed) keys
+    cases = [
+        np.array([pre[5]], dtype=np.uint64),
+        np.full(3000, pre[7], dtype=np.uint64),
+        np.array([2**32 - 1, 2**32, 2**32 + 1, 2**63 - 1, 2**63, 2**63 + 1, 0, 1, 2**64 - 2] * 7,
+                 dtype=np.uint64),
+        np.arange(4097, dtype=np.uint64)[::-1].copy(),
+    ]
+    rng = np.random.default_rng(0)
+    for keys in cases:
+        n = keys.shape[0]
+        cuts = np.sort(rng.integers(0, n + 1, size=15))
+        offsets = np.concatenate([[0], cuts, [n]]).astype(np.int32)     # ragged, some empty bags
+        grads = rng.normal(0, 1e-3, size=(16, cfg.dim)).astype(np.float32)
+        pooled = gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), 4, 4)
+        want = ot.pull(keys, offsets)
+        uniq, inv = gt.last_unique()
+        ou, oi = ot.last_unique()
+        assert np.array_equal(host_keys(uniq), ou) and np.array_equal(inv.cpu().numpy(), oi)
+        assert_close(pooled.cpu().numpy(), want, "pooled")
+        gt.push(torch.from_numpy(grads).cuda())
+        ot.push(grads)
+    compare_tables(gt, ot, "edge")
+    # push without pull
+    with pytest.raises(hps.HpsError) as e:
+        gt.push(zero_grads)
+    assert e.value.status == hps.ESTATE
+    # get: present and absent keys
+    probe = np.concatenate([pre[:10], synth.mix64(np.arange(10**9, 10**9 + 10, dtype=np.uint64))])
+    w, a, f = gt.get(dev_keys(probe))
+    ow, oa, of = ot.get(probe)
+    assert np.array_equal(f.cpu().numpy(), of)
+    assert_close(w.cpu().numpy()[of], ow[of], "get weights")
+    assert_close(a.cpu().numpy()[of], oa[of], "get acc")
+
+
+def test_reserved_key_and_table_full_are_reported():
+    gt = hps.HpsTable(100, 8, 1000, 4)
+    gt.insert(dev_keys(np.arange(100, dtype=np.uint64)))
+    assert gt.stats().size == 100 and gt.stats().error == 0
+    offs = torch.tensor([0, 1, 2, 2, 2], dtype=torch.int32, device="cuda")
+    gt.pull(dev_keys(np.array([5, 2**64 - 1], dtype=np.uint64)), offs, 2, 2)
+    assert gt.stats().error == hps.ERESERVED
+    gt.clear_error()
+    gt.pull(dev_keys(np.array([5, 1000], dtype=np.uint64)), offs, 2, 2)       # key 1000 does not fit
+    st = gt.stats()
+    assert st.error == hps.EFULL and st.size == 100
+    gt.clear_error()
+    pooled = gt.pull(dev_keys(np.array([5, 6], dtype=np.uint64)), offs, 2, 2)   # present keys: fine
+    assert gt.stats().error == 0
+    w, _, f = gt.get(dev_keys(np.array([5, 6], dtype=np.uint64)))
+    assert f.all() and torch.equal(pooled[:2], w)
+    with pytest.raises(hps.HpsError) as e:
+        gt.pull(dev_keys(np.arange(2000, dtype=np.uint64)), offs, 2, 2)         # n_keys > max_keys
+    assert e.value.status == hps.EINVAL
+
+
+def test_dump_insert_roundtrip():
+    cfg = synth.scaled(synth.CONFIGS["mid"], n_prefill=5000, n_examples=16, n_slots=20, steps=2)
+    gt, _ = run_steps(cfg, steps=2)
+    k, w, a = gt.dump()
+    g2 = hps.HpsTable(cfg.capacity, cfg.dim, 1000, 10)
+    g2.insert(k, w, a)
+    k2, w2, a2 = g2.dump()
+    o1, o2 = torch.argsort(k), torch.argsort(k2)
+    assert torch.equal(k[o1], k2[o2]) and torch.equal(w[o1], w2[o2]) and torch.equal(a[o1], a2[o2])
+    assert g2.stats().size == k.numel()
