@@ -57,11 +57,15 @@ __device__ __forceinline__ u64 slot_hash(u64 k) {
 }
 
 // Element j of key's initial row: uniform on [-a, a) from 24 random bits, as a
-// rounded product followed by a rounded difference (never fused).
+// rounded product followed by a rounded difference.  The two must never be fused
+// into one multiply-add (that would round once and change the bits), so
+// contraction is switched off for this function.
 __device__ __forceinline__ float init_weight(u64 base, u32 j, float a) {
+#pragma clang fp contract(off)
   const u64 r = mix64(base + j);
-  const float u = __fmul_rn((float)(u32)(r >> 40), 0x1.0p-24f);
-  return __fsub_rn(__fmul_rn(u, __fmul_rn(a, 2.0f)), a);
+  const float u = (float)(u32)(r >> 40) * 0x1.0p-24f;   // exact
+  const float scaled = u * (a * 2.0f);
+  return scaled - a;
 }
 
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & (kWave - 1); }

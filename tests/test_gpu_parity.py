@@ -125,7 +125,8 @@ def test_long_run_insert_heavy_50_steps_and_determinism():
 
 
 def test_edge_cases():
-    cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=1000, n_examples=4, n_slots=4, steps=1)
+    cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=1000, n_examples=4, n_slots=4,
+                       capacity=8000, steps=1)
     gt, ot = make_pair(cfg, 5000)
     pre = synth.prefill_keys(0, 1000)
     gt.insert(dev_keys(pre))
