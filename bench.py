@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Throughput of the HBM-PS mini-batch pull+push on one MI355X.
+
+One "step" = hps_pull + hps_push of one synthetic mini-batch (all five stages of the
+path: dedup, lookup-or-insert, gather + pool, reduce by key, Adagrad update), inputs
+already resident in HBM.  Prints ONE JSON line:
+
+  value      unique keys per second over the timed steps (whole job, one GPU)
+  roofline   the stage that takes the most time, its algorithmic HBM bytes per launch
+             over its HIP-event duration, against the 8 TB/s peak
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mid]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def stage_bytes(n, u, bags, d):
+    """Algorithmic HBM bytes of one step, per stage: what the method itself has to move
+    once, with 4-byte indices and each distinct row crossing HBM once per direction."""
+    return {
+        "dedup": 8 * n + 4 * n + 8 * u,                     # read keys, write inverse, write uniq
+        "lookup": 8 * u + 4 * u,                            # one slot key per unique, row id
+        "pool": 4 * d * u + 4 * n + 4 * bags + 4 * d * bags,  # rows, inverse, offsets, pooled
+        "push": 4 * d * bags + 4 * n + 2 * (4 * d + 4) * u,  # grads, grouping, row+acc r/w
+    }
+
+
+STAGE_BITS = {"dedup": 0b00011, "lookup": 0b00100, "pool": 0b01000, "push": 0b10000}
+STAGE_KERNELS = {
+    "dedup": "pairs_from_keys, pairs_regather, 8 x (radix_hist, scan_counters, radix_scatter), "
+             "heads_count, heads_scan, heads_emit",
+    "lookup": "probe_keys<1>",
+    "pool": "pool_bags",
+    "push": "push_segments, push_chunks, push_long",
+}
+
+
+def merge_stage_times(times):
+    out = {}
+    out["dedup"] = (times["sort"][0] + times["unique"][0], times["sort"][1])
+    for k in ("lookup", "pool", "push"):
+        out[k] = times[k]
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="mid")
+    ap.add_argument("--batches", type=int, default=0,
+                    help="distinct pre-generated batches (0: steps + warmup, at most 24)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="time budget of the CPU oracle leg (0 disables it)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one GPU's shard of the table, no "
+              "collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2003_05622_amd as hps
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    n_batches = args.batches or min(args.steps + args.warmup, 24)
+
+    def dev_keys(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).cuda()
+
+    # ---- inputs: generated on the host, resident in HBM before the timed region -------
+    t0 = time.time()
+    stream = synth.BatchStream(cfg)
+    host_batches, dev_batches = [], []
+    for _ in range(n_batches):
+        b = stream.next()
+        host_batches.append(b)
+        dev_batches.append((dev_keys(b.keys), torch.from_numpy(b.offsets).cuda(),
+                            torch.from_numpy(b.grads).cuda()))
+    n_max = max(b.n_keys for b in host_batches)
+    uniques = [int(np.unique(b.keys).shape[0]) for b in host_batches]
+    table = hps.HpsTable(cfg.capacity, cfg.dim, n_max, cfg.n_bags, lr=cfg.lr, eps=cfg.eps,
+                         init_acc=cfg.init_acc, init_range=cfg.init_range,
+                         init_seed=cfg.init_seed)
+    chunk = 1 << 23
+    for lo in range(0, cfg.n_prefill, chunk):
+        table.insert(dev_keys(synth.prefill_keys(lo, min(lo + chunk, cfg.n_prefill))))
+    torch.cuda.synchronize()
+    table.check("prefill")
+    pooled = torch.empty((cfg.n_bags, cfg.dim), dtype=torch.float32, device="cuda")
+    setup_s = time.time() - t0
+
+    def step(i):
+        k, o, g = dev_batches[i % n_batches]
+        table.pull(k, o, cfg.n_examples, cfg.n_slots, pooled)
+        table.push(g)
+
+    # ---- warm-up, and a look at which stage dominates ---------------------------------
+    table.set_stage_timing(0b11111)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    calib = merge_stage_times(table.stage_times())
+    if args.warmup == 0 or calib["dedup"][1] == 0:
+        dominant = "dedup"
+    else:
+        dominant = max(calib, key=lambda s: calib[s][0])
+    table.set_stage_timing(STAGE_BITS[dominant])
+
+    # ---- timed region --------------------------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timed = merge_stage_times(table.stage_times())
+    table.check("timed steps")
+
+    idx = [i % n_batches for i in range(args.warmup, args.warmup + args.steps)]
+    sum_u = sum(uniques[i] for i in idx)
+    sum_n = sum(host_batches[i].n_keys for i in idx)
+    mean_n, mean_u = sum_n / args.steps, sum_u / args.steps
+    per_stage = stage_bytes(mean_n, mean_u, cfg.n_bags, cfg.dim)
+    dom_ms = timed[dominant][0] / max(timed[dominant][1], 1)
+    achieved = per_stage[dominant] / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    step_bytes = sum(per_stage.values())
+
+    # ---- all stages once more, outside the timed region, for the record -------------------
+    table.set_stage_timing(0b11111)
+    for i in range(args.warmup + args.steps, args.warmup + args.steps + 5):
+        step(i)
+    torch.cuda.synchronize()
+    allst = merge_stage_times(table.stage_times())
+    stages = {s: {"ms": round(allst[s][0] / max(allst[s][1], 1), 4),
+                  "alg_bytes": int(per_stage[s]),
+                  "gbps": round(per_stage[s] / max(allst[s][0] / max(allst[s][1], 1), 1e-9) / 1e6, 1)}
+              for s in allst}
+    st = table.stats()
+
+    # ---- CPU oracle on a bounded sample of the same workload ------------------------------
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        ot = oracle.OracleTable(cfg.capacity, cfg.dim, lr=cfg.lr, eps=cfg.eps,
+                                init_acc=cfg.init_acc, init_range=cfg.init_range,
+                                init_seed=cfg.init_seed)
+        ot.declare_resident(cfg.n_prefill)
+        spent, done_u, done = 0.0, 0, 0
+        for b in host_batches:
+            res, _ = synth.resident_split(cfg, b)
+            ot.materialize(res)            # stands in for the prefill: not timed
+            c0 = time.perf_counter()
+            ot.pull(b.keys, b.offsets)
+            ot.push(b.grads)
+            spent += time.perf_counter() - c0
+            done_u += ot.n_unique
+            done += 1
+            if spent > args.cpu_seconds:
+                break
+        cpu = {"value": round(done_u / spent, 1), "unit": "unique keys/s", "cores": 1,
+               "kind": "oracle",
+               "sample": "%d mini-batch(es) of the '%s' workload, pull+push, single thread, "
+                         "%.1f s" % (done, cfg.name, spent)}
+
+    out = {
+        "metric": "unique keys/sec pull+push (1 MI355X) and achieved HBM GB/s vs peak",
+        "value": round(sum_u / elapsed, 1),
+        "unit": "unique keys/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "table_keys": int(st.size), "capacity": cfg.capacity,
+                   "dim": cfg.dim, "n_examples": cfg.n_examples, "n_slots": cfg.n_slots,
+                   "keys_per_step": round(mean_n, 1), "unique_per_step": round(mean_u, 1),
+                   "zipf_s": cfg.zipf_s, "fresh_frac": cfg.fresh_frac,
+                   "distinct_batches": n_batches},
+        "occurrences_per_s": round(sum_n / elapsed, 1),
+        "step_alg_bytes": int(step_bytes),
+        "step_gbps": round(step_bytes / (elapsed / args.steps) / 1e9, 1),
+        "step_frac_of_peak": round(step_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": dominant + ": " + STAGE_KERNELS[dominant],
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launch_ms": round(dom_ms, 4), "launches_timed": int(timed[dominant][1]),
+                     "alg_bytes_per_launch": int(per_stage[dominant])},
+        "stages": stages,
+        "cpu_baseline": cpu,
+        "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

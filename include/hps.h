@@ -98,7 +98,7 @@ size_t hps_workspace_bytes(uint64_t max_keys, uint64_t max_bags, uint32_t dim);
  *   capacity_keys  maximum number of keys ever stored (1 .. 2^32 * 0.69)
  *   dim            floats per embedding row; a multiple of 4, at most 1024
  *   d_storage      >= hps_table_bytes() bytes; d_workspace >= hps_workspace_bytes()
- *   max_keys       largest n_keys a pull may pass (< 2^31); max_bags likewise
+ *   max_keys       largest n_keys a pull may pass (< 2^30); max_bags likewise
  * Enqueues the clearing of the slot array on `stream`.  *out is set on success and
  * must be released with hps_destroy (which frees host memory only).
  * Errors: HPS_EINVAL, HPS_ENOMEM, HPS_EDEVICE. */
@@ -165,6 +165,27 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
 
 /* Clears the sticky device status. */
 hps_status hps_clear_error(hps_table* t, void* stream);
+
+/* Stage timing for measurement.  Stages of one step: */
+enum {
+  HPS_STAGE_SORT = 0,    /* pull: order the key occurrences                        */
+  HPS_STAGE_UNIQUE = 1,  /* pull: unique keys, inverse, grouping                   */
+  HPS_STAGE_LOOKUP = 2,  /* pull: find or insert every unique key                  */
+  HPS_STAGE_POOL = 3,    /* pull: row gather + bag sums                            */
+  HPS_STAGE_PUSH = 4,    /* push: reduce by key + optimizer update                 */
+  HPS_N_STAGES = 5
+};
+
+/* While bit s of stage_mask is set, every pull/push brackets stage s with a pair
+ * of HIP events recorded on the call's stream (at most 4096 pairs per stage are
+ * kept between two hps_stage_times calls; later ones are dropped).  Setting the
+ * mask discards pairs recorded so far. */
+hps_status hps_set_stage_timing(hps_table* t, uint32_t stage_mask);
+
+/* Waits for the recorded events and adds up, per stage, the elapsed milliseconds
+ * (h_ms_sum[HPS_N_STAGES]) and the number of pairs (h_count[HPS_N_STAGES]); the
+ * recorded pairs are then discarded.  Host arrays. */
+hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count);
 
 /* Frees the host object; device memory stays with the caller. */
 hps_status hps_destroy(hps_table* t);

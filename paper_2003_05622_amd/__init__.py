@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     ADAGRAD_ELEMENTWISE,
     OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM,
     EXPORTS,
+    STAGES,
 )

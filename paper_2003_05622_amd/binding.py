@@ -12,7 +12,9 @@ ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_push", "hps_last_unique", "hps_get", "hps_dump", "hps_stats", "hps_clear_error",
-           "hps_destroy", "hps_strerror")
+           "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
+
+STAGES = ("sort", "unique", "lookup", "pool", "push")
 
 
 class Optimizer(ctypes.Structure):
@@ -61,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
         L.hps_clear_error.restype = st
         L.hps_clear_error.argtypes = [vp, vp]
+        L.hps_set_stage_timing.restype = st
+        L.hps_set_stage_timing.argtypes = [vp, u32]
+        L.hps_stage_times.restype = st
+        L.hps_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(u32)]
         L.hps_destroy.restype = st
         L.hps_destroy.argtypes = [vp]
         L.hps_strerror.restype = ctypes.c_char_p
@@ -188,6 +194,16 @@ class HpsTable:
         s = Stats()
         _check(lib().hps_stats(self._h, ctypes.byref(s), _stream()), "hps_stats")
         return s
+
+    def set_stage_timing(self, stage_mask: int) -> None:
+        _check(lib().hps_set_stage_timing(self._h, stage_mask), "hps_set_stage_timing")
+
+    def stage_times(self):
+        """{stage name: (sum of milliseconds, number of timed launches)} since the last call."""
+        ms = (ctypes.c_double * len(STAGES))()
+        cnt = (ctypes.c_uint32 * len(STAGES))()
+        _check(lib().hps_stage_times(self._h, ms, cnt), "hps_stage_times")
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
 
     def clear_error(self) -> None:
         _check(lib().hps_clear_error(self._h, _stream()), "hps_clear_error")

@@ -33,7 +33,9 @@ struct PullCtx {
   u32 n_unique;        // U
   u32 n_long;          // long segments found by the push
   u32 n_chunk_items;   // (segment, chunk) work items of the push
-  u32 pad;
+  u32 n_evidence;      // sorted positions where a run of equal sorted bits mixes keys
+  u32 sort_error;      // set if a look-back wait gave up (never expected)
+  u32 pad[3];
 };
 
 // SplitMix64 output function for state x (Steele, Lea, Flood 2014).  The row

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "common.cuh"
 #include "dedup.cuh"
@@ -59,26 +60,29 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
 }
 
 struct WorkspaceLayout {
-  size_t ctx, pairs_a, pairs_b, hist, skeys, tile_heads, uniq, rows, inverse, perm, seg_off,
-      bag_of, long_list, chunk_items, partials, total;
-  uint64_t max_long, max_items;
+  size_t ctx, elems_a, elems_b, ghist, tickets, tile_state, head_state, evidence, skeys, uniq,
+      rows, inverse, perm, seg_off, bag_of, long_list, chunk_items, partials, total;
+  uint64_t max_long, max_items, sort_tiles, head_tiles;
 };
 
 WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   (void)bags;
   WorkspaceLayout L;
   const uint64_t n1 = n ? n : 1;
-  const uint64_t sort_tiles = (n1 + kSortTile - 1) / kSortTile;
-  const uint64_t head_tiles = (n1 + kHeadTile - 1) / kHeadTile;
+  L.sort_tiles = (n1 + kSortTile - 1) / kSortTile;
+  L.head_tiles = (n1 + kHeadTile - 1) / kHeadTile;
   L.max_long = n1 / kLongSeg + 1;
   L.max_items = n1 / kChunk + L.max_long + 1;
   size_t o = 0;
   L.ctx = o;         o = align_up(o + sizeof(PullCtx));
-  L.pairs_a = o;     o = align_up(o + n1 * 8);
-  L.pairs_b = o;     o = align_up(o + n1 * 8);
-  L.hist = o;        o = align_up(o + sort_tiles * kRadix * 4);
+  L.elems_a = o;     o = align_up(o + n1 * 8);
+  L.elems_b = o;     o = align_up(o + n1 * 8);
+  L.ghist = o;       o = align_up(o + 2 * kMaxPasses * kRadix * 4);
+  L.tickets = o;     o = align_up(o + (kMaxPasses + 1) * 4);
+  L.tile_state = o;  o = align_up(o + (size_t)kMaxPasses * L.sort_tiles * kRadix * 8);
+  L.head_state = o;  o = align_up(o + L.head_tiles * 8);
+  L.evidence = o;    o = align_up(o + kMaxEvidence * 4);
   L.skeys = o;       o = align_up(o + n1 * 8);
-  L.tile_heads = o;  o = align_up(o + head_tiles * 4);
   L.uniq = o;        o = align_up(o + n1 * 8);
   L.rows = o;        o = align_up(o + n1 * 4);
   L.inverse = o;     o = align_up(o + n1 * 4);
@@ -90,6 +94,25 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   L.partials = o;    o = align_up(o + L.max_items * (size_t)dim * 4);
   L.total = o;
   return L;
+}
+
+// How many 8-bit digits to sort for n occurrences: enough that two different keys
+// rarely agree in all sorted bits (about 2*log2(n) - 3 bits), within what an element
+// can carry beside the occurrence index.
+SortPlan sort_plan(uint64_t n) {
+  SortPlan p;
+  int idx_bits = 1;
+  while ((1ull << idx_bits) < n) ++idx_bits;
+  int log2n = idx_bits;
+  int want = (2 * log2n - 3 + 7) / 8;
+  const int room = (64 - idx_bits) / 8;
+  if (want < 2) want = 2;
+  if (want > room) want = room;
+  if (want > kMaxPasses) want = kMaxPasses;
+  p.n_pass = want;
+  p.idx_bits = idx_bits;
+  p.low_shift = 64 - 8 * want;
+  return p;
 }
 
 int lanes_per_row(uint32_t dim) {
@@ -110,11 +133,33 @@ struct hps_table {
   char* ws;
   WorkspaceLayout wl;
   int lpr;
+  uint32_t epoch;      // serial number of the pull (look-back status words carry it)
   bool pulled;
   uint64_t last_n_keys, last_n_bags;
 
+  // stage timing (measurement only)
+  uint32_t timing_mask;
+  std::vector<hipEvent_t> ev_pool[HPS_N_STAGES];   // begin/end alternate
+  size_t ev_used[HPS_N_STAGES];
+
   template <typename T> T* w(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
+
+namespace {
+constexpr size_t kMaxEventPairs = 4096;
+
+void stage_mark(hps_table* t, int stage, hipStream_t s) {
+  if (!(t->timing_mask & (1u << stage))) return;
+  std::vector<hipEvent_t>& pool = t->ev_pool[stage];
+  if (t->ev_used[stage] >= 2 * kMaxEventPairs) return;
+  if (t->ev_used[stage] == pool.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    pool.push_back(e);
+  }
+  (void)hipEventRecord(pool[t->ev_used[stage]++], s);
+}
+}  // namespace
 
 template <int LPR>
 static void launch_pool(hps_table* t, const int32_t* d_offsets, uint32_t n_bags, float* d_pooled,
@@ -169,7 +214,7 @@ size_t hps_table_bytes(uint64_t capacity_keys, uint32_t dim, const hps_optimizer
 }
 
 size_t hps_workspace_bytes(uint64_t max_keys, uint64_t max_bags, uint32_t dim) {
-  if (max_keys >= (1ull << 31) || max_bags >= (1ull << 31) || dim < 4 || dim > 1024 || dim % 4)
+  if (max_keys >= (1ull << 30) || max_bags >= (1ull << 31) || dim < 4 || dim > 1024 || dim % 4)
     return 0;
   return workspace_layout(max_keys, max_bags, dim).total;
 }
@@ -183,7 +228,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   if (!valid_opt(opt) || !valid_shape(capacity_keys, dim)) return HPS_EINVAL;
   if (!d_storage || !d_workspace) return HPS_EINVAL;
   if ((uintptr_t)d_storage % kAlign || (uintptr_t)d_workspace % kAlign) return HPS_EINVAL;
-  if (max_keys >= (1ull << 31) || max_bags >= (1ull << 31)) return HPS_EINVAL;
+  if (max_keys >= (1ull << 30) || max_bags >= (1ull << 31)) return HPS_EINVAL;
   const uint32_t acc_len = opt->kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? dim : 1;
   const uint64_t n_slots = slots_for(capacity_keys);
   const StorageLayout sl = storage_layout(n_slots, dim, acc_len);
@@ -218,9 +263,14 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->lpr = lanes_per_row(dim);
   t->pulled = false;
   t->last_n_keys = t->last_n_bags = 0;
+  t->timing_mask = 0;
+  for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
+  t->epoch = 0;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
+  // look-back status words and digit histograms start at zero
+  fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.skeys - wl.ghist) / 8, 0);
   reset_state<<<1, 1, 0, s>>>(t->view.st);
   set_ctx_empty<<<1, 1, 0, s>>>(t->w<PullCtx>(wl.ctx), t->w<u32>(wl.seg_off));
   if (!launch_ok()) { delete t; return HPS_EDEVICE; }
@@ -230,6 +280,8 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
 
 hps_status hps_destroy(hps_table* t) {
   if (!t) return HPS_EINVAL;
+  for (int i = 0; i < HPS_N_STAGES; ++i)
+    for (hipEvent_t e : t->ev_pool[i]) (void)hipEventDestroy(e);
   delete t;
   return HPS_OK;
 }
@@ -270,45 +322,65 @@ hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
     set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(L.seg_off));
     clear_inserted<<<1, 1, 0, s>>>(t->view.st);
   } else {
-    // a1: order the occurrences by key (two 32-bit halves, 8-bit digits, low half first)
-    u64* cur = t->w<u64>(L.pairs_a);
-    u64* alt = t->w<u64>(L.pairs_b);
-    u32* hist = t->w<u32>(L.hist);
-    const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    const unsigned flat_blocks = (n + 255) / 256;
-    for (int half = 0; half < 2; ++half) {
-      if (half == 0)
-        pairs_from_keys<<<flat_blocks, 256, 0, s>>>(d_keys, n, 0, cur);
-      else
-        pairs_regather<<<flat_blocks, 256, 0, s>>>(d_keys, n, 32, cur);
-      for (int shift = 0; shift < 32; shift += kRadixBits) {
-        radix_hist<<<n_tiles, kSortThreads, 0, s>>>(cur, n, shift, hist, n_tiles);
-        scan_counters<<<1, 1024, 0, s>>>(hist, n_tiles * kRadix);
-        radix_scatter<<<n_tiles, kSortThreads, 0, s>>>(cur, alt, n, shift, hist, n_tiles);
-        u64* tmp = cur; cur = alt; alt = tmp;
-      }
+    // a1: order the occurrences by the top bits of their keys
+    stage_mark(t, HPS_STAGE_SORT, s);
+    if (++t->epoch >= (1u << 30)) {      // status words of 2^30 pulls ago could alias: start over
+      fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_state), (L.evidence - L.tile_state) / 8, 0);
+      t->epoch = 1;
     }
+    const SortPlan plan = sort_plan(n);
+    u64* cur = t->w<u64>(L.elems_a);
+    u64* alt = t->w<u64>(L.elems_b);
+    u32* ghist = t->w<u32>(L.ghist) + (t->epoch & 1) * kMaxPasses * kRadix;
+    u32* ghist_next = t->w<u32>(L.ghist) + ((t->epoch + 1) & 1) * kMaxPasses * kRadix;
+    u32* tickets = t->w<u32>(L.tickets);
+    const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
+    sort_prepare<<<n_tiles < 1024 ? n_tiles : 1024, kSortThreads, 0, s>>>(d_keys, n, plan, ghist,
+                                                                          ghist_next, tickets, ctx);
+    for (int p = 0; p < plan.n_pass; ++p) {
+      u64* state = t->w<u64>(L.tile_state) + (size_t)p * L.sort_tiles * kRadix;
+      const int shift = plan.low_shift + p * kRadixBits;
+      if (p == 0)
+        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, cur, n, shift,
+                                                             plan.idx_bits, ghist, state, tickets,
+                                                             t->epoch, ctx);
+      else
+        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(nullptr, cur, alt, n, shift,
+                                                              plan.idx_bits, ghist + p * kRadix, state,
+                                                              tickets + p, t->epoch, ctx);
+      if (p > 0) { u64* tmp = cur; cur = alt; alt = tmp; }
+    }
+    stage_mark(t, HPS_STAGE_SORT, s);
     // a1: unique keys, ranks, grouping
+    stage_mark(t, HPS_STAGE_UNIQUE, s);
     const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
-    u32* tile_heads = t->w<u32>(L.tile_heads);
-    heads_count<<<head_tiles, kHeadThreads, 0, s>>>(cur, d_keys, n, t->w<u64>(L.skeys), tile_heads);
-    heads_scan<<<1, 1024, 0, s>>>(tile_heads, head_tiles, n, ctx, t->w<u32>(L.seg_off));
+    u64* skeys = t->w<u64>(L.skeys);
+    detect_mixed_runs<<<head_tiles, kHeadThreads, 0, s>>>(cur, d_keys, n, plan, skeys, ctx,
+                                                          t->w<u32>(L.evidence));
+    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(cur, alt, skeys, d_keys, n, plan, ctx,
+                                             t->w<u32>(L.evidence));
     clear_inserted<<<1, 1, 0, s>>>(t->view.st);
-    heads_emit<<<head_tiles, kHeadThreads, 0, s>>>(cur, t->w<u64>(L.skeys), n, tile_heads,
-                                                   t->w<u64>(L.uniq), t->w<i32>(L.inverse),
-                                                   t->w<u32>(L.perm), t->w<u32>(L.seg_off),
-                                                   t->view.st);
+    unique_emit<<<head_tiles, kHeadThreads, 0, s>>>(cur, skeys, n, plan.idx_bits,
+                                                    t->w<u64>(L.head_state), tickets + kMaxPasses,
+                                                    t->epoch, t->w<u64>(L.uniq),
+                                                    t->w<i32>(L.inverse), t->w<u32>(L.perm),
+                                                    t->w<u32>(L.seg_off), ctx, t->view.st);
+    stage_mark(t, HPS_STAGE_UNIQUE, s);
     // a2: look up or insert every unique key
+    stage_mark(t, HPS_STAGE_LOOKUP, s);
     const unsigned probe_blocks = (n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock;
     probe_keys<1><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
                                                          &ctx->n_unique, t->w<u32>(L.rows), nullptr,
                                                          nullptr, nullptr, nullptr, nullptr);
+    stage_mark(t, HPS_STAGE_LOOKUP, s);
   }
   // a3: gather rows and pool per bag
   if (n_bags) {
+    stage_mark(t, HPS_STAGE_POOL, s);
 #define CALL(LPR) launch_pool<LPR>(t, d_offsets, (uint32_t)n_bags, d_pooled, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
+    stage_mark(t, HPS_STAGE_POOL, s);
   }
   if (!launch_ok()) return HPS_EDEVICE;
   t->pulled = true;
@@ -339,9 +411,11 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   a.lr = t->opt.lr;
   a.eps = t->opt.eps;
   a.elementwise = t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE;
+  stage_mark(t, HPS_STAGE_PUSH, s);
 #define CALL(LPR) launch_push<LPR>(t, a, s)
   HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
+  stage_mark(t, HPS_STAGE_PUSH, s);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
@@ -410,6 +484,36 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->error = st.error;
   h_out->pull_outstanding = t->pulled ? 1 : 0;
   return HPS_OK;
+}
+
+hps_status hps_set_stage_timing(hps_table* t, uint32_t stage_mask) {
+  if (!t || stage_mask >= (1u << HPS_N_STAGES)) return HPS_EINVAL;
+  t->timing_mask = stage_mask;
+  for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
+  return HPS_OK;
+}
+
+hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count) {
+  if (!t || !h_ms_sum || !h_count) return HPS_EINVAL;
+  hps_status rc = HPS_OK;
+  for (int st = 0; st < HPS_N_STAGES; ++st) {
+    h_ms_sum[st] = 0.0;
+    h_count[st] = 0;
+    const size_t pairs = t->ev_used[st] / 2;
+    for (size_t p = 0; p < pairs; ++p) {
+      float ms = 0.f;
+      if (hipEventSynchronize(t->ev_pool[st][2 * p + 1]) != hipSuccess ||
+          hipEventElapsedTime(&ms, t->ev_pool[st][2 * p], t->ev_pool[st][2 * p + 1]) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = HPS_EDEVICE;
+        continue;
+      }
+      h_ms_sum[st] += ms;
+      h_count[st] += 1;
+    }
+    t->ev_used[st] = 0;
+  }
+  return rc;
 }
 
 hps_status hps_clear_error(hps_table* t, void* stream) {

@@ -63,6 +63,8 @@ __global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off) {
   ctx->n_unique = 0;
   ctx->n_long = 0;
   ctx->n_chunk_items = 0;
+  ctx->n_evidence = 0;
+  ctx->sort_error = 0;
   seg_off[0] = 0;
 }
 

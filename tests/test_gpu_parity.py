@@ -124,6 +124,20 @@ def test_long_run_insert_heavy_50_steps_and_determinism():
     assert torch.equal(k1[o1], k2[o2]) and torch.equal(w1[o1], w2[o2]) and torch.equal(a1[o1], a2[o2])
 
 
+def mixed_run_keys():
+    """Keys that agree in their high bits in groups: two-key groups, a 40-key group, and a
+    frequent key (600 occurrences) that shares its top 56 bits with two rare ones."""
+    rng = np.random.default_rng(9)
+    base = synth.mix64(np.arange(300, dtype=np.uint64)) & np.uint64(0xFFFFFFFFFFFFFF00)
+    pairs = np.concatenate([base[:100], base[:100] | np.uint64(1)])
+    group40 = base[100] | np.arange(40, dtype=np.uint64)
+    hot = np.concatenate([np.full(600, base[101] | np.uint64(7)), np.full(2, base[101] | np.uint64(3)),
+                          np.full(3, base[101] | np.uint64(200))])
+    filler = synth.mix64(rng.integers(0, 500, size=1500, dtype=np.uint64))
+    keys = np.concatenate([pairs, group40, group40[:10], hot, filler])
+    return keys[rng.permutation(keys.shape[0])]
+
+
 def test_edge_cases():
     cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=1000, n_examples=4, n_slots=4,
                        capacity=8000, steps=1)
@@ -145,6 +159,7 @@ def test_edge_cases():
         np.array([2**32 - 1, 2**32, 2**32 + 1, 2**63 - 1, 2**63, 2**63 + 1, 0, 1, 2**64 - 2] * 7,
                  dtype=np.uint64),
         np.arange(4097, dtype=np.uint64)[::-1].copy(),
+        mixed_run_keys(),
     ]
     rng = np.random.default_rng(0)
     for keys in cases:
