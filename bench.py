@@ -38,11 +38,11 @@ def stage_bytes(n, u, bags, d):
 
 STAGE_BITS = {"dedup": 0b00011, "lookup": 0b00100, "pool": 0b01000, "push": 0b10000}
 STAGE_KERNELS = {
-    "dedup": "pairs_from_keys, pairs_regather, 8 x (radix_hist, scan_counters, radix_scatter), "
-             "heads_count, heads_scan, heads_emit",
-    "lookup": "probe_keys<1>",
+    "dedup": "sort_prepare, n_pass x onesweep_pass, unique_emit, fix_mixed_runs, "
+             "unique_emit (redo)",
+    "lookup": "lookup_keys<0>, insert_missing, commit_insert",
     "pool": "pool_bags",
-    "push": "push_segments, push_chunks, push_long",
+    "push": "push_short, push_medium, push_chunks, push_long",
 }
 
 
@@ -61,7 +61,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="mid")
     ap.add_argument("--batches", type=int, default=0,
-                    help="distinct pre-generated batches (0: steps + warmup, at most 24)")
+                    help="distinct pre-generated batches (0: one per step run, at most 64)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="time budget of the CPU oracle leg (0 disables it)")
     args = ap.parse_args()
@@ -81,7 +81,8 @@ def main():
         return 3
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
-    n_batches = args.batches or min(args.steps + args.warmup, 24)
+    extra_steps = 5     # all-stage timing run after the timed region
+    n_batches = args.batches or min(args.steps + args.warmup + extra_steps, 64)
 
     def dev_keys(a):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).cuda()
@@ -146,7 +147,7 @@ def main():
 
     # ---- all stages once more, outside the timed region, for the record -------------------
     table.set_stage_timing(0b11111)
-    for i in range(args.warmup + args.steps, args.warmup + args.steps + 5):
+    for i in range(args.warmup + args.steps, args.warmup + args.steps + extra_steps):
         step(i)
     torch.cuda.synchronize()
     allst = merge_stage_times(table.stage_times())

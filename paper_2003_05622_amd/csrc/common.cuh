@@ -19,6 +19,8 @@ constexpr int kSlotsPerLine = 8;     // 8 keys of 8 bytes = one 64-byte line, pr
 constexpr int kErrFull = -2;
 constexpr int kErrReserved = -3;
 
+constexpr int kCountShards = 64;   // counters that many blocks add to are spread over this many words
+
 // Lives in the table's storage for the table's whole life.
 struct TableState {
   unsigned long long size;      // keys stored
@@ -26,16 +28,21 @@ struct TableState {
   int error;                    // sticky: 0 or a negative status
   int pad;
   unsigned long long dump_count;  // rows seen by the running dump
+  // Keys the running lookup found missing / rows the running insert created, spread
+  // over shards so that blocks do not all hit one address.
+  u32 miss_shard[kCountShards];
+  u32 made_shard[kCountShards];
 };
 
 // Lives in the workspace; describes the outstanding pull.
 struct PullCtx {
   u32 n_unique;        // U
-  u32 n_long;          // long segments found by the push
-  u32 n_chunk_items;   // (segment, chunk) work items of the push
+  u32 n_long;          // keys the push handles chunk by chunk
+  u32 n_medium;        // keys the push handles with one wave each
+  u32 n_chunk_items;   // (key, chunk) work items of the push
   u32 n_evidence;      // sorted positions where a run of equal sorted bits mixes keys
   u32 sort_error;      // set if a look-back wait gave up (never expected)
-  u32 pad[3];
+  u32 pad[2];
 };
 
 // SplitMix64 output function for state x (Steele, Lea, Flood 2014).  The row

@@ -1,19 +1,21 @@
-// Key dedup, part 2: from the elements sorted by their top bits to
+// Key dedup, part 2: from the occurrences sorted by the top bits of their keys
+// (skeys[j], sidx[j]) to
 //   uniq[U]      ascending unique keys
 //   inverse[N]   rank of each occurrence's key among them
-//   perm[N]      occurrence indices grouped by key (ascending key)
-//   seg_off[U+1] start of each key's group in perm
+//   bagperm[N]   bag of each occurrence, occurrences grouped by key (ascending key)
+//   seg_off[U+1] start of each key's group in bagperm
 //
-//   detect_mixed_runs  reads every sorted occurrence's full key (skeys) and records
-//                      the positions where two neighbours agree in the sorted bits
-//                      but are different keys ("evidence" of a mixed run);
-//   fix_mixed_runs     one workgroup; does nothing when there is no evidence (the
-//                      normal case for hashed keys); otherwise orders every mixed run
-//                      by full key -- runs of up to 64 elements inside one wave,
-//                      longer ones (or, with too much evidence, the whole array) by
-//                      a workgroup-local radix sort through global memory;
-//   unique_emit        group heads, their running count across tiles by decoupled
-//                      look-back, and all outputs.
+//   unique_emit     group heads, their running count across tiles by decoupled
+//                   look-back, and all outputs.  It also records "evidence": positions
+//                   where two neighbours agree in the sorted bits but are different
+//                   keys, i.e. where the order below the sorted bits may be wrong.
+//   fix_mixed_runs  one workgroup; does nothing without evidence (the normal case
+//                   for hashed keys); otherwise orders every mixed run by full key --
+//                   runs of up to 64 elements inside one wave, longer ones (or, with
+//                   too much evidence, the whole array) by a workgroup-local radix
+//                   sort through global memory;
+//   unique_emit     runs a second time, and only does anything then, if there was
+//                   evidence (REDO instance).
 #pragma once
 
 #include "common.cuh"
@@ -28,45 +30,8 @@ constexpr u32 kMaxEvidence = 1024;
 constexpr int kFixThreads = 1024;
 constexpr int kFixWaves = kFixThreads / kWave;
 
-__global__ void __launch_bounds__(kHeadThreads)
-detect_mixed_runs(const u64* __restrict__ elems, const u64* __restrict__ keys, u32 n,
-                  SortPlan plan, u64* __restrict__ skeys, PullCtx* __restrict__ ctx,
-                  u32* __restrict__ evidence) {
-  const u32 first = blockIdx.x * kHeadTile + threadIdx.x * kHeadItems;
-  if (first >= n) return;
-  u64 prev_e = 0, prev_key = 0;
-  if (first > 0) {
-    prev_e = elems[first - 1];
-    prev_key = keys[elem_idx(prev_e, plan.idx_bits)];
-  }
-  u64 e[kHeadItems], key[kHeadItems];
-#pragma unroll
-  for (int k = 0; k < kHeadItems; ++k) {
-    const u32 j = first + k;
-    e[k] = (j < n) ? elems[j] : 0;
-  }
-#pragma unroll
-  for (int k = 0; k < kHeadItems; ++k) {
-    const u32 j = first + k;
-    key[k] = (j < n) ? keys[elem_idx(e[k], plan.idx_bits)] : 0;
-  }
-#pragma unroll
-  for (int k = 0; k < kHeadItems; ++k) {
-    const u32 j = first + k;
-    if (j < n) {
-      skeys[j] = key[k];
-      if (j > 0 && key[k] != prev_key && (e[k] >> plan.low_shift) == (prev_e >> plan.low_shift)) {
-        const u32 slot = atomicAdd(&ctx->n_evidence, 1u);
-        if (slot < kMaxEvidence) evidence[slot] = j;
-      }
-      prev_e = e[k];
-      prev_key = key[k];
-    }
-  }
-}
-
-// ---- workgroup-local (one block of kFixThreads) stable radix sort of elems[a, b) by
-// ---- the full 64-bit key, through global memory.  Slow; for rare inputs only.
+// ---- workgroup-local (one block of kFixThreads) stable radix sort of the pairs in
+// ---- [a, b) by the full 64-bit key, through global memory.  Slow; rare inputs only.
 
 struct FixLds {
   u32 hist[kRadix];
@@ -75,13 +40,13 @@ struct FixLds {
   u32 scratch[kFixThreads / kWave + 1];
 };
 
-// One pass over words (sort word << 32 | idx) in src[a, b) -> dst[a, b).
-__device__ void wg_radix_pass(const u64* src, u64* dst, u32 a, u32 b, int shift, FixLds& L) {
+__device__ void wg_radix_pass(const u64* ksrc, const u32* isrc, u64* kdst, u32* idst, u32 a, u32 b,
+                              int shift, FixLds& L) {
   const u32 tid = threadIdx.x, wave = tid / kWave;
   const u64 lt = lanemask_lt();
   if (tid < kRadix) L.hist[tid] = 0;
   __syncthreads();
-  for (u32 j = a + tid; j < b; j += kFixThreads) atomicAdd(&L.hist[(u32)(src[j] >> (32 + shift)) & 255u], 1u);
+  for (u32 j = a + tid; j < b; j += kFixThreads) atomicAdd(&L.hist[key_digit(ksrc[j], shift)], 1u);
   __syncthreads();
   u32 total;
   const u32 ex = block_excl_sum<kFixThreads>(tid < kRadix ? L.hist[tid] : 0, L.scratch, &total);
@@ -90,8 +55,9 @@ __device__ void wg_radix_pass(const u64* src, u64* dst, u32 a, u32 b, int shift,
   for (u32 base = a; base < b; base += kFixThreads) {
     const u32 j = base + tid;
     const bool valid = j < b;
-    const u64 e = valid ? src[j] : 0;
-    const u32 d = (u32)(e >> (32 + shift)) & 255u;
+    const u64 key = valid ? ksrc[j] : 0;
+    const u32 idx = valid ? isrc[j] : 0;
+    const u32 d = key_digit(key, shift);
     u32 before, same;
     match_digit(d, valid, lt, &before, &same);
     const bool leader = valid && before == 0;
@@ -107,44 +73,26 @@ __device__ void wg_radix_pass(const u64* src, u64* dst, u32 a, u32 b, int shift,
       atomicAdd(&L.bin[d], same);
       L.wave_cnt[wave][d] = 0;
     }
-    if (valid) dst[dest] = e;
+    if (valid) { kdst[dest] = key; idst[dest] = idx; }
     __syncthreads();
   }
 }
 
-// Orders elems[a, b) (and skeys) by full key; equal keys keep their order.
-__device__ void wg_sort_range_full(u64* elems, u64* alt, u64* skeys, const u64* keys, u32 a, u32 b,
-                                   int idx_bits, FixLds& L) {
-  const u32 tid = threadIdx.x;
-  for (int w = tid; w < kFixWaves * kRadix; w += kFixThreads) (&L.wave_cnt[0][0])[w] = 0;
-  // Two stable 32-bit sorts: by the key's low half, then by its high half.  Elements
-  // with equal keys keep their current relative order.
-  for (int half = 0; half < 2; ++half) {
-    __syncthreads();
-    for (u32 j = a + tid; j < b; j += kFixThreads) {
-      const u32 idx = half == 0 ? elem_idx(elems[j], idx_bits) : (u32)elems[j];
-      const u64 key = keys[idx];
-      elems[j] = ((u64)(half == 0 ? (u32)key : (u32)(key >> 32)) << 32) | idx;
-    }
-    __syncthreads();
-    for (int shift = 0; shift < 32; shift += kRadixBits) {
-      wg_radix_pass(elems, alt, a, b, shift, L);
-      u64* t = elems; elems = alt; alt = t;
-    }
-  }
+// Orders the pairs in [a, b) by full key; equal keys keep their order.  Eight passes
+// (an even number), so the result ends up in (skeys, sidx) again.
+__device__ void wg_sort_range_full(u64* skeys, u32* sidx, u64* kalt, u32* ialt, u32 a, u32 b,
+                                   FixLds& L) {
+  for (int w = threadIdx.x; w < kFixWaves * kRadix; w += kFixThreads) (&L.wave_cnt[0][0])[w] = 0;
   __syncthreads();
-  for (u32 j = a + tid; j < b; j += kFixThreads) {
-    const u32 idx = (u32)elems[j];
-    const u64 key = keys[idx];
-    elems[j] = make_elem(key, idx, idx_bits);
-    skeys[j] = key;
+  for (int shift = 0; shift < 64; shift += 2 * kRadixBits) {
+    wg_radix_pass(skeys, sidx, kalt, ialt, a, b, shift, L);
+    wg_radix_pass(kalt, ialt, skeys, sidx, a, b, shift + kRadixBits, L);
   }
-  __syncthreads();
 }
 
 __global__ void __launch_bounds__(kFixThreads)
-fix_mixed_runs(u64* __restrict__ elems, u64* __restrict__ alt, u64* __restrict__ skeys,
-               const u64* __restrict__ keys, u32 n, SortPlan plan, PullCtx* __restrict__ ctx,
+fix_mixed_runs(u64* __restrict__ skeys, u32* __restrict__ sidx, u64* __restrict__ kalt,
+               u32* __restrict__ ialt, u32 n, SortPlan plan, const PullCtx* __restrict__ ctx,
                const u32* __restrict__ evidence) {
   const u32 E = ctx->n_evidence;
   if (E == 0) return;
@@ -154,7 +102,7 @@ fix_mixed_runs(u64* __restrict__ elems, u64* __restrict__ alt, u64* __restrict__
   __shared__ u32 run_hi[kMaxEvidence];
   const u32 tid = threadIdx.x;
   if (E > kMaxEvidence) {
-    wg_sort_range_full(elems, alt, skeys, keys, 0, n, plan.idx_bits, L);
+    wg_sort_range_full(skeys, sidx, kalt, ialt, 0, n, L);
     return;
   }
   // sort the evidence positions (bitonic, one per thread)
@@ -175,17 +123,17 @@ fix_mixed_runs(u64* __restrict__ elems, u64* __restrict__ alt, u64* __restrict__
   // same run is dropped (run_lo = run_hi)
   if (tid < E) {
     const u32 j = ev[tid];
-    const u64 v = elems[j] >> plan.low_shift;
+    const u64 v = skeys[j] >> plan.low_shift;
     u32 lo = 0, hi = j;                       // first position with top bits >= v
     while (lo < hi) {
       const u32 mid = lo + (hi - lo) / 2;
-      if ((elems[mid] >> plan.low_shift) < v) lo = mid + 1; else hi = mid;
+      if ((skeys[mid] >> plan.low_shift) < v) lo = mid + 1; else hi = mid;
     }
     const u32 a = lo;
     lo = j; hi = n;                           // first position with top bits > v
     while (lo < hi) {
       const u32 mid = lo + (hi - lo) / 2;
-      if ((elems[mid] >> plan.low_shift) <= v) lo = mid + 1; else hi = mid;
+      if ((skeys[mid] >> plan.low_shift) <= v) lo = mid + 1; else hi = mid;
     }
     const bool first = tid == 0 || ev[tid - 1] < a;
     run_lo[tid] = a;
@@ -197,46 +145,48 @@ fix_mixed_runs(u64* __restrict__ elems, u64* __restrict__ alt, u64* __restrict__
   for (u32 r = wave; r < E; r += kFixWaves) {
     const u32 a = run_lo[r], len = run_hi[r] - a;
     if (len == 0 || len > (u32)kWave) continue;
-    u64 e = 0, key = 0;
+    u64 key = 0;
     u32 idx = 0;
-    if (lane < len) {
-      e = elems[a + lane];
-      idx = elem_idx(e, plan.idx_bits);
-      key = keys[idx];
-    }
+    if (lane < len) { key = skeys[a + lane]; idx = sidx[a + lane]; }
     u32 rank = 0;
     for (u32 m = 0; m < len; ++m) {
       const u64 okey = __shfl(key, (int)m, kWave);
       const u32 oidx = __shfl(idx, (int)m, kWave);
       rank += (okey < key || (okey == key && oidx < idx)) ? 1u : 0u;
     }
-    if (lane < len) {
-      elems[a + rank] = e;
-      skeys[a + rank] = key;
-    }
+    if (lane < len) { skeys[a + rank] = key; sidx[a + rank] = idx; }
   }
   __syncthreads();
   // long runs: the whole workgroup, one run after the other
   for (u32 r = 0; r < E; ++r) {
     const u32 a = run_lo[r], b = run_hi[r];
-    if (b - a > (u32)kWave) wg_sort_range_full(elems, alt, skeys, keys, a, b, plan.idx_bits, L);
+    if (b - a > (u32)kWave) wg_sort_range_full(skeys, sidx, kalt, ialt, a, b, L);
   }
 }
 
 // Heads of the key groups, their ranks, and every output of the dedup.
-//   head_state [n_tiles] look-back status words (see sort.cuh), ticket: tile tickets
+//   head_rows [n_tiles] and head_groups [n_groups]: status words of the tiles' and
+//   tile groups' head counts (see sort.cuh), ticket: tile tickets
+//   bagperm[j] = bag of the occurrence at sorted position j, bit 31 set on group heads
+// REDO = false: the first instance; counts evidence.  REDO = true: the instance after
+// fix_mixed_runs; returns at once unless there was evidence.
+template <bool REDO>
 __global__ void __launch_bounds__(kHeadThreads)
-unique_emit(const u64* __restrict__ elems, const u64* __restrict__ skeys, u32 n, int idx_bits,
-            u64* __restrict__ head_state, u32* __restrict__ ticket, u32 epoch,
-            u64* __restrict__ uniq, i32* __restrict__ inverse, u32* __restrict__ perm,
-            u32* __restrict__ seg_off, PullCtx* __restrict__ ctx, TableState* __restrict__ st) {
+unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, int low_shift,
+            u32* __restrict__ head_rows, u32* __restrict__ head_groups, u32 group,
+            u32* __restrict__ ticket, u32 epoch,
+            const i32* __restrict__ bag_of, u32 n_bags, u64* __restrict__ uniq,
+            i32* __restrict__ inverse, u32* __restrict__ bagperm, u32* __restrict__ seg_off,
+            PullCtx* __restrict__ ctx, u32* __restrict__ evidence, TableState* __restrict__ st) {
   __shared__ u32 scratch[kHeadThreads / kWave + 1];
   __shared__ u32 s_tile, s_earlier;
+  if (REDO && ctx->n_evidence == 0) return;
   if (threadIdx.x == 0) s_tile = atomicAdd(ticket, 1u);
   __syncthreads();
   const u32 tile = s_tile;
   const u32 first = tile * kHeadTile + threadIdx.x * kHeadItems;
   u64 key[kHeadItems];
+  u32 idx[kHeadItems], bag[kHeadItems];
   bool head[kHeadItems];
   u64 prev = 0;
   if (first > 0 && first < n) prev = skeys[first - 1];
@@ -245,40 +195,45 @@ unique_emit(const u64* __restrict__ elems, const u64* __restrict__ skeys, u32 n,
   for (int k = 0; k < kHeadItems; ++k) {
     const u32 j = first + k;
     key[k] = (j < n) ? skeys[j] : 0;
+    idx[k] = (j < n) ? sidx[j] : 0;
+  }
+#pragma unroll
+  for (int k = 0; k < kHeadItems; ++k) {
+    const u32 j = first + k;
+    // clamped: a stale entry (offsets that do not cover every occurrence) must not
+    // send the push outside the gradient buffer
+    bag[k] = (j < n) ? min((u32)bag_of[idx[k]], n_bags - 1) : 0;
     head[k] = (j < n) && (j == 0 || key[k] != prev);
     heads += head[k] ? 1u : 0u;
+    if (!REDO && head[k] && j > 0 && (key[k] >> low_shift) == (prev >> low_shift)) {
+      const u32 slot = atomicAdd(&ctx->n_evidence, 1u);
+      if (slot < kMaxEvidence) evidence[slot] = j;
+    }
     prev = key[k];
   }
   u32 tile_heads;
   const u32 before = block_excl_sum<kHeadThreads>(heads, scratch, &tile_heads);
-  if (threadIdx.x == 0) {
-    u32 earlier = 0;
-    if (tile == 0) {
-      __hip_atomic_store(head_state, state_word(epoch, kFlagInclusive, tile_heads),
-                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      __hip_atomic_store(head_state + tile, state_word(epoch, kFlagAggregate, tile_heads),
-                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      u32 p = tile - 1, spins = 0;
-      while (true) {
-        const u64 w = __hip_atomic_load(head_state + p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const u64 flag = (w >> 32) & 3;
-        if ((u32)(w >> 34) != epoch || flag == 0) {
-          if (++spins > kSpinLimit) { ctx->sort_error = 1; break; }   // never expected
-          __builtin_amdgcn_s_sleep(1);
-          continue;
-        }
-        earlier += (u32)w;
-        if (flag == kFlagInclusive || p == 0) break;
-        --p;
+  if (threadIdx.x < kWave) {
+    // Wave 0 publishes the tile's head count, then adds up the counts of the earlier
+    // tiles of its group and of all earlier groups.
+    const u32 lane = threadIdx.x;
+    bool ok = true;
+    if (lane == 0)
+      __hip_atomic_store(head_rows + tile, status_word(epoch, tile_heads), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    const u32 g = tile / group;
+    u32 earlier = wave_sum_words(head_rows, g * group, tile, lane, epoch, &ok);
+    if (tile % group == group - 1 && lane == 0)
+      __hip_atomic_store(head_groups + g, status_word(epoch, earlier + tile_heads), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    earlier += wave_sum_words(head_groups, 0, g, lane, epoch, &ok);
+    if (!ok) ctx->sort_error = 1;
+    if (lane == 0) {
+      s_earlier = earlier;
+      if ((u64)(tile + 1) * kHeadTile >= n) {     // the last tile knows U
+        ctx->n_unique = earlier + tile_heads;
+        seg_off[earlier + tile_heads] = n;
       }
-      __hip_atomic_store(head_state + tile, state_word(epoch, kFlagInclusive, earlier + tile_heads),
-                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    s_earlier = earlier;
-    if ((u64)(tile + 1) * kHeadTile >= n) {     // the last tile knows U
-      ctx->n_unique = earlier + tile_heads;
-      seg_off[earlier + tile_heads] = n;
     }
   }
   __syncthreads();
@@ -293,9 +248,8 @@ unique_emit(const u64* __restrict__ elems, const u64* __restrict__ skeys, u32 n,
         if (key[k] == kEmptyKey) raise_error(st, kErrReserved);
         ++rank;
       }
-      const u32 idx = elem_idx(elems[j], idx_bits);
-      perm[j] = idx;
-      inverse[idx] = (i32)(rank - 1);
+      bagperm[j] = bag[k] | (head[k] ? 0x80000000u : 0u);
+      inverse[idx[k]] = (i32)(rank - 1);
     }
   }
 }

@@ -25,6 +25,7 @@ namespace {
 constexpr double kLoadFactor = 0.7;
 constexpr size_t kAlign = 256;
 constexpr uint64_t kMaxSlots = 0xFFFFFFF0ull;   // row indices are 32-bit, kNoRow is reserved
+constexpr uint32_t kMinTileGroup = 8;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -60,9 +61,10 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
 }
 
 struct WorkspaceLayout {
-  size_t ctx, elems_a, elems_b, ghist, tickets, tile_state, head_state, evidence, skeys, uniq,
-      rows, inverse, perm, seg_off, bag_of, long_list, chunk_items, partials, total;
-  uint64_t max_long, max_items, sort_tiles, head_tiles;
+  size_t ctx, keys_a, keys_b, idx_a, idx_b, ghist, tickets, tile_rows, group_rows, head_rows,
+      head_groups, evidence, uniq, rows, inverse, bagperm, seg_off, bag_of, med_list, long_list, chunk_items,
+      partials, total;
+  uint64_t max_med, max_long, max_items, sort_tiles, head_tiles;
 };
 
 WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
@@ -71,24 +73,30 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   const uint64_t n1 = n ? n : 1;
   L.sort_tiles = (n1 + kSortTile - 1) / kSortTile;
   L.head_tiles = (n1 + kHeadTile - 1) / kHeadTile;
-  L.max_long = n1 / kLongSeg + 1;
+  L.max_med = n1 / (kShortSeg + 1) + 1;     // keys with more than kShortSeg occurrences
+  L.max_long = n1 / (kMedSeg + 1) + 1;      // keys with more than kMedSeg occurrences
   L.max_items = n1 / kChunk + L.max_long + 1;
   size_t o = 0;
   L.ctx = o;         o = align_up(o + sizeof(PullCtx));
-  L.elems_a = o;     o = align_up(o + n1 * 8);
-  L.elems_b = o;     o = align_up(o + n1 * 8);
+  L.keys_a = o;      o = align_up(o + n1 * 8);
+  L.keys_b = o;      o = align_up(o + n1 * 8);
+  L.idx_a = o;       o = align_up(o + n1 * 4);
+  L.idx_b = o;       o = align_up(o + n1 * 4);
+  // from here to `evidence`: cleared at creation, never again (see sort.cuh)
   L.ghist = o;       o = align_up(o + 2 * kMaxPasses * kRadix * 4);
-  L.tickets = o;     o = align_up(o + (kMaxPasses + 1) * 4);
-  L.tile_state = o;  o = align_up(o + (size_t)kMaxPasses * L.sort_tiles * kRadix * 8);
-  L.head_state = o;  o = align_up(o + L.head_tiles * 8);
+  L.tickets = o;     o = align_up(o + (kMaxPasses + 2) * 4);
+  L.tile_rows = o;   o = align_up(o + (size_t)kMaxPasses * L.sort_tiles * kRadix * 4);
+  L.group_rows = o;  o = align_up(o + (size_t)kMaxPasses * (L.sort_tiles / kMinTileGroup + 1) * kRadix * 4);
+  L.head_rows = o;   o = align_up(o + 2 * L.head_tiles * 4);
+  L.head_groups = o; o = align_up(o + 2 * (L.head_tiles / kMinTileGroup + 1) * 4);
   L.evidence = o;    o = align_up(o + kMaxEvidence * 4);
-  L.skeys = o;       o = align_up(o + n1 * 8);
   L.uniq = o;        o = align_up(o + n1 * 8);
   L.rows = o;        o = align_up(o + n1 * 4);
   L.inverse = o;     o = align_up(o + n1 * 4);
-  L.perm = o;        o = align_up(o + n1 * 4);
+  L.bagperm = o;     o = align_up(o + n1 * 4);
   L.seg_off = o;     o = align_up(o + (n1 + 1) * 4);
   L.bag_of = o;      o = align_up(o + n1 * 4);
+  L.med_list = o;    o = align_up(o + L.max_med * 4);
   L.long_list = o;   o = align_up(o + L.max_long * 8);
   L.chunk_items = o; o = align_up(o + L.max_items * 8);
   L.partials = o;    o = align_up(o + L.max_items * (size_t)dim * 4);
@@ -97,22 +105,32 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
 }
 
 // How many 8-bit digits to sort for n occurrences: enough that two different keys
-// rarely agree in all sorted bits (about 2*log2(n) - 3 bits), within what an element
-// can carry beside the occurrence index.
+// rarely agree in all sorted bits.  With b sorted bits about n^2 / 2^(b+1) pairs of
+// distinct hashed keys collide; b >= 2*log2(n) - 2 keeps that near one in a few
+// batches, and every collision is repaired anyway (dedup.cuh).
+uint32_t tile_group(uint64_t n_tiles) {
+  uint32_t g = kMinTileGroup;
+  while (g < kMaxTileGroup && (uint64_t)g * g < n_tiles) ++g;
+  return g;
+}
+
 SortPlan sort_plan(uint64_t n) {
   SortPlan p;
-  int idx_bits = 1;
-  while ((1ull << idx_bits) < n) ++idx_bits;
-  int log2n = idx_bits;
-  int want = (2 * log2n - 3 + 7) / 8;
-  const int room = (64 - idx_bits) / 8;
+  int log2n = 1;
+  while ((1ull << log2n) < n) ++log2n;
+  int want = (2 * log2n - 2 + 7) / 8;
   if (want < 2) want = 2;
-  if (want > room) want = room;
   if (want > kMaxPasses) want = kMaxPasses;
   p.n_pass = want;
-  p.idx_bits = idx_bits;
   p.low_shift = 64 - 8 * want;
+  p.group = tile_group((n + kSortTile - 1) / kSortTile);
   return p;
+}
+
+unsigned grid_for(uint64_t work_items, uint64_t items_per_block, unsigned max_blocks) {
+  uint64_t b = (work_items + items_per_block - 1) / items_per_block;
+  if (b < 1) b = 1;
+  return (unsigned)(b < max_blocks ? b : max_blocks);
 }
 
 int lanes_per_row(uint32_t dim) {
@@ -133,7 +151,7 @@ struct hps_table {
   char* ws;
   WorkspaceLayout wl;
   int lpr;
-  uint32_t epoch;      // serial number of the pull (look-back status words carry it)
+  uint64_t serial;     // number of pulls so far (status words carry it modulo kEpochMod)
   bool pulled;
   uint64_t last_n_keys, last_n_bags;
 
@@ -164,21 +182,20 @@ void stage_mark(hps_table* t, int stage, hipStream_t s) {
 template <int LPR>
 static void launch_pool(hps_table* t, const int32_t* d_offsets, uint32_t n_bags, float* d_pooled,
                         hipStream_t s) {
-  const unsigned blocks = (unsigned)(((uint64_t)n_bags * LPR + kPoolThreads - 1) / kPoolThreads);
-  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, d_offsets, n_bags,
+  const unsigned blocks = grid_for(n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
+  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, d_offsets, n_bags, (u32)t->last_n_keys,
                                                  t->w<i32>(t->wl.inverse), t->w<u32>(t->wl.rows),
-                                                 d_pooled, t->w<i32>(t->wl.bag_of));
+                                                 d_pooled);
 }
 
 template <int LPR>
 static void launch_push(hps_table* t, const PushArgs& a, hipStream_t s) {
   const uint64_t n = t->last_n_keys;
-  const unsigned seg_blocks = (unsigned)((n * LPR + kPushThreads - 1) / kPushThreads);
-  const unsigned max_long = (unsigned)(n / kLongSeg + 1);
-  const unsigned max_items = (unsigned)(n / kChunk + max_long + 1);
-  push_segments<LPR><<<seg_blocks, kPushThreads, 0, s>>>(t->view, a);
-  push_chunks<LPR><<<max_items, kPushThreads, 0, s>>>(t->view, a);
-  push_long<LPR><<<max_long, kPushThreads, 0, s>>>(t->view, a);
+  push_short<LPR><<<grid_for(n, kPushThreads / LPR, kPushShortBlocks), kPushThreads, 0, s>>>(t->view, a);
+  push_medium<LPR><<<grid_for(n / (kShortSeg + 1) + 1, kPushThreads / kWave, kPushMediumBlocks),
+                     kPushThreads, 0, s>>>(t->view, a);
+  push_chunks<LPR><<<grid_for(n / kChunk + 1, 1, kPushChunkBlocks), kPushThreads, 0, s>>>(t->view, a);
+  push_long<LPR><<<grid_for(n / (kMedSeg + 1) + 1, 1, kPushLongBlocks), kPushThreads, 0, s>>>(t->view, a);
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -265,14 +282,14 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->last_n_keys = t->last_n_bags = 0;
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
-  t->epoch = 0;
+  t->serial = 0;
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
   // look-back status words and digit histograms start at zero
-  fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.skeys - wl.ghist) / 8, 0);
-  reset_state<<<1, 1, 0, s>>>(t->view.st);
-  set_ctx_empty<<<1, 1, 0, s>>>(t->w<PullCtx>(wl.ctx), t->w<u32>(wl.seg_off));
+  fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.uniq - wl.ghist) / 8, 0);
+  reset_state<<<1, 64, 0, s>>>(t->view.st);
+  set_ctx_empty<<<1, 1, 0, s>>>(t->w<PullCtx>(wl.ctx), t->w<u32>(wl.seg_off), t->view.st);
   if (!launch_ok()) { delete t; return HPS_EDEVICE; }
   *out = t;
   return HPS_OK;
@@ -289,18 +306,19 @@ hps_status hps_destroy(hps_table* t) {
 hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_weights,
                       const float* d_acc, void* stream) {
   if (!t || (n && !d_keys) || (d_acc && !d_weights)) return HPS_EINVAL;
-  if (n >= (1ull << 31) * kProbeKeysPerBlock) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  clear_inserted<<<1, 1, 0, s>>>(t->view.st);
+  const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
   if (n) {
-    const unsigned blocks = (unsigned)((n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock);
     if (d_weights)
-      probe_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr,
-                                                     d_weights, d_acc, nullptr, nullptr, nullptr);
+      lookup_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
+                                                      d_acc, nullptr, nullptr, nullptr);
     else
-      probe_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr,
-                                                     nullptr, nullptr, nullptr, nullptr, nullptr);
+      lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
+                                                      nullptr, nullptr, nullptr, nullptr);
+    insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
+                                                    d_acc);
   }
+  commit_insert<<<1, 64, 0, s>>>(t->view.st);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
@@ -317,61 +335,75 @@ hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
   const WorkspaceLayout& L = t->wl;
   PullCtx* ctx = t->w<PullCtx>(L.ctx);
   const u32 n = (u32)n_keys;
+  t->last_n_keys = n_keys;
+  t->last_n_bags = n_bags;
 
   if (n == 0) {
-    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(L.seg_off));
-    clear_inserted<<<1, 1, 0, s>>>(t->view.st);
+    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(L.seg_off), t->view.st);
   } else {
     // a1: order the occurrences by the top bits of their keys
     stage_mark(t, HPS_STAGE_SORT, s);
-    if (++t->epoch >= (1u << 30)) {      // status words of 2^30 pulls ago could alias: start over
-      fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_state), (L.evidence - L.tile_state) / 8, 0);
-      t->epoch = 1;
-    }
+    ++t->serial;
+    const u32 epoch = (u32)(t->serial % kEpochMod) + 1;
+    if (epoch == 1 && t->serial >= kEpochMod)   // the epochs start over: forget the old words
+      fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
     const SortPlan plan = sort_plan(n);
-    u64* cur = t->w<u64>(L.elems_a);
-    u64* alt = t->w<u64>(L.elems_b);
-    u32* ghist = t->w<u32>(L.ghist) + (t->epoch & 1) * kMaxPasses * kRadix;
-    u32* ghist_next = t->w<u32>(L.ghist) + ((t->epoch + 1) & 1) * kMaxPasses * kRadix;
+    u64* kcur = t->w<u64>(L.keys_a);
+    u64* kalt = t->w<u64>(L.keys_b);
+    u32* icur = t->w<u32>(L.idx_a);
+    u32* ialt = t->w<u32>(L.idx_b);
+    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kMaxPasses * kRadix;
+    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kMaxPasses * kRadix;
     u32* tickets = t->w<u32>(L.tickets);
     const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    sort_prepare<<<n_tiles < 1024 ? n_tiles : 1024, kSortThreads, 0, s>>>(d_keys, n, plan, ghist,
-                                                                          ghist_next, tickets, ctx);
+    sort_prepare<<<n_tiles < 1024 ? n_tiles : 1024, kPrepThreads, 0, s>>>(
+        d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, (u32)n_bags,
+        t->w<i32>(L.bag_of));
     for (int p = 0; p < plan.n_pass; ++p) {
-      u64* state = t->w<u64>(L.tile_state) + (size_t)p * L.sort_tiles * kRadix;
+      u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
+      u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
       const int shift = plan.low_shift + p * kRadixBits;
-      if (p == 0)
-        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, cur, n, shift,
-                                                             plan.idx_bits, ghist, state, tickets,
-                                                             t->epoch, ctx);
-      else
-        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(nullptr, cur, alt, n, shift,
-                                                              plan.idx_bits, ghist + p * kRadix, state,
-                                                              tickets + p, t->epoch, ctx);
-      if (p > 0) { u64* tmp = cur; cur = alt; alt = tmp; }
+      if (p == 0) {
+        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, kcur, icur, n, shift,
+                                                             ghist, tile_rows, group_rows, plan.group,
+                                                             tickets, epoch, ctx);
+      } else {
+        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(kcur, icur, kalt, ialt, n, shift,
+                                                              ghist + p * kRadix, tile_rows, group_rows,
+                                                              plan.group, tickets + p, epoch, ctx);
+        u64* tk = kcur; kcur = kalt; kalt = tk;
+        u32* ti = icur; icur = ialt; ialt = ti;
+      }
     }
     stage_mark(t, HPS_STAGE_SORT, s);
-    // a1: unique keys, ranks, grouping
+    // a1: unique keys, ranks, grouping (second instance only acts after a repair)
     stage_mark(t, HPS_STAGE_UNIQUE, s);
     const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
-    u64* skeys = t->w<u64>(L.skeys);
-    detect_mixed_runs<<<head_tiles, kHeadThreads, 0, s>>>(cur, d_keys, n, plan, skeys, ctx,
-                                                          t->w<u32>(L.evidence));
-    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(cur, alt, skeys, d_keys, n, plan, ctx,
-                                             t->w<u32>(L.evidence));
-    clear_inserted<<<1, 1, 0, s>>>(t->view.st);
-    unique_emit<<<head_tiles, kHeadThreads, 0, s>>>(cur, skeys, n, plan.idx_bits,
-                                                    t->w<u64>(L.head_state), tickets + kMaxPasses,
-                                                    t->epoch, t->w<u64>(L.uniq),
-                                                    t->w<i32>(L.inverse), t->w<u32>(L.perm),
-                                                    t->w<u32>(L.seg_off), ctx, t->view.st);
+    const u32 head_group = tile_group(head_tiles);
+    u32* evidence = t->w<u32>(L.evidence);
+    unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
+        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
+        tickets + kMaxPasses, epoch,
+        t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(L.uniq), t->w<i32>(L.inverse),
+        t->w<u32>(L.bagperm), t->w<u32>(L.seg_off), ctx, evidence, t->view.st);
+    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, icur, kalt, ialt, n, plan, ctx, evidence);
+    unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
+        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
+        t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
+        tickets + kMaxPasses + 1, epoch,
+        t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(L.uniq), t->w<i32>(L.inverse),
+        t->w<u32>(L.bagperm), t->w<u32>(L.seg_off), ctx, evidence, t->view.st);
     stage_mark(t, HPS_STAGE_UNIQUE, s);
-    // a2: look up or insert every unique key
+    // a2: look up every unique key, create the missing ones
     stage_mark(t, HPS_STAGE_LOOKUP, s);
-    const unsigned probe_blocks = (n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock;
-    probe_keys<1><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
-                                                         &ctx->n_unique, t->w<u32>(L.rows), nullptr,
-                                                         nullptr, nullptr, nullptr, nullptr);
+    const unsigned probe_blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+    lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
+                                                          &ctx->n_unique, t->w<u32>(L.rows), nullptr,
+                                                          nullptr, nullptr, nullptr, nullptr);
+    insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
+                                                          &ctx->n_unique, t->w<u32>(L.rows), nullptr,
+                                                          nullptr);
+    commit_insert<<<1, 64, 0, s>>>(t->view.st);
     stage_mark(t, HPS_STAGE_LOOKUP, s);
   }
   // a3: gather rows and pool per bag
@@ -400,11 +432,11 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   const WorkspaceLayout& L = t->wl;
   PushArgs a;
   a.seg_off = t->w<u32>(L.seg_off);
-  a.perm = t->w<u32>(L.perm);
-  a.bag_of = t->w<i32>(L.bag_of);
+  a.bagperm = t->w<u32>(L.bagperm);
   a.rows = t->w<u32>(L.rows);
   a.grads = d_pooled_grads;
   a.ctx = t->w<PullCtx>(L.ctx);
+  a.med_list = t->w<u32>(L.med_list);
   a.long_list = t->w<uint2>(L.long_list);
   a.chunk_items = t->w<uint2>(L.chunk_items);
   a.partials = t->w<float>(L.partials);
@@ -439,12 +471,11 @@ hps_status hps_last_unique(hps_table* t, uint64_t* d_uniq_out, int32_t* d_invers
 hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_weights_out,
                    float* d_acc_out, uint8_t* d_found_out, void* stream) {
   if (!t || (n && (!d_keys || !d_weights_out || !d_acc_out || !d_found_out))) return HPS_EINVAL;
-  if (n >= (1ull << 31) * kProbeKeysPerBlock) return HPS_EINVAL;
   if (n == 0) return HPS_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned blocks = (unsigned)((n + kProbeKeysPerBlock - 1) / kProbeKeysPerBlock);
-  probe_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                 nullptr, d_weights_out, d_acc_out, d_found_out);
+  const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+  lookup_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
+                                                  nullptr, d_weights_out, d_acc_out, d_found_out);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
@@ -518,7 +549,7 @@ hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count) {
 
 hps_status hps_clear_error(hps_table* t, void* stream) {
   if (!t) return HPS_EINVAL;
-  clear_error<<<1, 1, 0, static_cast<hipStream_t>(stream)>>>(t->view.st);
+  clear_error<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(t->view.st);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 

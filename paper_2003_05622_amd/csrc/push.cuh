@@ -1,16 +1,20 @@
 // Gradient reduce-by-key fused with the Adagrad row update.
 //
-// The dedup left the occurrences grouped by unique key (perm / seg_off) and the
-// pooling recorded each occurrence's bag.  The gradient of a sum-pooled bag reaches
-// every occurrence unchanged, so the gradient of unique key u is the sum of
-// grads[bag_of[perm[j]]] over j in [seg_off[u], seg_off[u+1]).
+// The dedup left the occurrences grouped by unique key: seg_off[u] .. seg_off[u+1]
+// are the sorted positions of key u, and bagperm[j] is the bag of the occurrence at
+// sorted position j.  The gradient of a sum-pooled bag reaches every occurrence
+// unchanged, so the gradient of key u is the sum of grads[bagperm[j]] over its
+// positions.  Keys are handled by how often they occur:
 //
-//   push_segments   one group of LPR lanes per unique key; groups of at most
-//                   kLongSeg occurrences are reduced and updated on the spot, longer
-//                   ones are cut into chunks of kChunk occurrences and queued;
-//   push_chunks     one block per queued chunk: tree-reduced partial sum;
-//   push_long       one block per long key: sums its chunks' partials in chunk order
-//                   (tree) and updates the row.
+//   push_short    a group of LPR lanes per key; keys with at most kShortSeg
+//                 occurrences are reduced and updated on the spot, the others are
+//                 queued: up to kMedSeg occurrences on the medium list, more as
+//                 chunks of kChunk positions;
+//   push_medium   one wave per queued key: its lane groups stride over the positions,
+//                 then add up across the wave;
+//   push_chunks   one block per queued chunk: tree-reduced partial sum;
+//   push_long     one block per chunked key: sums its chunks' partials in chunk order
+//                 (tree) and updates the row.
 // Every sum has a fixed shape, so results do not depend on scheduling.
 #pragma once
 
@@ -20,17 +24,23 @@
 namespace hps {
 
 constexpr int kPushThreads = 256;
-constexpr u32 kLongSeg = 256;     // occurrences above which a key is handled by whole blocks
-constexpr u32 kChunk = 2048;      // occurrences per queued chunk
+constexpr int kPushShortBlocks = 2048;   // fixed grids: groups, waves and blocks loop
+constexpr int kPushMediumBlocks = 1024;
+constexpr int kPushChunkBlocks = 1024;
+constexpr int kPushLongBlocks = 256;
+constexpr u32 kShortSeg = 16;     // occurrences handled serially by one lane group
+constexpr u32 kMedSeg = 512;      // occurrences handled by one wave
+constexpr u32 kChunk = 1024;      // occurrences per queued chunk of a longer key
 constexpr int kMaxCols = 4;       // float4 columns per lane
+constexpr u32 kBagMask = 0x7FFFFFFFu;
 
 struct PushArgs {
   const u32* seg_off;
-  const u32* perm;
-  const i32* bag_of;
+  const u32* bagperm;
   const u32* rows;
   const float* grads;
   PullCtx* ctx;
+  u32* med_list;        // unique indices
   uint2* long_list;     // (unique index, first chunk item)
   uint2* chunk_items;   // (unique index, chunk number)
   float* partials;      // [chunk item][dim]
@@ -99,15 +109,47 @@ __device__ __forceinline__ void add_grad_row(float4* g, const float* grads, u32 
   }
 }
 
+// Adds the bag gradients of positions lo, lo+stride, ... < hi, four positions in
+// flight at a time.
 template <int LPR>
-__global__ void __launch_bounds__(kPushThreads) push_segments(TableView t, PushArgs a) {
-  const u32 u = (blockIdx.x * kPushThreads + threadIdx.x) / LPR;
+__device__ __forceinline__ void add_positions(float4* g, const PushArgs& a, u32 lo, u32 hi,
+                                              u32 stride, u32 dim, u32 sub) {
+  u32 j = lo;
+  for (; j + 3 * stride < hi; j += 4 * stride) {
+    const u32 b0 = a.bagperm[j] & kBagMask, b1 = a.bagperm[j + stride] & kBagMask;
+    const u32 b2 = a.bagperm[j + 2 * stride] & kBagMask, b3 = a.bagperm[j + 3 * stride] & kBagMask;
+    float4 t0[kMaxCols], t1[kMaxCols], t2[kMaxCols], t3[kMaxCols];
+#pragma unroll
+    for (int c = 0; c < kMaxCols; ++c) t0[c] = t1[c] = t2[c] = t3[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    add_grad_row<LPR>(t0, a.grads, b0, dim, sub);
+    add_grad_row<LPR>(t1, a.grads, b1, dim, sub);
+    add_grad_row<LPR>(t2, a.grads, b2, dim, sub);
+    add_grad_row<LPR>(t3, a.grads, b3, dim, sub);
+#pragma unroll
+    for (int c = 0; c < kMaxCols; ++c) {
+      g[c].x += (t0[c].x + t1[c].x) + (t2[c].x + t3[c].x);
+      g[c].y += (t0[c].y + t1[c].y) + (t2[c].y + t3[c].y);
+      g[c].z += (t0[c].z + t1[c].z) + (t2[c].z + t3[c].z);
+      g[c].w += (t0[c].w + t1[c].w) + (t2[c].w + t3[c].w);
+    }
+  }
+  for (; j < hi; j += stride) add_grad_row<LPR>(g, a.grads, a.bagperm[j] & kBagMask, dim, sub);
+}
+
+template <int LPR>
+__global__ void __launch_bounds__(kPushThreads) push_short(TableView t, PushArgs a) {
   const u32 sub = threadIdx.x % LPR;
-  if (u >= a.ctx->n_unique) return;
   if (load_error(t.st) != 0) return;
+  const u32 n_unique = a.ctx->n_unique;
+  const u32 n_groups = gridDim.x * (kPushThreads / LPR);
+  for (u32 u = (blockIdx.x * kPushThreads + threadIdx.x) / LPR; u < n_unique; u += n_groups) {
   const u32 lo = a.seg_off[u], hi = a.seg_off[u + 1];
   const u32 len = hi - lo;
-  if (len > kLongSeg) {
+  if (len > kShortSeg) {
+    if (len <= kMedSeg) {
+      if (sub == 0) a.med_list[atomicAdd(&a.ctx->n_medium, 1u)] = u;
+      continue;
+    }
     const u32 n_chunks = (len + kChunk - 1) / kChunk;
     u32 base = 0;
     if (sub == 0) {
@@ -116,15 +158,44 @@ __global__ void __launch_bounds__(kPushThreads) push_segments(TableView t, PushA
     }
     base = __shfl(base, (int)(lane_id() - sub), kWave);
     for (u32 c = sub; c < n_chunks; c += LPR) a.chunk_items[base + c] = make_uint2(u, c);
-    return;
+    continue;
   }
   const u32 r = a.rows[u];
-  if (r == kNoRow) return;
+  if (r == kNoRow) continue;
   float4 g[kMaxCols];
 #pragma unroll
   for (int c = 0; c < kMaxCols; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (u32 j = lo; j < hi; ++j) add_grad_row<LPR>(g, a.grads, (u32)a.bag_of[a.perm[j]], t.dim, sub);
+  add_positions<LPR>(g, a, lo, hi, 1, t.dim, sub);
   adagrad_row<LPR>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+  }
+}
+
+template <int LPR>
+__global__ void __launch_bounds__(kPushThreads) push_medium(TableView t, PushArgs a) {
+  constexpr u32 kGroups = kWave / LPR;
+  if (load_error(t.st) != 0) return;
+  const u32 n_medium = a.ctx->n_medium;
+  const u32 n_waves = gridDim.x * (kPushThreads / kWave);
+  const u32 group = lane_id() / LPR, sub = lane_id() % LPR;
+  for (u32 m = (blockIdx.x * kPushThreads + threadIdx.x) / kWave; m < n_medium; m += n_waves) {
+  const u32 u = a.med_list[m];
+  float4 g[kMaxCols];
+#pragma unroll
+  for (int c = 0; c < kMaxCols; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+  add_positions<LPR>(g, a, a.seg_off[u] + group, a.seg_off[u + 1], kGroups, t.dim, sub);
+#pragma unroll
+  for (int c = 0; c < kMaxCols; ++c) {
+#pragma unroll
+    for (int d = LPR; d < kWave; d <<= 1) {
+      g[c].x += __shfl_xor(g[c].x, d, kWave);
+      g[c].y += __shfl_xor(g[c].y, d, kWave);
+      g[c].z += __shfl_xor(g[c].z, d, kWave);
+      g[c].w += __shfl_xor(g[c].w, d, kWave);
+    }
+  }
+  const u32 r = a.rows[u];
+  if (group == 0 && r != kNoRow) adagrad_row<LPR>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+  }
 }
 
 // Sums, over the kPushThreads/LPR groups of the block, the float4 columns each
@@ -153,18 +224,17 @@ template <int LPR>
 __global__ void __launch_bounds__(kPushThreads) push_chunks(TableView t, PushArgs a) {
   __shared__ float4 lds[kPushThreads];
   constexpr int kGroups = kPushThreads / LPR;
-  const u32 item = blockIdx.x;
-  if (item >= a.ctx->n_chunk_items) return;
   if (load_error(t.st) != 0) return;
-  const uint2 it = a.chunk_items[item];
+  const u32 n_items = a.ctx->n_chunk_items;
   const u32 group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+  for (u32 item = blockIdx.x; item < n_items; item += gridDim.x) {
+  const uint2 it = a.chunk_items[item];
   const u32 lo = a.seg_off[it.x] + it.y * kChunk;
   const u32 hi = min(lo + kChunk, a.seg_off[it.x + 1]);
   float4 g[kMaxCols];
 #pragma unroll
   for (int c = 0; c < kMaxCols; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (u32 j = lo + group; j < hi; j += kGroups)
-    add_grad_row<LPR>(g, a.grads, (u32)a.bag_of[a.perm[j]], t.dim, sub);
+  add_positions<LPR>(g, a, lo + group, hi, kGroups, t.dim, sub);
   block_tree_sum<LPR>(g, lds, t.dim >> 2);
   if (group == 0) {
     float4* out = reinterpret_cast<float4*>(a.partials + (u64)item * t.dim);
@@ -172,16 +242,18 @@ __global__ void __launch_bounds__(kPushThreads) push_chunks(TableView t, PushArg
     for (int c = 0; c < kMaxCols; ++c)
       if (sub + c * LPR < (t.dim >> 2)) out[sub + c * LPR] = g[c];
   }
+  }
 }
 
 template <int LPR>
 __global__ void __launch_bounds__(kPushThreads) push_long(TableView t, PushArgs a) {
   __shared__ float4 lds[kPushThreads];
   constexpr int kGroups = kPushThreads / LPR;
-  if (blockIdx.x >= a.ctx->n_long) return;
   if (load_error(t.st) != 0) return;
-  const uint2 seg = a.long_list[blockIdx.x];
+  const u32 n_long = a.ctx->n_long;
   const u32 group = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+  for (u32 l = blockIdx.x; l < n_long; l += gridDim.x) {
+  const uint2 seg = a.long_list[l];
   const u32 len = a.seg_off[seg.x + 1] - a.seg_off[seg.x];
   const u32 n_chunks = (len + kChunk - 1) / kChunk;
   float4 g[kMaxCols];
@@ -192,6 +264,7 @@ __global__ void __launch_bounds__(kPushThreads) push_long(TableView t, PushArgs 
   block_tree_sum<LPR>(g, lds, t.dim >> 2);
   const u32 r = a.rows[seg.x];
   if (group == 0 && r != kNoRow) adagrad_row<LPR>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+  }
 }
 
 }  // namespace hps

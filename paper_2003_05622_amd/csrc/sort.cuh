@@ -1,23 +1,31 @@
 // Key dedup, part 1: ordering the key occurrences.
 //
-// Each occurrence i becomes one 64-bit element: the key's high bits with the
-// occurrence index in the low `idx_bits` bits (idx_bits = bits needed for N).
-// Elements are sorted by their top `8 * n_pass` bits with a stable
-// least-significant-digit radix sort, 8 bits per pass, ONE kernel per pass:
+// The occurrences (key, index) are sorted by the keys' top `8 * n_pass` bits with a
+// stable least-significant-digit radix sort, 8 bits per pass, ONE kernel per pass:
 //
-//   sort_prepare    digit histograms of all passes in one read of the keys
-//   onesweep_pass   a tile takes a ticket, ranks its elements with wave ballots,
-//                   obtains the number of same-digit elements in earlier tiles by
-//                   decoupled look-back over per-tile status words, stages the tile
-//                   in LDS and writes each digit's run contiguously.
+//   sort_prepare    digit histograms of all passes in one read of the keys (also
+//                   writes bag_of[i], the bag of occurrence i);
+//   onesweep_pass   a tile takes a ticket and counts its digits; an extra wave then
+//                   publishes the counts and obtains, by decoupled look-back over the
+//                   per-tile status words, how many same-digit elements earlier tiles
+//                   hold, while the three worker waves rank the tile's elements with
+//                   wave ballots; the tile is staged in LDS and each digit's run is
+//                   written contiguously.
 //
 // Mini-batch keys are hashed feature ids, so the top 8*n_pass bits separate
 // almost all distinct keys; the rare runs that still mix different keys are
 // found and put right afterwards (dedup.cuh), so the result is exact for any input.
 //
-// Look-back status word (64-bit): epoch << 34 | flag << 32 | count.  The epoch is
-// the pull's serial number, so words of earlier pulls read as "not ready" and
-// nothing has to be cleared between pulls.
+// Cross-tile counts without a serial chain: tiles are grouped, `group` consecutive
+// tiles (by ticket) per group.  Every tile publishes its digit counts (a row of 256
+// status words); the last tile of a group also publishes the group's counts.  A tile
+// then needs the rows of the earlier tiles of its own group and the rows of all
+// earlier groups: two dependent waits however many tiles there are.  A tile only ever
+// waits for tiles with smaller tickets, which are running, so the waits end.
+//
+// Status word (32-bit): epoch << 20 | count.  The epoch (1..4095) is the pull's serial
+// number modulo 4095, so words of earlier pulls read as "not ready"; the host clears
+// the words each time the epoch wraps.
 #pragma once
 
 #include "common.cuh"
@@ -27,34 +35,107 @@ namespace hps {
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
 constexpr int kMaxPasses = 8;
-constexpr int kSortThreads = 256;
-constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kSortItems = 16;                         // per thread
-constexpr int kSortTile = kSortThreads * kSortItems;   // 4096 elements
+constexpr int kSortThreads = 256;                      // three worker waves + the look-back wave
+constexpr int kSortWorkers = kSortThreads - kWave;     // threads that hold elements
+constexpr int kSortWaves = kSortWorkers / kWave;
+constexpr int kSortItems = 16;                         // per worker thread
+constexpr int kSortTile = kSortWorkers * kSortItems;   // 3072 elements
 constexpr int kSortWaveSpan = kWave * kSortItems;      // 1024 consecutive elements per wave
+constexpr int kPrepThreads = 256;
 
-constexpr u64 kFlagAggregate = 1;   // count of this tile only
-constexpr u64 kFlagInclusive = 2;   // count of this tile and all earlier tiles
-constexpr u32 kSpinLimit = 1u << 26;
+constexpr u32 kSpinLimit = 1u << 22;
+constexpr u32 kEpochMod = 4095;        // epochs run 1..4095
+constexpr u32 kMaxTileGroup = 64;      // tiles per group at most (count fits 19 bits)
+constexpr int kLookChunk = 8;          // status rows read per round trip
+
+static_assert(kRadix == kSortThreads, "thread d owns digit d");
+static_assert(kRadix == 4 * kWave, "each look-back lane owns four digits");
 
 struct SortPlan {
   int n_pass;       // digits sorted
-  int idx_bits;     // low bits of an element that hold the occurrence index
   int low_shift;    // 64 - 8 * n_pass: position of the least significant sorted digit
+  u32 group;        // tiles per group
 };
 
-__device__ __forceinline__ u64 make_elem(u64 key, u32 i, int idx_bits) {
-  return ((key >> idx_bits) << idx_bits) | (u64)i;
-}
-__device__ __forceinline__ u32 elem_idx(u64 e, int idx_bits) {
-  return (u32)(e & ((1ull << idx_bits) - 1));
-}
-__device__ __forceinline__ u32 elem_digit(u64 e, int shift) {
-  return (u32)(e >> shift) & (kRadix - 1);
+__device__ __forceinline__ u32 key_digit(u64 k, int shift) {
+  return (u32)(k >> shift) & (kRadix - 1);
 }
 
-__device__ __forceinline__ u64 state_word(u32 epoch, u64 flag, u32 count) {
-  return ((u64)epoch << 34) | (flag << 32) | count;
+// ---- status words -------------------------------------------------------------------
+__device__ __forceinline__ u32 status_word(u32 epoch, u32 count) { return (epoch << 20) | count; }
+__device__ __forceinline__ bool status_ready(u32 w, u32 epoch) { return (w >> 20) == epoch; }
+__device__ __forceinline__ u32 status_count(u32 w) { return w & 0xFFFFFu; }
+
+// A lane's four consecutive status words (16 bytes) as two 64-bit device-scope
+// accesses.  Every 32-bit word is valid on its own, so nothing orders them.
+__device__ __forceinline__ void store_row4(u32* row, u32 lane, u32 epoch, const u32* count) {
+  u64* p = reinterpret_cast<u64*>(row + 4 * lane);
+  __hip_atomic_store(p, (u64)status_word(epoch, count[0]) | ((u64)status_word(epoch, count[1]) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(p + 1, (u64)status_word(epoch, count[2]) | ((u64)status_word(epoch, count[3]) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void load_row4(const u32* row, u32 lane, u32* w) {
+  const u64* p = reinterpret_cast<const u64*>(row + 4 * lane);
+  const u64 a = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const u64 b = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  w[0] = (u32)a; w[1] = (u32)(a >> 32); w[2] = (u32)b; w[3] = (u32)(b >> 32);
+}
+
+// Adds to sum[0..3] this lane's digits of rows [first, last) of `rows` (kRadix words
+// per row), waiting for each row to be published.  Returns false if a wait gave up.
+__device__ __forceinline__ bool sum_rows(const u32* rows, u32 first, u32 last, u32 lane, u32 epoch,
+                                         u32* sum) {
+  for (u32 r0 = first; r0 < last; r0 += kLookChunk) {
+    u32 spins = 0;
+    while (true) {
+      u32 w[kLookChunk][4];
+#pragma unroll
+      for (int k = 0; k < kLookChunk; ++k) {
+        if (r0 + k < last) {
+          load_row4(rows + (u64)(r0 + k) * kRadix, lane, w[k]);
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) w[k][q] = status_word(epoch, 0);
+        }
+      }
+      bool ready = true;
+#pragma unroll
+      for (int k = 0; k < kLookChunk; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) ready = ready && status_ready(w[k][q], epoch);
+      if (ready) {
+#pragma unroll
+        for (int k = 0; k < kLookChunk; ++k)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) sum[q] += status_count(w[k][q]);
+        break;
+      }
+      if (++spins > kSpinLimit) return false;   // never expected
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+  return true;
+}
+
+// Wave-wide sum of the counts in words[first, last) (one status word each), waiting
+// for every word to be published.  All lanes get the sum; *ok is cleared if a wait
+// gave up.
+__device__ __forceinline__ u32 wave_sum_words(const u32* words, u32 first, u32 last, u32 lane,
+                                              u32 epoch, bool* ok) {
+  u32 c = 0;
+  for (u32 r = first + lane; r < last; r += kWave) {
+    u32 spins = 0;
+    while (true) {
+      const u32 w = __hip_atomic_load(words + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (status_ready(w, epoch)) { c += status_count(w); break; }
+      if (++spins > kSpinLimit) { *ok = false; break; }   // never expected
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
+  return c;
 }
 
 // Number of lanes of the wave (among `valid` ones) whose digit equals this lane's,
@@ -71,24 +152,48 @@ __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* befo
   *count = __popcll(same);
 }
 
-// Histograms of every pass's digit over all keys; also resets what the passes need.
+// Histograms of every pass's digit over all keys; also resets what the passes need
+// and writes bag_of[i] (a wave takes 64 bags at a time; bags of more than 8
+// occurrences are filled by the whole wave).
 //   ghist      [kMaxPasses][kRadix] of this pull (zero on entry), ghist_next the
 //              buffer the next pull will use (cleared here)
-//   tickets    [kMaxPasses + 1] tile tickets of the passes and of the unique scan
-__global__ void __launch_bounds__(kSortThreads)
+//   tickets    [kMaxPasses + 2] tile tickets of the passes and of the two unique scans
+__global__ void __launch_bounds__(kPrepThreads)
 sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict__ ghist,
-             u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx) {
+             u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx,
+             const i32* __restrict__ offsets, u32 n_bags, i32* __restrict__ bag_of) {
   __shared__ u32 h[kMaxPasses][kRadix];
-  for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kSortThreads) (&h[0][0])[i] = 0;
+  for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) (&h[0][0])[i] = 0;
   if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kSortThreads) ghist_next[i] = 0;
-    if (threadIdx.x <= kMaxPasses) tickets[threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) ghist_next[i] = 0;
+    if (threadIdx.x < kMaxPasses + 2) tickets[threadIdx.x] = 0;
     if (threadIdx.x == 0) {
       ctx->n_unique = 0;
       ctx->n_long = 0;
+      ctx->n_medium = 0;
       ctx->n_chunk_items = 0;
       ctx->n_evidence = 0;
       ctx->sort_error = 0;
+    }
+  }
+  {
+    const u32 wave_global = (blockIdx.x * kPrepThreads + threadIdx.x) / kWave;
+    const u32 n_waves = gridDim.x * (kPrepThreads / kWave);
+    for (u32 b0 = wave_global * kWave; b0 < n_bags; b0 += n_waves * kWave) {
+      const u32 b = b0 + lane_id();
+      i32 lo = 0, hi = 0;
+      if (b < n_bags) { lo = offsets[b]; hi = offsets[b + 1]; }
+      lo = max(lo, 0);
+      hi = min(hi, (i32)n);          // never write outside bag_of, whatever the offsets say
+      const bool big = hi - lo > 8;
+      if (!big) for (i32 i = lo; i < hi; ++i) bag_of[i] = (i32)b;
+      u64 todo = __ballot(big);
+      while (todo) {
+        const int src = __ffsll((unsigned long long)todo) - 1;
+        todo &= todo - 1;
+        const i32 blo = __shfl(lo, src, kWave), bhi = __shfl(hi, src, kWave);
+        for (i32 i = blo + (i32)lane_id(); i < bhi; i += kWave) bag_of[i] = (i32)(b0 + src);
+      }
     }
   }
   __syncthreads();
@@ -96,80 +201,112 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
   for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const u32 base = tile * kSortTile;
 #pragma unroll 4
-    for (int k = 0; k < kSortItems; ++k) {
-      const u32 i = base + k * kSortThreads + threadIdx.x;
+    for (int k = 0; k < kSortTile / kPrepThreads; ++k) {
+      const u32 i = base + k * kPrepThreads + threadIdx.x;
       if (i < n) {
         const u64 key = keys[i];
         for (int p = 0; p < plan.n_pass; ++p)
-          atomicAdd(&h[p][(u32)(key >> (plan.low_shift + p * kRadixBits)) & (kRadix - 1)], 1u);
+          atomicAdd(&h[p][key_digit(key, plan.low_shift + p * kRadixBits)], 1u);
       }
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < plan.n_pass * kRadix; i += kSortThreads) {
+  for (int i = threadIdx.x; i < plan.n_pass * kRadix; i += kPrepThreads) {
     const u32 c = (&h[0][0])[i];
     if (c) atomicAdd(&ghist[i], c);
   }
 }
 
-// One stable radix pass.  FIRST: elements are built from the keys; otherwise read
-// from `in`.  `ghist` is this pass's global digit histogram, `state` this pass's
-// [n_tiles][kRadix] status words.
+// One stable radix pass over (key, idx) pairs.  FIRST: idx is the position itself
+// and is not read.  `ghist` is this pass's global digit histogram; tile_rows
+// [n_tiles][kRadix] and group_rows [n_groups][kRadix] are this pass's status words.
 template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads)
-onesweep_pass(const u64* __restrict__ keys, const u64* __restrict__ in, u64* __restrict__ out,
-              u32 n, int shift, int idx_bits, const u32* __restrict__ ghist,
-              u64* __restrict__ state, u32* __restrict__ ticket, u32 epoch,
+onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
+              u64* __restrict__ keys_out, u32* __restrict__ idx_out, u32 n, int shift,
+              const u32* __restrict__ ghist, u32* __restrict__ tile_rows,
+              u32* __restrict__ group_rows, u32 group, u32* __restrict__ ticket, u32 epoch,
               PullCtx* __restrict__ ctx) {
+  __shared__ u32 tile_hist[kRadix];              // digit counts of the tile
+  __shared__ u32 earlier[kRadix];                // same-digit elements in earlier tiles
   __shared__ u32 wave_cnt[kSortWaves][kRadix];   // per-wave digit counts, then wave offsets
   __shared__ u32 local_start[kRadix];            // first staged position of each digit
   __shared__ u32 out_base[kRadix];               // global position of the digit's run - local_start
   __shared__ u32 scratch[kSortThreads / kWave + 1];
   __shared__ u32 s_tile;
-  __shared__ u64 stage[kSortTile];
+  __shared__ u64 stage[kSortTile];               // keys first, then (as u32) the indices
 
   const u32 tid = threadIdx.x;
+  const bool worker = tid < kSortWorkers;
   if (tid == 0) s_tile = atomicAdd(ticket, 1u);
   for (int d = tid; d < kSortWaves * kRadix; d += kSortThreads) (&wave_cnt[0][0])[d] = 0;
+  tile_hist[tid] = 0;
   __syncthreads();
   const u32 tile = s_tile;
   const u32 wave = tid / kWave, lane = tid & (kWave - 1);
-  volatile u32* cnt = &wave_cnt[wave][0];
-
   const u32 tile_base = tile * kSortTile;
   const u32 tile_n = min((u32)kSortTile, n - tile_base);
   const u32 wave_base = tile_base + wave * kSortWaveSpan;
-  const u64 lt = lanemask_lt();
 
-  u64 e[kSortItems];
+  u64 key[kSortItems];
+  u32 idx[kSortItems];
   u32 rank[kSortItems];
+  if (worker) {
 #pragma unroll
-  for (int r = 0; r < kSortItems; ++r) {
-    const u32 i = wave_base + r * kWave + lane;
-    if (FIRST)
-      e[r] = (i < n) ? make_elem(keys[i], i, idx_bits) : ~0ull;
-    else
-      e[r] = (i < n) ? in[i] : ~0ull;
-  }
-  // Rank each element among the wave's earlier elements with the same digit
-  // (element order inside a wave: round by round, then by lane).
+    for (int r = 0; r < kSortItems; ++r) {
+      const u32 i = wave_base + r * kWave + lane;
+      key[r] = (i < n) ? keys_in[i] : ~0ull;
+      idx[r] = FIRST ? i : ((i < n) ? idx_in[i] : 0u);
+    }
 #pragma unroll
-  for (int r = 0; r < kSortItems; ++r) {
-    const u32 i = wave_base + r * kWave + lane;
-    const bool valid = i < n;
-    const u32 d = elem_digit(e[r], shift);
-    u32 before, same;
-    match_digit(d, valid, lt, &before, &same);
-    u32 old = 0;
-    if (valid) old = cnt[d];
-    __builtin_amdgcn_wave_barrier();
-    if (valid && before == 0) cnt[d] = old + same;
-    __builtin_amdgcn_wave_barrier();
-    rank[r] = old + before;
+    for (int r = 0; r < kSortItems; ++r) {
+      const u32 i = wave_base + r * kWave + lane;
+      if (i < n) atomicAdd(&tile_hist[key_digit(key[r], shift)], 1u);
+    }
   }
   __syncthreads();
 
-  // Thread d owns digit d: the tile's count, the waves' offsets inside the run.
+  if (!worker) {
+    // Look-back wave: lane l owns digits 4l .. 4l+3.
+    u32 mine[4], sum[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) mine[q] = tile_hist[4 * lane + q];
+    store_row4(tile_rows + (u64)tile * kRadix, lane, epoch, mine);
+    const u32 g = tile / group;
+    bool ok = sum_rows(tile_rows, g * group, tile, lane, epoch, sum);   // earlier tiles of my group
+    if (tile % group == group - 1) {                                    // last of the group
+      u32 total[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) total[q] = sum[q] + mine[q];
+      store_row4(group_rows + (u64)g * kRadix, lane, epoch, total);
+    }
+    ok = sum_rows(group_rows, 0, g, lane, epoch, sum) && ok;            // all earlier groups
+    if (!ok) ctx->sort_error = 1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) earlier[4 * lane + q] = sum[q];
+  } else {
+    // Workers: rank each element among the wave's earlier elements with the same
+    // digit (element order inside a wave: round by round, then by lane).
+    volatile u32* cnt = &wave_cnt[wave][0];
+    const u64 lt = lanemask_lt();
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+      const u32 i = wave_base + r * kWave + lane;
+      const bool valid = i < n;
+      const u32 d = key_digit(key[r], shift);
+      u32 before, same;
+      match_digit(d, valid, lt, &before, &same);
+      u32 old = 0;
+      if (valid) old = cnt[d];
+      __builtin_amdgcn_wave_barrier();
+      if (valid && before == 0) cnt[d] = old + same;
+      __builtin_amdgcn_wave_barrier();
+      rank[r] = old + before;
+    }
+  }
+  __syncthreads();
+
+  // Thread d owns digit d: the waves' offsets inside the run, the run's place.
   u32 digit_total = 0;
 #pragma unroll
   for (int w = 0; w < kSortWaves; ++w) {
@@ -177,55 +314,55 @@ onesweep_pass(const u64* __restrict__ keys, const u64* __restrict__ in, u64* __r
     wave_cnt[w][tid] = digit_total;
     digit_total += c;
   }
-  // Publish, then look back over earlier tiles for the same digit.
-  u64* my_state = state + (u64)tile * kRadix + tid;
-  u32 earlier = 0;
-  if (tile == 0) {
-    __hip_atomic_store(my_state, state_word(epoch, kFlagInclusive, digit_total), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-  } else {
-    __hip_atomic_store(my_state, state_word(epoch, kFlagAggregate, digit_total), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-    u32 prev = tile - 1;
-    u32 spins = 0;
-    while (true) {
-      const u64 w = __hip_atomic_load(state + (u64)prev * kRadix + tid, __ATOMIC_RELAXED,
-                                      __HIP_MEMORY_SCOPE_AGENT);
-      const u64 flag = (w >> 32) & 3;
-      if ((u32)(w >> 34) != epoch || flag == 0) {
-        if (++spins > kSpinLimit) { ctx->sort_error = 1; break; }   // never expected
-        __builtin_amdgcn_s_sleep(1);
-        continue;
-      }
-      earlier += (u32)w;
-      if (flag == kFlagInclusive || prev == 0) break;
-      --prev;
-    }
-    __hip_atomic_store(my_state, state_word(epoch, kFlagInclusive, earlier + digit_total),
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
   u32 total;
   const u32 gbase = block_excl_sum<kSortThreads>(ghist[tid], scratch, &total);
   const u32 start = block_excl_sum<kSortThreads>(digit_total, scratch, &total);
   local_start[tid] = start;
-  out_base[tid] = gbase + earlier - start;
+  out_base[tid] = gbase + earlier[tid] - start;
   __syncthreads();
 
+  u32 pos[kSortItems];
+  if (worker) {
 #pragma unroll
-  for (int r = 0; r < kSortItems; ++r) {
-    const u32 i = wave_base + r * kWave + lane;
-    if (i < n) {
-      const u32 d = elem_digit(e[r], shift);
-      stage[local_start[d] + wave_cnt[wave][d] + rank[r]] = e[r];
+    for (int r = 0; r < kSortItems; ++r) {
+      const u32 i = wave_base + r * kWave + lane;
+      pos[r] = 0;
+      if (i < n) {
+        const u32 d = key_digit(key[r], shift);
+        pos[r] = local_start[d] + wave_cnt[wave][d] + rank[r];
+        stage[pos[r]] = key[r];
+      }
     }
   }
   __syncthreads();
+  u32 dest[kSortItems];
+  if (worker) {
 #pragma unroll
-  for (int k = 0; k < kSortItems; ++k) {
-    const u32 p = k * kSortThreads + tid;
-    if (p < tile_n) {
-      const u64 el = stage[p];
-      out[out_base[elem_digit(el, shift)] + p] = el;
+    for (int k = 0; k < kSortItems; ++k) {
+      const u32 p = k * kSortWorkers + tid;
+      dest[k] = 0;
+      if (p < tile_n) {
+        const u64 kk = stage[p];
+        dest[k] = out_base[key_digit(kk, shift)] + p;
+        keys_out[dest[k]] = kk;
+      }
+    }
+  }
+  __syncthreads();
+  u32* stage_idx = reinterpret_cast<u32*>(stage);
+  if (worker) {
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+      const u32 i = wave_base + r * kWave + lane;
+      if (i < n) stage_idx[pos[r]] = idx[r];
+    }
+  }
+  __syncthreads();
+  if (worker) {
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+      const u32 p = k * kSortWorkers + tid;
+      if (p < tile_n) idx_out[dest[k]] = stage_idx[p];
     }
   }
 }

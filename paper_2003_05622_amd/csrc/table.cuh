@@ -6,6 +6,13 @@
 //   keys[n_slots]            u64, kEmptyKey when free
 //   w[n_slots][dim]          f32
 //   acc[n_slots][acc_len]    f32
+//
+// Looking keys up and creating the missing ones are two kernels, so that the room
+// check against the capacity is one consistent decision and no block has to hit a
+// single counter: lookup_keys counts the missing keys into sharded counters,
+// insert_missing (every block reads the same total) claims slots only if all of
+// them fit and counts the rows it creates, commit_insert adds that count to the
+// table size.
 #pragma once
 
 #include "common.cuh"
@@ -27,9 +34,9 @@ struct TableView {
 };
 
 constexpr int kProbeThreads = 256;
-constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // keys in flight per block
-constexpr int kProbeKeysPerGroup = 4;
-constexpr int kProbeKeysPerBlock = kProbeGroups * kProbeKeysPerGroup;
+constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
+constexpr int kProbeInFlight = 4;                             // keys a group probes at a time
+constexpr int kProbeMaxBlocks = 2048;
 
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
 __device__ __forceinline__ u32 group_bits(u64 ballot) {
@@ -45,192 +52,240 @@ __global__ void __launch_bounds__(256) fill_u64(u64* __restrict__ p, u64 n, u64 
   for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (u64)gridDim.x * blockDim.x)
     p[i] = v;
 }
-__global__ void __launch_bounds__(256) fill_f32(float* __restrict__ p, u64 n, float v) {
-  for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (u64)gridDim.x * blockDim.x)
-    p[i] = v;
+__global__ void __launch_bounds__(64) reset_state(TableState* st) {
+  if (threadIdx.x == 0) {
+    st->size = 0;
+    st->inserted = 0;
+    st->error = 0;
+    st->pad = 0;
+    st->dump_count = 0;
+  }
+  if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
 }
-__global__ void reset_state(TableState* st) {
-  st->size = 0;
-  st->inserted = 0;
-  st->error = 0;
-  st->pad = 0;
-  st->dump_count = 0;
+__global__ void __launch_bounds__(64) clear_error(TableState* st) {
+  if (threadIdx.x == 0) st->error = 0;
+  if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
 }
-__global__ void clear_error(TableState* st) { st->error = 0; }
-__global__ void clear_inserted(TableState* st) { st->inserted = 0; }
 __global__ void clear_dump_count(TableState* st) { st->dump_count = 0; }
-__global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off) {
+__global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off, TableState* st) {
   ctx->n_unique = 0;
   ctx->n_long = 0;
+  ctx->n_medium = 0;
   ctx->n_chunk_items = 0;
   ctx->n_evidence = 0;
   ctx->sort_error = 0;
   seg_off[0] = 0;
+  st->inserted = 0;
 }
 
-// Look up `n_keys` keys (the count is read from *n_keys_dev when that pointer is
-// not null, so that a pull needs no host round trip for U); MODE:
-//   0  find only                       -> rows[u] = slot or kNoRow
-//   1  find or insert the initial row  -> rows[u] = slot (kNoRow if the table is full)
-//   2  insert/overwrite given values   -> rows[u] = slot
-//   3  find and copy the row out        -> w_out[u], acc_out[u], found_out[u]
-// In modes 1 and 2 the keys handed to one block's groups are first looked up, the
-// block then reserves room for all its missing keys with ONE atomic add on the
-// table size, and only then claims slots.
+// Adds the rows insert_missing created to the table size and clears the counters.
+__global__ void __launch_bounds__(64) commit_insert(TableState* st) {
+  u32 made = threadIdx.x < kCountShards ? st->made_shard[threadIdx.x] : 0;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) made += __shfl_xor(made, d, kWave);
+  if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
+  if (threadIdx.x == 0) {
+    st->size += made;
+    st->inserted = made;
+  }
+}
+
+// Walks key's probe sequence from `line` on.  Returns the slot of the key, or
+// kNoRow with `line` left at the first line that has a free slot (slot_key holds
+// this lane's slot of that line).  All 8 lanes of the group call it together.
+__device__ __forceinline__ u32 probe_find(const TableView& t, u64 key, u32 sub, u64& line,
+                                          u64& slot_key) {
+  for (u64 step = 0; step < t.n_lines; ++step) {
+    const u32 hit = group_bits(__ballot(slot_key == key));
+    if (hit) return (u32)(line * kSlotsPerLine + (__ffs(hit) - 1));
+    if (group_bits(__ballot(slot_key == kEmptyKey))) return kNoRow;
+    line = line + 1 == t.n_lines ? 0 : line + 1;
+    slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);
+  }
+  return kNoRow;
+}
+
+// Finds the key or claims a free slot for it.  *created tells which.
+__device__ __forceinline__ u32 probe_find_or_claim(const TableView& t, u64 key, u32 sub, u64 line,
+                                                   u64 slot_key, bool* created) {
+  *created = false;
+  for (u64 step = 0; step < 2 * t.n_lines; ++step) {
+    const u32 hit = group_bits(__ballot(slot_key == key));
+    if (hit) return (u32)(line * kSlotsPerLine + (__ffs(hit) - 1));
+    const u32 free_slots = group_bits(__ballot(slot_key == kEmptyKey));
+    if (free_slots) {
+      const u32 target = __ffs(free_slots) - 1;
+      u64 seen = 0;
+      if (sub == target)
+        seen = atomicCAS((unsigned long long*)&t.keys[line * kSlotsPerLine + target],
+                         (unsigned long long)kEmptyKey, (unsigned long long)key);
+      seen = __shfl(seen, (int)((lane_id() & ~7u) + target), kWave);
+      if (seen == kEmptyKey) { *created = true; return (u32)(line * kSlotsPerLine + target); }
+      if (seen == key) return (u32)(line * kSlotsPerLine + target);
+      slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);   // another key took it
+      continue;
+    }
+    line = line + 1 == t.n_lines ? 0 : line + 1;
+    slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);
+  }
+  return kNoRow;
+}
+
+// MODE 0  pull: rows[u] = slot or kNoRow, missing keys counted
+// MODE 1  bulk insert, initial rows: missing keys counted, nothing written
+// MODE 2  bulk insert with values: present keys overwritten, missing keys counted
+// MODE 3  get: copy the row out, found flags
+// n_keys is read from *n_keys_dev when that pointer is not null (the pull's U lives
+// on the device).
 template <int MODE>
 __global__ void __launch_bounds__(kProbeThreads)
-probe_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
-           const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
-           const float* __restrict__ w_in, const float* __restrict__ acc_in,
-           float* __restrict__ w_out, float* __restrict__ acc_out,
-           uint8_t* __restrict__ found_out) {
-  __shared__ u32 s_need;
-  __shared__ int s_ok;
+lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
+            const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
+            const float* __restrict__ w_in, const float* __restrict__ acc_in,
+            float* __restrict__ w_out, float* __restrict__ acc_out,
+            uint8_t* __restrict__ found_out) {
+  __shared__ u32 s_missing;
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
-  const u64 block_first = (u64)blockIdx.x * kProbeKeysPerBlock;
-  if (block_first >= n_keys) return;
   if (load_error(t.st) != 0) return;
-  if (threadIdx.x == 0) { s_need = 0; s_ok = 1; }
+  if (threadIdx.x == 0) s_missing = 0;
   __syncthreads();
-
   const u32 sub = threadIdx.x & 7;
-  const u32 group = threadIdx.x >> 3;
-  u64 key[kProbeKeysPerGroup];
-  u64 line[kProbeKeysPerGroup];
-  u64 slot_key[kProbeKeysPerGroup];
-  u32 row[kProbeKeysPerGroup];
-  bool live[kProbeKeysPerGroup];
-
-#pragma unroll
-  for (int k = 0; k < kProbeKeysPerGroup; ++k) {
-    const u64 u = block_first + (u64)k * kProbeGroups + group;
-    live[k] = u < n_keys;
-    key[k] = live[k] ? keys[u] : 0;
-    line[k] = __umul64hi(slot_hash(key[k]), t.n_lines);
-    row[k] = kNoRow;
-    slot_key[k] = live[k] ? load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]) : 0;
-  }
-
-  // Phase 1: walk each key's probe sequence to its match or to the first line with a free slot.
+  const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
+  const u64 n_groups = (u64)gridDim.x * kProbeGroups;
   u32 missing = 0;
+  for (u64 u0 = group; u0 < n_keys; u0 += n_groups * kProbeInFlight) {
+    u64 key[kProbeInFlight], line[kProbeInFlight], slot_key[kProbeInFlight];
 #pragma unroll
-  for (int k = 0; k < kProbeKeysPerGroup; ++k) {
-    if (!live[k]) continue;
-    if (key[k] == kEmptyKey) { raise_error(t.st, kErrReserved); live[k] = false; continue; }
-    for (u64 step = 0; step < t.n_lines; ++step) {
-      const u32 hit = group_bits(__ballot(slot_key[k] == key[k]));
-      if (hit) { row[k] = (u32)(line[k] * kSlotsPerLine + (__ffs(hit) - 1)); break; }
-      const u32 free_slots = group_bits(__ballot(slot_key[k] == kEmptyKey));
-      if (free_slots) break;
-      line[k] = line[k] + 1 == t.n_lines ? 0 : line[k] + 1;
-      slot_key[k] = load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]);
+    for (int k = 0; k < kProbeInFlight; ++k) {
+      const u64 u = u0 + (u64)k * n_groups;
+      key[k] = u < n_keys ? keys[u] : 0;
+      line[k] = __umul64hi(slot_hash(key[k]), t.n_lines);
     }
-    if (row[k] == kNoRow) ++missing;
-  }
-
-  if (MODE == 1 || MODE == 2) {
-    if (sub == 0 && missing) atomicAdd(&s_need, missing);
-    __syncthreads();
-    if (threadIdx.x == 0 && s_need) {
-      const unsigned long long before = atomicAdd(&t.st->size, (unsigned long long)s_need);
-      if (before + s_need > t.capacity) {
-        atomicAdd(&t.st->size, (unsigned long long)(-(long long)s_need));
-        raise_error(t.st, kErrFull);
-        s_ok = 0;
-      } else {
-        atomicAdd(&t.st->inserted, (unsigned long long)s_need);
+#pragma unroll
+    for (int k = 0; k < kProbeInFlight; ++k) {
+      const u64 u = u0 + (u64)k * n_groups;
+      slot_key[k] = u < n_keys ? load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]) : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kProbeInFlight; ++k) {
+      const u64 u = u0 + (u64)k * n_groups;
+      if (u >= n_keys) continue;
+      if (key[k] == kEmptyKey) {
+        if (MODE != 3) raise_error(t.st, kErrReserved);
+        if (MODE == 3 && sub == 0) found_out[u] = 0;
+        if (MODE == 0 && sub == 0) rows[u] = kNoRow;
+        continue;
       }
-    }
-    __syncthreads();
-
-    // Phase 2: claim a slot for each missing key.
-#pragma unroll
-    for (int k = 0; k < kProbeKeysPerGroup; ++k) {
-      if (!live[k] || row[k] != kNoRow || !s_ok) continue;
-      bool created = false;
-      for (u64 step = 0; step < 2 * t.n_lines; ++step) {
-        const u32 hit = group_bits(__ballot(slot_key[k] == key[k]));
-        if (hit) { row[k] = (u32)(line[k] * kSlotsPerLine + (__ffs(hit) - 1)); break; }
-        const u32 free_slots = group_bits(__ballot(slot_key[k] == kEmptyKey));
-        if (free_slots) {
-          const u32 target = __ffs(free_slots) - 1;
-          u64 seen = 0;
-          if (sub == target)
-            seen = atomicCAS((unsigned long long*)&t.keys[line[k] * kSlotsPerLine + target],
-                             (unsigned long long)kEmptyKey, (unsigned long long)key[k]);
-          seen = __shfl(seen, (lane_id() & ~7u) + target, kWave);
-          if (seen == kEmptyKey) {
-            row[k] = (u32)(line[k] * kSlotsPerLine + target);
-            created = true;
-            break;
-          }
-          if (seen == key[k]) { row[k] = (u32)(line[k] * kSlotsPerLine + target); break; }
-          // another key took the slot: look at the line again
-          slot_key[k] = load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]);
-          continue;
+      const u32 row = probe_find(t, key[k], sub, line[k], slot_key[k]);
+      if (row == kNoRow && MODE != 3) ++missing;
+      if (MODE == 0 && sub == 0) rows[u] = row;
+      if (MODE == 2 && row != kNoRow) {
+        float* wr = t.w + (u64)row * t.dim;
+        for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
+        float* ar = t.acc + (u64)row * t.acc_len;
+        for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = acc_in ? acc_in[u * t.acc_len + j] : t.init_acc;
+      }
+      if (MODE == 3) {
+        if (sub == 0) found_out[u] = row != kNoRow;
+        if (row != kNoRow) {
+          const float* wr = t.w + (u64)row * t.dim;
+          for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = wr[j];
+          const float* ar = t.acc + (u64)row * t.acc_len;
+          for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = ar[j];
         }
-        line[k] = line[k] + 1 == t.n_lines ? 0 : line[k] + 1;
-        slot_key[k] = load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]);
-      }
-      if (!created && sub == 0) {
-        // the key turned out to be present (duplicate in a bulk insert): give the room back
-        atomicAdd(&t.st->size, (unsigned long long)(-1ll));
-        atomicAdd(&t.st->inserted, (unsigned long long)(-1ll));
-      }
-      if (created && MODE == 1) {
-        const u64 base = mix64(key[k] ^ t.init_seed);
-        float* wr = t.w + (u64)row[k] * t.dim;
-        for (u32 j = sub; j < t.dim; j += 8) wr[j] = init_weight(base, j, t.init_range);
-        float* ar = t.acc + (u64)row[k] * t.acc_len;
-        for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = t.init_acc;
       }
     }
   }
-
-#pragma unroll
-  for (int k = 0; k < kProbeKeysPerGroup; ++k) {
-    const u64 u = block_first + (u64)k * kProbeGroups + group;
-    if (u >= n_keys) continue;
-    if (MODE == 2 && row[k] != kNoRow) {
-      float* wr = t.w + (u64)row[k] * t.dim;
-      const float* ws = w_in + u * t.dim;
-      for (u32 j = sub; j < t.dim; j += 8) wr[j] = ws[j];
-      float* ar = t.acc + (u64)row[k] * t.acc_len;
-      for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = acc_in ? acc_in[u * t.acc_len + j] : t.init_acc;
-    }
-    if (MODE == 3) {
-      if (sub == 0) found_out[u] = row[k] != kNoRow;
-      if (row[k] != kNoRow) {
-        const float* wr = t.w + (u64)row[k] * t.dim;
-        for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = wr[j];
-        const float* ar = t.acc + (u64)row[k] * t.acc_len;
-        for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = ar[j];
-      }
-    }
-    if (rows && sub == 0) rows[u] = row[k];
+  if (MODE != 3) {
+    if (sub == 0 && missing) atomicAdd(&s_missing, missing);
+    __syncthreads();
+    if (threadIdx.x == 0 && s_missing) atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], s_missing);
   }
 }
 
-// dump: every occupied slot, compacted through one counter (order unspecified).
+// Creates the keys lookup_keys found missing, if the table has room for all of them
+// (a key that occurs twice in a bulk insert is counted twice for this check).
+// rows != null (pull): only keys with rows[u] == kNoRow are visited, rows[u] is set.
+// rows == null (bulk insert): every key is probed again.
+// w_in == null: new rows get the deterministic initial row; else the given values.
+__global__ void __launch_bounds__(kProbeThreads)
+insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
+               const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
+               const float* __restrict__ w_in, const float* __restrict__ acc_in) {
+  __shared__ u32 s_total, s_made;
+  if (load_error(t.st) != 0) return;
+  if (threadIdx.x < kWave) {
+    u32 c = threadIdx.x < kCountShards ? t.st->miss_shard[threadIdx.x] : 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
+    if (threadIdx.x == 0) { s_total = c; s_made = 0; }
+  }
+  __syncthreads();
+  const u32 total = s_total;
+  if (total == 0) return;
+  // st->size does not change while this kernel runs: every block decides the same
+  if (t.st->size + total > t.capacity) {
+    if (threadIdx.x == 0) raise_error(t.st, kErrFull);
+    return;
+  }
+  const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
+  const u32 sub = threadIdx.x & 7;
+  const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
+  const u64 n_groups = (u64)gridDim.x * kProbeGroups;
+  u32 made = 0;
+  for (u64 u = group; u < n_keys; u += n_groups) {
+    if (rows && rows[u] != kNoRow) continue;
+    const u64 key = keys[u];
+    if (key == kEmptyKey) continue;
+    const u64 line = __umul64hi(slot_hash(key), t.n_lines);
+    const u64 slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);
+    bool created;
+    const u32 row = probe_find_or_claim(t, key, sub, line, slot_key, &created);
+    if (rows && sub == 0) rows[u] = row;
+    if (!created) continue;
+    ++made;
+    float* wr = t.w + (u64)row * t.dim;
+    float* ar = t.acc + (u64)row * t.acc_len;
+    if (w_in) {
+      for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
+      for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = acc_in ? acc_in[u * t.acc_len + j] : t.init_acc;
+    } else {
+      const u64 base = mix64(key ^ t.init_seed);
+      for (u32 j = sub; j < t.dim; j += 8) wr[j] = init_weight(base, j, t.init_range);
+      for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = t.init_acc;
+    }
+  }
+  if (sub == 0 && made) atomicAdd(&s_made, made);
+  __syncthreads();
+  if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
+}
+
+// dump: every occupied slot, compacted through one counter per block of slots
+// (order unspecified).
 __global__ void __launch_bounds__(256)
 dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
           float* __restrict__ acc_out, u64 max_rows, unsigned long long* __restrict__ counter) {
+  __shared__ u32 scratch[256 / kWave + 1];
+  __shared__ unsigned long long s_base;
   const u64 n_slots = t.n_lines * kSlotsPerLine;
-  for (u64 s = (u64)blockIdx.x * blockDim.x + threadIdx.x; s < n_slots + (kWave - 1);
-       s += (u64)gridDim.x * blockDim.x) {
+  const u64 n_rounds = (n_slots + 255) / 256;
+  for (u64 round = blockIdx.x; round < n_rounds; round += gridDim.x) {
+    const u64 s = round * 256 + threadIdx.x;
     const u64 key = s < n_slots ? t.keys[s] : kEmptyKey;
     const bool used = key != kEmptyKey;
-    const u64 m = __ballot(used);
-    if (m == 0) continue;
-    unsigned long long base = 0;
-    if (lane_id() == 0) base = atomicAdd(counter, (unsigned long long)__popcll(m));
-    base = __shfl(base, 0, kWave);
-    if (!used) continue;
-    const u64 o = base + __popcll(m & lanemask_lt());
-    if (o >= max_rows) continue;
-    keys_out[o] = key;
-    for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = t.w[s * t.dim + j];
-    for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = t.acc[s * t.acc_len + j];
+    u32 total;
+    const u32 before = block_excl_sum<256>(used ? 1u : 0u, scratch, &total);
+    if (threadIdx.x == 0 && total) s_base = atomicAdd(counter, (unsigned long long)total);
+    __syncthreads();
+    if (used) {
+      const u64 o = s_base + before;
+      if (o < max_rows) {
+        keys_out[o] = key;
+        for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = t.w[s * t.dim + j];
+        for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = t.acc[s * t.acc_len + j];
+      }
+    }
+    __syncthreads();
   }
 }
 
