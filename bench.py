@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--config", default="mid")
     ap.add_argument("--batches", type=int, default=0,
                     help="distinct pre-generated batches (0: one per step run, at most 64)")
+    ap.add_argument("--serial", action="store_true",
+                    help="plain hps_pull per step (default: hps_prepare of the next mini-batch "
+                         "on a second stream while the current one is pushed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="time budget of the CPU oracle leg (0 disables it)")
     args = ap.parse_args()
@@ -109,13 +112,30 @@ def main():
     pooled = torch.empty((cfg.n_bags, cfg.dim), dtype=torch.float32, device="cuda")
     setup_s = time.time() - t0
 
-    def step(i):
+    side = torch.cuda.Stream()          # default priority
+
+    def prepare(i):
+        k, o, _ = dev_batches[i % n_batches]
+        with torch.cuda.stream(side):
+            table.prepare(k, o, cfg.n_examples, cfg.n_slots)
+
+    def step(i, more=True):
+        """One step = dedup + lookup/insert + pool + reduce + update of mini-batch i.  In the
+        pipelined form the dedup of mini-batch i was enqueued during step i-1 and that of
+        mini-batch i+1 is enqueued here, between this step's pull and push."""
         k, o, g = dev_batches[i % n_batches]
-        table.pull(k, o, cfg.n_examples, cfg.n_slots, pooled)
+        if args.serial:
+            table.pull(k, o, cfg.n_examples, cfg.n_slots, pooled)
+        else:
+            table.pull_prepared(pooled)
+            if more:
+                prepare(i + 1)
         table.push(g)
 
     # ---- warm-up, and a look at which stage dominates ---------------------------------
     table.set_stage_timing(0b11111)
+    if not args.serial:
+        prepare(0)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -147,8 +167,9 @@ def main():
 
     # ---- all stages once more, outside the timed region, for the record -------------------
     table.set_stage_timing(0b11111)
-    for i in range(args.warmup + args.steps, args.warmup + args.steps + extra_steps):
-        step(i)
+    last = args.warmup + args.steps + extra_steps - 1
+    for i in range(args.warmup + args.steps, last + 1):
+        step(i, more=i < last)
     torch.cuda.synchronize()
     allst = merge_stage_times(table.stage_times())
     stages = {s: {"ms": round(allst[s][0] / max(allst[s][1], 1), 4),
@@ -195,7 +216,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "table_keys": int(st.size), "capacity": cfg.capacity,
+        "config": {"workload": cfg.name, "schedule": "serial" if args.serial else "dedup of batch i+1 overlaps push of batch i", "table_keys": int(st.size), "capacity": cfg.capacity,
                    "dim": cfg.dim, "n_examples": cfg.n_examples, "n_slots": cfg.n_slots,
                    "keys_per_step": round(mean_n, 1), "unique_per_step": round(mean_u, 1),
                    "zipf_s": cfg.zipf_s, "fresh_frac": cfg.fresh_frac,

@@ -33,9 +33,13 @@
  *     status word; the kernels of later calls do nothing while it is set, and it
  *     is reported by hps_stats() and cleared by hps_clear_error().
  *   - The key 0xFFFFFFFFFFFFFFFF marks an empty slot and is not a legal key.
- *   - One pull may be outstanding per table; a new pull replaces it.
- *   - Calls on one table must be issued on one stream at a time (or be ordered by
- *     the caller); the table is not internally synchronised across streams.
+ *   - One pull may be outstanding per table (between hps_pull and hps_push); a new
+ *     pull replaces it.  In addition one mini-batch may be "prepared" (its key dedup
+ *     done ahead of time, see hps_prepare); the workspace holds both contexts.
+ *   - Calls that touch the table (insert, pull, pull_prepared, push, get, dump) must
+ *     be issued on one stream at a time (or be ordered by the caller).  hps_prepare
+ *     does not touch the table and may run on another stream; the library orders it
+ *     against the calls that share its buffers with HIP events.
  */
 #ifndef HPS_H_
 #define HPS_H_
@@ -131,6 +135,23 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
 hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
                     const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
                     float* d_pooled, void* stream);
+
+/* The dedup half of a pull, ahead of time (Section 3's prefetch pipeline: the next
+ * mini-batch is made ready while the GPU still works on the current one).  Orders the
+ * keys, finds the unique keys, ranks and grouping of the mini-batch into the context
+ * that the outstanding pull does not use; reads no table row.  May be called between
+ * hps_pull and hps_push of the previous mini-batch, on any stream.  A second
+ * hps_prepare before hps_pull_prepared replaces the first.  d_offsets must stay valid
+ * until the work of the matching hps_pull_prepared has run.  Arguments as hps_pull. */
+hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                       const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
+                       void* stream);
+
+/* The table half of a pull for the prepared mini-batch: makes `stream` wait for the
+ * prepare, looks up / inserts the unique keys and pools into d_pooled.  The prepared
+ * mini-batch becomes the outstanding pull.  hps_pull(...) is hps_prepare followed by
+ * hps_pull_prepared on the same stream.  HPS_ESTATE if nothing is prepared. */
+hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream);
 
 /* Algorithm 1 push_parameters_updates_back_kernel / Algorithm 2's local accumulate.
  *   d_pooled_grads [n_bags, dim]: gradient of the loss w.r.t. d_pooled of the

@@ -11,6 +11,7 @@ OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM = 0, -1, -2, -3, -4, -5, -
 ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
+           "hps_prepare", "hps_pull_prepared",
            "hps_push", "hps_last_unique", "hps_get", "hps_dump", "hps_stats", "hps_clear_error",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
@@ -51,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.hps_insert.argtypes = [vp, vp, u64, vp, vp, vp]
         L.hps_pull.restype = st
         L.hps_pull.argtypes = [vp, vp, u64, vp, u32, u32, vp, vp]
+        L.hps_prepare.restype = st
+        L.hps_prepare.argtypes = [vp, vp, u64, vp, u32, u32, vp]
+        L.hps_pull_prepared.restype = st
+        L.hps_pull_prepared.argtypes = [vp, vp, vp]
         L.hps_push.restype = st
         L.hps_push.argtypes = [vp, vp, vp]
         L.hps_last_unique.restype = st
@@ -126,6 +131,7 @@ class HpsTable:
                                 max_keys, max_bags, _stream()), "hps_create")
         self._h = h
         self._last_n = 0
+        self._prepared = None
 
     def close(self) -> None:
         if self._h:
@@ -152,6 +158,21 @@ class HpsTable:
         _check(lib().hps_pull(self._h, _ptr(keys), keys.numel(), _ptr(offsets), n_examples,
                               n_slots, _ptr(pooled), _stream()), "hps_pull")
         self._last_n = keys.numel()
+        return pooled
+
+    def prepare(self, keys, offsets, n_examples: int, n_slots: int) -> None:
+        assert offsets.numel() == n_examples * n_slots + 1
+        _check(lib().hps_prepare(self._h, _ptr(keys), keys.numel(), _ptr(offsets), n_examples,
+                                 n_slots, _stream()), "hps_prepare")
+        self._prepared = (keys.numel(), n_examples * n_slots, keys, offsets)
+
+    def pull_prepared(self, pooled=None):
+        import torch
+        n, n_bags, _, _ = self._prepared
+        if pooled is None:
+            pooled = torch.empty((n_bags, self.dim), dtype=torch.float32, device=self.device)
+        _check(lib().hps_pull_prepared(self._h, _ptr(pooled), _stream()), "hps_pull_prepared")
+        self._last_n = n
         return pooled
 
     def push(self, pooled_grads) -> None:

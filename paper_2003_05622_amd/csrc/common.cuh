@@ -32,6 +32,8 @@ struct TableState {
   // over shards so that blocks do not all hit one address.
   u32 miss_shard[kCountShards];
   u32 made_shard[kCountShards];
+  u32 miss_overflow;            // the list of missing keys did not fit: scan instead
+  u32 pad2;
 };
 
 // Lives in the workspace; describes the outstanding pull.

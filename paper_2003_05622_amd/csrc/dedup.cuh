@@ -180,22 +180,32 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
             PullCtx* __restrict__ ctx, u32* __restrict__ evidence, TableState* __restrict__ st) {
   __shared__ u32 scratch[kHeadThreads / kWave + 1];
   __shared__ u32 s_tile, s_earlier;
+  __shared__ u64 lds_key[kHeadTile];     // the tile, read coalesced, handed out in runs of 8
+  __shared__ u32 lds_idx[kHeadTile];     // later reused for the bagperm words going out
   if (REDO && ctx->n_evidence == 0) return;
   if (threadIdx.x == 0) s_tile = atomicAdd(ticket, 1u);
   __syncthreads();
   const u32 tile = s_tile;
-  const u32 first = tile * kHeadTile + threadIdx.x * kHeadItems;
+  const u32 tile_base = tile * kHeadTile;
+#pragma unroll
+  for (int k = 0; k < kHeadItems; ++k) {
+    const u32 p = k * kHeadThreads + threadIdx.x;
+    const u32 j = tile_base + p;
+    lds_key[p] = (j < n) ? skeys[j] : 0;
+    lds_idx[p] = (j < n) ? sidx[j] : 0;
+  }
+  __syncthreads();
+  const u32 first = tile_base + threadIdx.x * kHeadItems;
   u64 key[kHeadItems];
   u32 idx[kHeadItems], bag[kHeadItems];
   bool head[kHeadItems];
   u64 prev = 0;
-  if (first > 0 && first < n) prev = skeys[first - 1];
+  if (first > 0 && first < n) prev = threadIdx.x ? lds_key[threadIdx.x * kHeadItems - 1] : skeys[first - 1];
   u32 heads = 0;
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {
-    const u32 j = first + k;
-    key[k] = (j < n) ? skeys[j] : 0;
-    idx[k] = (j < n) ? sidx[j] : 0;
+    key[k] = lds_key[threadIdx.x * kHeadItems + k];
+    idx[k] = lds_idx[threadIdx.x * kHeadItems + k];
   }
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {
@@ -248,9 +258,15 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
         if (key[k] == kEmptyKey) raise_error(st, kErrReserved);
         ++rank;
       }
-      bagperm[j] = bag[k] | (head[k] ? 0x80000000u : 0u);
+      lds_idx[threadIdx.x * kHeadItems + k] = bag[k] | (head[k] ? 0x80000000u : 0u);
       inverse[idx[k]] = (i32)(rank - 1);
     }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kHeadItems; ++k) {
+    const u32 p = k * kHeadThreads + threadIdx.x;
+    if (tile_base + p < n) bagperm[tile_base + p] = lds_idx[p];
   }
 }
 

@@ -60,11 +60,17 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
   return L;
 }
 
+// Per pull context (two of them, so that the dedup of the next mini-batch can run
+// while the current one is still between pull and push).
+struct ContextLayout {
+  size_t ctx, uniq, rows, inverse, bagperm, seg_off;
+};
+
 struct WorkspaceLayout {
-  size_t ctx, keys_a, keys_b, idx_a, idx_b, ghist, tickets, tile_rows, group_rows, head_rows,
-      head_groups, evidence, uniq, rows, inverse, bagperm, seg_off, bag_of, med_list, long_list, chunk_items,
-      partials, total;
-  uint64_t max_med, max_long, max_items, sort_tiles, head_tiles;
+  size_t keys_a, keys_b, idx_a, idx_b, ghist, tickets, tile_rows, group_rows, head_rows,
+      head_groups, evidence, bag_of, miss_list, med_list, long_list, chunk_items, partials, total;
+  ContextLayout c[2];
+  uint64_t max_med, max_long, max_items, sort_tiles, head_tiles, shard_cap;
 };
 
 WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
@@ -77,7 +83,6 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   L.max_long = n1 / (kMedSeg + 1) + 1;      // keys with more than kMedSeg occurrences
   L.max_items = n1 / kChunk + L.max_long + 1;
   size_t o = 0;
-  L.ctx = o;         o = align_up(o + sizeof(PullCtx));
   L.keys_a = o;      o = align_up(o + n1 * 8);
   L.keys_b = o;      o = align_up(o + n1 * 8);
   L.idx_a = o;       o = align_up(o + n1 * 4);
@@ -90,12 +95,17 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   L.head_rows = o;   o = align_up(o + 2 * L.head_tiles * 4);
   L.head_groups = o; o = align_up(o + 2 * (L.head_tiles / kMinTileGroup + 1) * 4);
   L.evidence = o;    o = align_up(o + kMaxEvidence * 4);
-  L.uniq = o;        o = align_up(o + n1 * 8);
-  L.rows = o;        o = align_up(o + n1 * 4);
-  L.inverse = o;     o = align_up(o + n1 * 4);
-  L.bagperm = o;     o = align_up(o + n1 * 4);
-  L.seg_off = o;     o = align_up(o + (n1 + 1) * 4);
   L.bag_of = o;      o = align_up(o + n1 * 4);
+  L.shard_cap = n1 / kCountShards + kMissLdsCap;
+  L.miss_list = o;   o = align_up(o + (size_t)kCountShards * L.shard_cap * 4);
+  for (int k = 0; k < 2; ++k) {
+    L.c[k].ctx = o;     o = align_up(o + sizeof(PullCtx));
+    L.c[k].uniq = o;    o = align_up(o + n1 * 8);
+    L.c[k].rows = o;    o = align_up(o + n1 * 4);
+    L.c[k].inverse = o; o = align_up(o + n1 * 4);
+    L.c[k].bagperm = o; o = align_up(o + n1 * 4);
+    L.c[k].seg_off = o; o = align_up(o + (n1 + 1) * 4);
+  }
   L.med_list = o;    o = align_up(o + L.max_med * 4);
   L.long_list = o;   o = align_up(o + L.max_long * 8);
   L.chunk_items = o; o = align_up(o + L.max_items * 8);
@@ -151,9 +161,21 @@ struct hps_table {
   char* ws;
   WorkspaceLayout wl;
   int lpr;
-  uint64_t serial;     // number of pulls so far (status words carry it modulo kEpochMod)
-  bool pulled;
-  uint64_t last_n_keys, last_n_bags;
+  uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
+
+  // Pull contexts.  `current` is the context of the outstanding pull (-1: none),
+  // `prepared` the one whose dedup has been enqueued but not yet pulled (-1: none).
+  struct Context {
+    uint64_t n_keys, n_bags;
+    const int32_t* d_offsets;
+    hipEvent_t ready;     // recorded after the dedup kernels
+    hipEvent_t released;  // recorded after the push that used the context
+    bool ready_set, released_set;
+  } cx[2];
+  int current, prepared;
+  hipEvent_t scratch_free;   // the last dedup's end: the sort scratch is shared
+  bool scratch_set;
+  uint64_t last_n_keys;      // of the most recent pull, for hps_stats
 
   // stage timing (measurement only)
   uint32_t timing_mask;
@@ -161,6 +183,7 @@ struct hps_table {
   size_t ev_used[HPS_N_STAGES];
 
   template <typename T> T* w(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  PullCtx* ctx(int c) const { return w<PullCtx>(wl.c[c].ctx); }
 };
 
 namespace {
@@ -180,17 +203,16 @@ void stage_mark(hps_table* t, int stage, hipStream_t s) {
 }  // namespace
 
 template <int LPR>
-static void launch_pool(hps_table* t, const int32_t* d_offsets, uint32_t n_bags, float* d_pooled,
-                        hipStream_t s) {
-  const unsigned blocks = grid_for(n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
-  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, d_offsets, n_bags, (u32)t->last_n_keys,
-                                                 t->w<i32>(t->wl.inverse), t->w<u32>(t->wl.rows),
-                                                 d_pooled);
+static void launch_pool(hps_table* t, int c, float* d_pooled, hipStream_t s) {
+  const hps_table::Context& cx = t->cx[c];
+  const unsigned blocks = grid_for(cx.n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
+  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags, (u32)cx.n_keys,
+                                                 t->w<i32>(t->wl.c[c].inverse),
+                                                 t->w<u32>(t->wl.c[c].rows), d_pooled);
 }
 
 template <int LPR>
-static void launch_push(hps_table* t, const PushArgs& a, hipStream_t s) {
-  const uint64_t n = t->last_n_keys;
+static void launch_push(hps_table* t, uint64_t n, const PushArgs& a, hipStream_t s) {
   push_short<LPR><<<grid_for(n, kPushThreads / LPR, kPushShortBlocks), kPushThreads, 0, s>>>(t->view, a);
   push_medium<LPR><<<grid_for(n / (kShortSeg + 1) + 1, kPushThreads / kWave, kPushMediumBlocks),
                      kPushThreads, 0, s>>>(t->view, a);
@@ -278,8 +300,19 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->ws = static_cast<char*>(d_workspace);
   t->wl = wl;
   t->lpr = lanes_per_row(dim);
-  t->pulled = false;
-  t->last_n_keys = t->last_n_bags = 0;
+  t->current = t->prepared = -1;
+  t->last_n_keys = 0;
+  t->scratch_set = false;
+  bool events_ok = hipEventCreateWithFlags(&t->scratch_free, hipEventDisableTiming) == hipSuccess;
+  for (int k = 0; k < 2; ++k) {
+    t->cx[k].n_keys = t->cx[k].n_bags = 0;
+    t->cx[k].d_offsets = nullptr;
+    t->cx[k].ready_set = t->cx[k].released_set = false;
+    events_ok = events_ok &&
+                hipEventCreateWithFlags(&t->cx[k].ready, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&t->cx[k].released, hipEventDisableTiming) == hipSuccess;
+  }
+  if (!events_ok) { (void)hipGetLastError(); delete t; return HPS_EDEVICE; }
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
   t->serial = 0;
@@ -287,9 +320,10 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   hipStream_t s = static_cast<hipStream_t>(stream);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
   // look-back status words and digit histograms start at zero
-  fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.uniq - wl.ghist) / 8, 0);
+  fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.bag_of - wl.ghist) / 8, 0);
   reset_state<<<1, 64, 0, s>>>(t->view.st);
-  set_ctx_empty<<<1, 1, 0, s>>>(t->w<PullCtx>(wl.ctx), t->w<u32>(wl.seg_off), t->view.st);
+  for (int k = 0; k < 2; ++k)
+    set_ctx_empty<<<1, 1, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
   if (!launch_ok()) { delete t; return HPS_EDEVICE; }
   *out = t;
   return HPS_OK;
@@ -299,6 +333,11 @@ hps_status hps_destroy(hps_table* t) {
   if (!t) return HPS_EINVAL;
   for (int i = 0; i < HPS_N_STAGES; ++i)
     for (hipEvent_t e : t->ev_pool[i]) (void)hipEventDestroy(e);
+  (void)hipEventDestroy(t->scratch_free);
+  for (int k = 0; k < 2; ++k) {
+    (void)hipEventDestroy(t->cx[k].ready);
+    (void)hipEventDestroy(t->cx[k].released);
+  }
   delete t;
   return HPS_OK;
 }
@@ -311,35 +350,38 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
   if (n) {
     if (d_weights)
       lookup_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                      d_acc, nullptr, nullptr, nullptr);
+                                                      d_acc, nullptr, nullptr, nullptr, nullptr, 0);
     else
       lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                      nullptr, nullptr, nullptr, nullptr);
+                                                      nullptr, nullptr, nullptr, nullptr, nullptr, 0);
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                    d_acc);
+                                                    d_acc, nullptr, 0);
   }
   commit_insert<<<1, 64, 0, s>>>(t->view.st);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
-hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
-                    const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
-                    float* d_pooled, void* stream) {
+hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                       const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
+                       void* stream) {
   if (!t || !d_offsets || (n_keys && !d_keys)) return HPS_EINVAL;
   const uint64_t n_bags = (uint64_t)n_examples * n_slots;
   if (n_keys > t->max_keys || n_bags > t->max_bags) return HPS_EINVAL;
-  if (n_bags && !d_pooled) return HPS_EINVAL;
-  if ((uintptr_t)d_keys % 8 || (uintptr_t)d_offsets % 4 || (uintptr_t)d_pooled % 16)
-    return HPS_EINVAL;
+  if ((uintptr_t)d_keys % 8 || (uintptr_t)d_offsets % 4) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const WorkspaceLayout& L = t->wl;
-  PullCtx* ctx = t->w<PullCtx>(L.ctx);
+  const int c = t->current == 0 ? 1 : 0;        // the context the outstanding pull does not use
+  const ContextLayout& C = L.c[c];
+  hps_table::Context& cx = t->cx[c];
+  PullCtx* ctx = t->ctx(c);
   const u32 n = (u32)n_keys;
-  t->last_n_keys = n_keys;
-  t->last_n_bags = n_bags;
+  // order after the push that last read this context, and after the previous dedup
+  // (the sort scratch is shared); both may have run on other streams
+  if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
+  if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
 
   if (n == 0) {
-    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(L.seg_off), t->view.st);
+    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(C.seg_off));
   } else {
     // a1: order the occurrences by the top bits of their keys
     stage_mark(t, HPS_STAGE_SORT, s);
@@ -356,7 +398,7 @@ hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
     u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kMaxPasses * kRadix;
     u32* tickets = t->w<u32>(L.tickets);
     const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    sort_prepare<<<n_tiles < 1024 ? n_tiles : 1024, kPrepThreads, 0, s>>>(
+    sort_prepare<<<n_tiles < 512 ? n_tiles : 512, kPrepThreads, 0, s>>>(
         d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, (u32)n_bags,
         t->w<i32>(L.bag_of));
     for (int p = 0; p < plan.n_pass; ++p) {
@@ -383,87 +425,129 @@ hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
     u32* evidence = t->w<u32>(L.evidence);
     unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
         kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
-        tickets + kMaxPasses, epoch,
-        t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(L.uniq), t->w<i32>(L.inverse),
-        t->w<u32>(L.bagperm), t->w<u32>(L.seg_off), ctx, evidence, t->view.st);
+        tickets + kMaxPasses, epoch, t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(C.uniq),
+        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
     fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, icur, kalt, ialt, n, plan, ctx, evidence);
     unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
         kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
         t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
-        tickets + kMaxPasses + 1, epoch,
-        t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(L.uniq), t->w<i32>(L.inverse),
-        t->w<u32>(L.bagperm), t->w<u32>(L.seg_off), ctx, evidence, t->view.st);
+        tickets + kMaxPasses + 1, epoch, t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(C.uniq),
+        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
     stage_mark(t, HPS_STAGE_UNIQUE, s);
-    // a2: look up every unique key, create the missing ones
-    stage_mark(t, HPS_STAGE_LOOKUP, s);
-    const unsigned probe_blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
-    lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
-                                                          &ctx->n_unique, t->w<u32>(L.rows), nullptr,
-                                                          nullptr, nullptr, nullptr, nullptr);
-    insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(L.uniq), 0,
-                                                          &ctx->n_unique, t->w<u32>(L.rows), nullptr,
-                                                          nullptr);
-    commit_insert<<<1, 64, 0, s>>>(t->view.st);
-    stage_mark(t, HPS_STAGE_LOOKUP, s);
   }
+  if (!launch_ok()) return HPS_EDEVICE;
+  if (hipEventRecord(cx.ready, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)
+    return HPS_EDEVICE;
+  cx.ready_set = true;
+  t->scratch_set = true;
+  cx.n_keys = n_keys;
+  cx.n_bags = n_bags;
+  cx.d_offsets = d_offsets;
+  t->prepared = c;
+  return HPS_OK;
+}
+
+hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
+  if (!t) return HPS_EINVAL;
+  if (t->prepared < 0) return HPS_ESTATE;
+  const int c = t->prepared;
+  const hps_table::Context& cx = t->cx[c];
+  if (cx.n_bags && !d_pooled) return HPS_EINVAL;
+  if ((uintptr_t)d_pooled % 16) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const ContextLayout& C = t->wl.c[c];
+  PullCtx* ctx = t->ctx(c);
+  if (hipStreamWaitEvent(s, cx.ready, 0) != hipSuccess) return HPS_EDEVICE;
+  // a2: look up every unique key, create the missing ones
+  stage_mark(t, HPS_STAGE_LOOKUP, s);
+  if (cx.n_keys) {
+    const unsigned probe_blocks = grid_for(cx.n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+    u32* miss_list = t->w<u32>(t->wl.miss_list);
+    const u32 shard_cap = (u32)t->wl.shard_cap;
+    lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
+                                                          &ctx->n_unique, t->w<u32>(C.rows), nullptr,
+                                                          nullptr, nullptr, nullptr, nullptr, miss_list,
+                                                          shard_cap);
+    insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
+                                                          &ctx->n_unique, t->w<u32>(C.rows), nullptr,
+                                                          nullptr, miss_list, shard_cap);
+  }
+  commit_insert<<<1, 64, 0, s>>>(t->view.st);
+  stage_mark(t, HPS_STAGE_LOOKUP, s);
   // a3: gather rows and pool per bag
-  if (n_bags) {
+  if (cx.n_bags) {
     stage_mark(t, HPS_STAGE_POOL, s);
-#define CALL(LPR) launch_pool<LPR>(t, d_offsets, (uint32_t)n_bags, d_pooled, s)
+#define CALL(LPR) launch_pool<LPR>(t, c, d_pooled, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
     stage_mark(t, HPS_STAGE_POOL, s);
   }
   if (!launch_ok()) return HPS_EDEVICE;
-  t->pulled = true;
-  t->last_n_keys = n_keys;
-  t->last_n_bags = n_bags;
+  t->current = c;
+  t->prepared = -1;
+  t->last_n_keys = cx.n_keys;
   return HPS_OK;
+}
+
+hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                    const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
+                    float* d_pooled, void* stream) {
+  if ((uint64_t)n_examples * n_slots && !d_pooled) return HPS_EINVAL;
+  if ((uintptr_t)d_pooled % 16) return HPS_EINVAL;
+  const hps_status rc = hps_prepare(t, d_keys, n_keys, d_offsets, n_examples, n_slots, stream);
+  return rc != HPS_OK ? rc : hps_pull_prepared(t, d_pooled, stream);
 }
 
 hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   if (!t) return HPS_EINVAL;
-  if (!t->pulled) return HPS_ESTATE;
-  if (t->last_n_bags && !d_pooled_grads) return HPS_EINVAL;
+  if (t->current < 0) return HPS_ESTATE;
+  const int c = t->current;
+  hps_table::Context& cx = t->cx[c];
+  if (cx.n_bags && cx.n_keys && !d_pooled_grads) return HPS_EINVAL;
   if ((uintptr_t)d_pooled_grads % 16) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  t->pulled = false;
-  if (t->last_n_keys == 0) return HPS_OK;
-  const WorkspaceLayout& L = t->wl;
-  PushArgs a;
-  a.seg_off = t->w<u32>(L.seg_off);
-  a.bagperm = t->w<u32>(L.bagperm);
-  a.rows = t->w<u32>(L.rows);
-  a.grads = d_pooled_grads;
-  a.ctx = t->w<PullCtx>(L.ctx);
-  a.med_list = t->w<u32>(L.med_list);
-  a.long_list = t->w<uint2>(L.long_list);
-  a.chunk_items = t->w<uint2>(L.chunk_items);
-  a.partials = t->w<float>(L.partials);
-  a.lr = t->opt.lr;
-  a.eps = t->opt.eps;
-  a.elementwise = t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE;
-  stage_mark(t, HPS_STAGE_PUSH, s);
-#define CALL(LPR) launch_push<LPR>(t, a, s)
-  HPS_DISPATCH_LPR(t->lpr, CALL)
+  t->current = -1;
+  if (cx.n_keys) {
+    const WorkspaceLayout& L = t->wl;
+    PushArgs a;
+    a.seg_off = t->w<u32>(L.c[c].seg_off);
+    a.bagperm = t->w<u32>(L.c[c].bagperm);
+    a.rows = t->w<u32>(L.c[c].rows);
+    a.grads = d_pooled_grads;
+    a.ctx = t->ctx(c);
+    a.med_list = t->w<u32>(L.med_list);
+    a.long_list = t->w<uint2>(L.long_list);
+    a.chunk_items = t->w<uint2>(L.chunk_items);
+    a.partials = t->w<float>(L.partials);
+    a.lr = t->opt.lr;
+    a.eps = t->opt.eps;
+    a.elementwise = t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE;
+    stage_mark(t, HPS_STAGE_PUSH, s);
+#define CALL(LPR) launch_push<LPR>(t, cx.n_keys, a, s)
+    HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
-  stage_mark(t, HPS_STAGE_PUSH, s);
-  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+    stage_mark(t, HPS_STAGE_PUSH, s);
+    if (!launch_ok()) return HPS_EDEVICE;
+  }
+  if (hipEventRecord(cx.released, s) != hipSuccess) return HPS_EDEVICE;
+  cx.released_set = true;
+  return HPS_OK;
 }
 
 hps_status hps_last_unique(hps_table* t, uint64_t* d_uniq_out, int32_t* d_inverse_out,
                            void* stream) {
   if (!t) return HPS_EINVAL;
-  if (!t->pulled) return HPS_ESTATE;
+  if (t->current < 0) return HPS_ESTATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const uint64_t n = t->last_n_keys;
+  const ContextLayout& C = t->wl.c[t->current];
+  const uint64_t n = t->cx[t->current].n_keys;
   if (n == 0) return HPS_OK;
   // U <= n is only known on the device: copy n entries, the caller reads the first U.
   if (d_uniq_out &&
-      hipMemcpyAsync(d_uniq_out, t->w<u64>(t->wl.uniq), n * 8, hipMemcpyDeviceToDevice, s) != hipSuccess)
+      hipMemcpyAsync(d_uniq_out, t->w<u64>(C.uniq), n * 8, hipMemcpyDeviceToDevice, s) != hipSuccess)
     return HPS_EDEVICE;
   if (d_inverse_out &&
-      hipMemcpyAsync(d_inverse_out, t->w<i32>(t->wl.inverse), n * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
+      hipMemcpyAsync(d_inverse_out, t->w<i32>(C.inverse), n * 4, hipMemcpyDeviceToDevice, s) != hipSuccess)
     return HPS_EDEVICE;
   return HPS_OK;
 }
@@ -475,7 +559,8 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                  nullptr, d_weights_out, d_acc_out, d_found_out);
+                                                  nullptr, d_weights_out, d_acc_out, d_found_out,
+                                                  nullptr, 0);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
@@ -503,7 +588,8 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   PullCtx ctx;
   if (hipMemcpyAsync(&st, t->view.st, sizeof(st), hipMemcpyDeviceToHost, s) != hipSuccess)
     return HPS_EDEVICE;
-  if (hipMemcpyAsync(&ctx, t->w<PullCtx>(t->wl.ctx), sizeof(ctx), hipMemcpyDeviceToHost, s) != hipSuccess)
+  const int which = t->current >= 0 ? t->current : (t->prepared >= 0 ? t->prepared : 0);
+  if (hipMemcpyAsync(&ctx, t->ctx(which), sizeof(ctx), hipMemcpyDeviceToHost, s) != hipSuccess)
     return HPS_EDEVICE;
   if (hipStreamSynchronize(s) != hipSuccess) return HPS_EDEVICE;
   h_out->size = st.size;
@@ -513,7 +599,7 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->last_n_unique = ctx.n_unique;
   h_out->last_n_inserted = st.inserted;
   h_out->error = st.error;
-  h_out->pull_outstanding = t->pulled ? 1 : 0;
+  h_out->pull_outstanding = t->current >= 0 ? 1 : 0;
   return HPS_OK;
 }
 

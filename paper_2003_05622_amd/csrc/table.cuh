@@ -37,6 +37,7 @@ constexpr int kProbeThreads = 256;
 constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
 constexpr int kProbeInFlight = 4;                             // keys a group probes at a time
 constexpr int kProbeMaxBlocks = 2048;
+constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
 
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
 __device__ __forceinline__ u32 group_bits(u64 ballot) {
@@ -61,13 +62,14 @@ __global__ void __launch_bounds__(64) reset_state(TableState* st) {
     st->dump_count = 0;
   }
   if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
+  if (threadIdx.x == 0) st->miss_overflow = 0;
 }
 __global__ void __launch_bounds__(64) clear_error(TableState* st) {
-  if (threadIdx.x == 0) st->error = 0;
+  if (threadIdx.x == 0) { st->error = 0; st->miss_overflow = 0; }
   if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
 }
 __global__ void clear_dump_count(TableState* st) { st->dump_count = 0; }
-__global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off, TableState* st) {
+__global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off) {
   ctx->n_unique = 0;
   ctx->n_long = 0;
   ctx->n_medium = 0;
@@ -75,7 +77,6 @@ __global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off, TableState* st) {
   ctx->n_evidence = 0;
   ctx->sort_error = 0;
   seg_off[0] = 0;
-  st->inserted = 0;
 }
 
 // Adds the rows insert_missing created to the table size and clears the counters.
@@ -87,6 +88,7 @@ __global__ void __launch_bounds__(64) commit_insert(TableState* st) {
   if (threadIdx.x == 0) {
     st->size += made;
     st->inserted = made;
+    st->miss_overflow = 0;
   }
 }
 
@@ -136,15 +138,18 @@ __device__ __forceinline__ u32 probe_find_or_claim(const TableView& t, u64 key, 
 // MODE 2  bulk insert with values: present keys overwritten, missing keys counted
 // MODE 3  get: copy the row out, found flags
 // n_keys is read from *n_keys_dev when that pointer is not null (the pull's U lives
-// on the device).
+// on the device).  MODE 0 also lists the missing keys' indices: block b appends to
+// shard b % 64 of miss_list (shard_cap entries each); if a list does not fit, the
+// overflow flag makes insert_missing scan all keys instead.
 template <int MODE>
 __global__ void __launch_bounds__(kProbeThreads)
 lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
             const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
             const float* __restrict__ w_in, const float* __restrict__ acc_in,
             float* __restrict__ w_out, float* __restrict__ acc_out,
-            uint8_t* __restrict__ found_out) {
-  __shared__ u32 s_missing;
+            uint8_t* __restrict__ found_out, u32* __restrict__ miss_list, u32 shard_cap) {
+  __shared__ u32 s_missing, s_base;
+  __shared__ u32 s_list[MODE == 0 ? kMissLdsCap : 1];
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
   if (load_error(t.st) != 0) return;
   if (threadIdx.x == 0) s_missing = 0;
@@ -177,8 +182,14 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         continue;
       }
       const u32 row = probe_find(t, key[k], sub, line[k], slot_key[k]);
-      if (row == kNoRow && MODE != 3) ++missing;
-      if (MODE == 0 && sub == 0) rows[u] = row;
+      if (row == kNoRow && MODE != 3 && MODE != 0) ++missing;
+      if (MODE == 0 && sub == 0) {
+        rows[u] = row;
+        if (row == kNoRow) {
+          const u32 at = atomicAdd(&s_missing, 1u);
+          if (at < kMissLdsCap) s_list[at] = (u32)u;
+        }
+      }
       if (MODE == 2 && row != kNoRow) {
         float* wr = t.w + (u64)row * t.dim;
         for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
@@ -196,29 +207,47 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
       }
     }
   }
-  if (MODE != 3) {
+  if (MODE == 1 || MODE == 2) {
     if (sub == 0 && missing) atomicAdd(&s_missing, missing);
     __syncthreads();
     if (threadIdx.x == 0 && s_missing) atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], s_missing);
+  }
+  if (MODE == 0) {
+    __syncthreads();
+    const u32 cnt = s_missing;
+    if (cnt == 0) return;
+    if (threadIdx.x == 0) s_base = atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], cnt);
+    __syncthreads();
+    const u32 base = s_base;
+    if (cnt > kMissLdsCap || base + cnt > shard_cap) {
+      if (threadIdx.x == 0) t.st->miss_overflow = 1;
+      return;
+    }
+    u32* dst = miss_list + (u64)(blockIdx.x % kCountShards) * shard_cap + base;
+    for (u32 i = threadIdx.x; i < cnt; i += kProbeThreads) dst[i] = s_list[i];
   }
 }
 
 // Creates the keys lookup_keys found missing, if the table has room for all of them
 // (a key that occurs twice in a bulk insert is counted twice for this check).
-// rows != null (pull): only keys with rows[u] == kNoRow are visited, rows[u] is set.
+// rows != null (pull): the listed missing keys are visited (or, after a list overflow,
+// all keys with rows[u] == kNoRow); rows[u] is set.
 // rows == null (bulk insert): every key is probed again.
 // w_in == null: new rows get the deterministic initial row; else the given values.
 __global__ void __launch_bounds__(kProbeThreads)
 insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
                const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
-               const float* __restrict__ w_in, const float* __restrict__ acc_in) {
-  __shared__ u32 s_total, s_made;
+               const float* __restrict__ w_in, const float* __restrict__ acc_in,
+               const u32* __restrict__ miss_list, u32 shard_cap) {
+  __shared__ u32 s_total, s_made, s_mine;
   if (load_error(t.st) != 0) return;
   if (threadIdx.x < kWave) {
-    u32 c = threadIdx.x < kCountShards ? t.st->miss_shard[threadIdx.x] : 0;
+    const u32 mine = threadIdx.x < kCountShards ? t.st->miss_shard[threadIdx.x] : 0;
+    u32 c = mine;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
     if (threadIdx.x == 0) { s_total = c; s_made = 0; }
+    if (threadIdx.x == blockIdx.x % kCountShards) s_mine = mine;
   }
   __syncthreads();
   const u32 total = s_total;
@@ -233,8 +262,16 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
   const u64 n_groups = (u64)gridDim.x * kProbeGroups;
   u32 made = 0;
-  for (u64 u = group; u < n_keys; u += n_groups) {
-    if (rows && rows[u] != kNoRow) continue;
+  const bool listed = rows != nullptr && t.st->miss_overflow == 0;
+  // listed: this block's share of its shard's list; else every key
+  const u32 shard = blockIdx.x % kCountShards;
+  const u32 shard_blocks = (gridDim.x - shard + kCountShards - 1) / kCountShards;
+  const u64 first = listed ? (u64)(blockIdx.x / kCountShards) * kProbeGroups + (threadIdx.x >> 3) : group;
+  const u64 stride = listed ? (u64)shard_blocks * kProbeGroups : n_groups;
+  const u64 count = listed ? (u64)s_mine : n_keys;
+  for (u64 e = first; e < count; e += stride) {
+    const u64 u = listed ? (u64)miss_list[(u64)shard * shard_cap + e] : e;
+    if (!listed && rows && rows[u] != kNoRow) continue;
     const u64 key = keys[u];
     if (key == kEmptyKey) continue;
     const u64 line = __umul64hi(slot_hash(key), t.n_lines);

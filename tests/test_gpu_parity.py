@@ -138,6 +138,42 @@ def mixed_run_keys():
     return keys[rng.permutation(keys.shape[0])]
 
 
+def test_prepare_overlapping_the_previous_push():
+    """hps_prepare of mini-batch i+1 on a second stream between pull and push of mini-batch i
+    gives the same results as plain pulls (the oracle knows nothing of the schedule)."""
+    cfg = synth.scaled(synth.CONFIGS["insert_heavy"], n_prefill=60_000, n_examples=64,
+                       n_slots=100, steps=8)
+    stream = synth.BatchStream(cfg)
+    batches = [stream.next() for _ in range(8)]
+    gt, ot = make_pair(cfg, max(b.n_keys for b in batches))
+    pre = synth.prefill_keys(0, cfg.n_prefill)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+    dev = [(dev_keys(b.keys), torch.from_numpy(b.offsets).cuda(), torch.from_numpy(b.grads).cuda())
+           for b in batches]
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        gt.prepare(dev[0][0], dev[0][1], cfg.n_examples, cfg.n_slots)
+    for i, b in enumerate(batches):
+        pooled = gt.pull_prepared()
+        if i + 1 < len(batches):
+            with torch.cuda.stream(side):
+                gt.prepare(dev[i + 1][0], dev[i + 1][1], cfg.n_examples, cfg.n_slots)
+        want = ot.pull(b.keys, b.offsets)
+        uniq, inv = gt.last_unique()
+        ou, oi = ot.last_unique()
+        assert np.array_equal(host_keys(uniq), ou) and np.array_equal(inv.cpu().numpy(), oi)
+        assert gt.stats().last_n_inserted == ot.n_inserted
+        assert_close(pooled.cpu().numpy(), want, "pooled step %d" % i)
+        gt.push(dev[i][2])
+        ot.push(b.grads)
+    compare_tables(gt, ot, "pipelined")
+    with pytest.raises(hps.HpsError) as e:
+        gt.pull_prepared()                      # nothing prepared
+    assert e.value.status == hps.ESTATE
+
+
 def test_edge_cases():
     cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=1000, n_examples=4, n_slots=4,
                        capacity=8000, steps=1)
