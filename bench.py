@@ -10,6 +10,10 @@ already resident in HBM.  Prints ONE JSON line:
              over its HIP-event duration, against the 8 TB/s peak
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
 
+Schedule of the timed steps (default): pull_prepared(i); prepare(i+1) on a second
+stream; push(i) -- every mini-batch goes through all five stages, the dedup of the next
+one overlaps the push of the current one.  --serial times plain hps_pull + hps_push.
+
 python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mid]
 """
 import argparse
@@ -23,6 +27,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+
+
+def measured_traffic(workload, stage):
+    """HBM bytes per launch of a stage from the committed rocprofv3 counter summary
+    (profiles/<workload>_hbm_counters.md, lines 'traffic <stage> <bytes>'), or None."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_counters.md" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic" and parts[1] == stage:
+                    return int(float(parts[2]))
+    except OSError:
+        pass
+    return None
 
 
 def stage_bytes(n, u, bags, d):
@@ -40,9 +59,9 @@ STAGE_BITS = {"dedup": 0b00011, "lookup": 0b00100, "pool": 0b01000, "push": 0b10
 STAGE_KERNELS = {
     "dedup": "sort_prepare, n_pass x onesweep_pass, unique_emit, fix_mixed_runs, "
              "unique_emit (redo)",
-    "lookup": "lookup_keys<0>, insert_missing, commit_insert",
+    "lookup": "lookup_keys<0>, insert_missing",
     "pool": "pool_bags",
-    "push": "push_short, push_medium, push_chunks, push_long",
+    "push": "push_main (short | medium | chunk roles), push_long",
 }
 
 
@@ -85,7 +104,8 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     extra_steps = 5     # all-stage timing run after the timed region
-    n_batches = args.batches or min(args.steps + args.warmup + extra_steps, 64)
+    serial_steps = 0 if args.serial else 8   # plain pull+push afterwards, for comparison
+    n_batches = args.batches or min(args.steps + args.warmup + extra_steps + serial_steps, 64)
 
     def dev_keys(a):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).cuda()
@@ -176,6 +196,21 @@ def main():
                   "alg_bytes": int(per_stage[s]),
                   "gbps": round(per_stage[s] / max(allst[s][0] / max(allst[s][1], 1), 1e-9) / 1e6, 1)}
               for s in allst}
+    serial_ms = None
+    if serial_steps:
+        table.set_stage_timing(0)
+        first = last + 1
+        k, o, g = dev_batches[first % n_batches]
+        table.pull(k, o, cfg.n_examples, cfg.n_slots, pooled)      # one untimed step
+        table.push(g)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(first + 1, first + serial_steps):
+            k, o, g = dev_batches[i % n_batches]
+            table.pull(k, o, cfg.n_examples, cfg.n_slots, pooled)
+            table.push(g)
+        torch.cuda.synchronize()
+        serial_ms = (time.perf_counter() - c0) / (serial_steps - 1) * 1e3
     st = table.stats()
 
     # ---- CPU oracle on a bounded sample of the same workload ------------------------------
@@ -227,10 +262,12 @@ def main():
         "step_frac_of_peak": round(step_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "kernel": dominant + ": " + STAGE_KERNELS[dominant],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic(cfg.name, dominant),
                      "launch_ms": round(dom_ms, 4), "launches_timed": int(timed[dominant][1]),
                      "alg_bytes_per_launch": int(per_stage[dominant])},
         "stages": stages,
+        "serial_ms_per_step": None if serial_ms is None else round(serial_ms, 4),
         "cpu_baseline": cpu,
         "setup_s": round(setup_s, 1),
     }

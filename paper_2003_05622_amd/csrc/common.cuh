@@ -40,11 +40,12 @@ struct TableState {
 struct PullCtx {
   u32 n_unique;        // U
   u32 n_long;          // keys the push handles chunk by chunk
-  u32 n_medium;        // keys the push handles with one wave each
+  u32 med_overflow;    // unused
   u32 n_chunk_items;   // (key, chunk) work items of the push
   u32 n_evidence;      // sorted positions where a run of equal sorted bits mixes keys
   u32 sort_error;      // set if a look-back wait gave up (never expected)
   u32 pad[2];
+  u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
 };
 
 // SplitMix64 output function for state x (Steele, Lea, Flood 2014).  The row

@@ -70,7 +70,7 @@ struct WorkspaceLayout {
   size_t keys_a, keys_b, idx_a, idx_b, ghist, tickets, tile_rows, group_rows, head_rows,
       head_groups, evidence, bag_of, miss_list, med_list, long_list, chunk_items, partials, total;
   ContextLayout c[2];
-  uint64_t max_med, max_long, max_items, sort_tiles, head_tiles, shard_cap;
+  uint64_t med_cap, max_long, max_items, sort_tiles, head_tiles, shard_cap;
 };
 
 WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
@@ -79,7 +79,7 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   const uint64_t n1 = n ? n : 1;
   L.sort_tiles = (n1 + kSortTile - 1) / kSortTile;
   L.head_tiles = (n1 + kHeadTile - 1) / kHeadTile;
-  L.max_med = n1 / (kShortSeg + 1) + 1;     // keys with more than kShortSeg occurrences
+  L.med_cap = n1 / kCountShards + 2048;     // per shard: no shard's blocks see more keys
   L.max_long = n1 / (kMedSeg + 1) + 1;      // keys with more than kMedSeg occurrences
   L.max_items = n1 / kChunk + L.max_long + 1;
   size_t o = 0;
@@ -106,7 +106,7 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
     L.c[k].bagperm = o; o = align_up(o + n1 * 4);
     L.c[k].seg_off = o; o = align_up(o + (n1 + 1) * 4);
   }
-  L.med_list = o;    o = align_up(o + L.max_med * 4);
+  L.med_list = o;    o = align_up(o + (size_t)kCountShards * L.med_cap * 4);
   L.long_list = o;   o = align_up(o + L.max_long * 8);
   L.chunk_items = o; o = align_up(o + L.max_items * 8);
   L.partials = o;    o = align_up(o + L.max_items * (size_t)dim * 4);
@@ -206,18 +206,30 @@ template <int LPR>
 static void launch_pool(hps_table* t, int c, float* d_pooled, hipStream_t s) {
   const hps_table::Context& cx = t->cx[c];
   const unsigned blocks = grid_for(cx.n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
-  pool_bags<LPR><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags, (u32)cx.n_keys,
-                                                 t->w<i32>(t->wl.c[c].inverse),
-                                                 t->w<u32>(t->wl.c[c].rows), d_pooled);
+  if (t->dim <= (uint32_t)LPR * 4)
+    pool_bags<LPR, 1><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
+                                                      (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
+                                                      t->w<u32>(t->wl.c[c].rows), d_pooled);
+  else
+    pool_bags<LPR, 4><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
+                                                      (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
+                                                      t->w<u32>(t->wl.c[c].rows), d_pooled);
 }
 
 template <int LPR>
-static void launch_push(hps_table* t, uint64_t n, const PushArgs& a, hipStream_t s) {
-  push_short<LPR><<<grid_for(n, kPushThreads / LPR, kPushShortBlocks), kPushThreads, 0, s>>>(t->view, a);
-  push_medium<LPR><<<grid_for(n / (kShortSeg + 1) + 1, kPushThreads / kWave, kPushMediumBlocks),
-                     kPushThreads, 0, s>>>(t->view, a);
-  push_chunks<LPR><<<grid_for(n / kChunk + 1, 1, kPushChunkBlocks), kPushThreads, 0, s>>>(t->view, a);
-  push_long<LPR><<<grid_for(n / (kMedSeg + 1) + 1, 1, kPushLongBlocks), kPushThreads, 0, s>>>(t->view, a);
+static void launch_push(hps_table* t, uint64_t n, PushArgs& a, hipStream_t s) {
+  a.short_blocks = grid_for(n, kPushThreads / LPR, kPushShortBlocks);
+  a.medium_blocks = kPushMediumBlocks;
+  const unsigned chunk_blocks = grid_for(n / kChunk + 1, 1, kPushChunkBlocks);
+  const unsigned main_blocks = a.short_blocks + a.medium_blocks + chunk_blocks;
+  const unsigned long_blocks = grid_for(n / (kMedSeg + 1) + 1, 1, kPushLongBlocks);
+  if (t->dim <= (uint32_t)LPR * 4) {
+    push_main<LPR, 1><<<main_blocks, kPushThreads, 0, s>>>(t->view, a);
+    push_long<LPR, 1><<<long_blocks, kPushThreads, 0, s>>>(t->view, a);
+  } else {
+    push_main<LPR, 4><<<main_blocks, kPushThreads, 0, s>>>(t->view, a);
+    push_long<LPR, 4><<<long_blocks, kPushThreads, 0, s>>>(t->view, a);
+  }
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -323,7 +335,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.bag_of - wl.ghist) / 8, 0);
   reset_state<<<1, 64, 0, s>>>(t->view.st);
   for (int k = 0; k < 2; ++k)
-    set_ctx_empty<<<1, 1, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
+    set_ctx_empty<<<1, 64, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
   if (!launch_ok()) { delete t; return HPS_EDEVICE; }
   *out = t;
   return HPS_OK;
@@ -350,10 +362,10 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
   if (n) {
     if (d_weights)
       lookup_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                      d_acc, nullptr, nullptr, nullptr, nullptr, 0);
+                                                      d_acc, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     else
       lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                      nullptr, nullptr, nullptr, nullptr, nullptr, 0);
+                                                      nullptr, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
                                                     d_acc, nullptr, 0);
   }
@@ -381,7 +393,7 @@ hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
   if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
 
   if (n == 0) {
-    set_ctx_empty<<<1, 1, 0, s>>>(ctx, t->w<u32>(C.seg_off));
+    set_ctx_empty<<<1, 64, 0, s>>>(ctx, t->w<u32>(C.seg_off));
   } else {
     // a1: order the occurrences by the top bits of their keys
     stage_mark(t, HPS_STAGE_SORT, s);
@@ -464,15 +476,22 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
     const unsigned probe_blocks = grid_for(cx.n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
     u32* miss_list = t->w<u32>(t->wl.miss_list);
     const u32 shard_cap = (u32)t->wl.shard_cap;
+    OftenLists often;
+    often.seg_off = t->w<u32>(C.seg_off);
+    often.ctx = ctx;
+    often.med_list = t->w<u32>(t->wl.med_list);
+    often.med_cap = (u32)t->wl.med_cap;
+    often.long_list = t->w<uint2>(t->wl.long_list);
+    often.chunk_items = t->w<uint2>(t->wl.chunk_items);
     lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
                                                           nullptr, nullptr, nullptr, nullptr, miss_list,
-                                                          shard_cap);
+                                                          shard_cap, often);
     insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
                                                           nullptr, miss_list, shard_cap);
   }
-  commit_insert<<<1, 64, 0, s>>>(t->view.st);
+  if (!cx.n_bags) commit_insert<<<1, 64, 0, s>>>(t->view.st);   // else the pooling kernel does it
   stage_mark(t, HPS_STAGE_LOOKUP, s);
   // a3: gather rows and pool per bag
   if (cx.n_bags) {
@@ -516,6 +535,7 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
     a.grads = d_pooled_grads;
     a.ctx = t->ctx(c);
     a.med_list = t->w<u32>(L.med_list);
+    a.med_cap = (u32)L.med_cap;
     a.long_list = t->w<uint2>(L.long_list);
     a.chunk_items = t->w<uint2>(L.chunk_items);
     a.partials = t->w<float>(L.partials);
@@ -560,7 +580,7 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
   const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
                                                   nullptr, d_weights_out, d_acc_out, d_found_out,
-                                                  nullptr, 0);
+                                                  nullptr, 0, OftenLists());
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 

@@ -170,11 +170,12 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
     if (threadIdx.x == 0) {
       ctx->n_unique = 0;
       ctx->n_long = 0;
-      ctx->n_medium = 0;
+      ctx->med_overflow = 0;
       ctx->n_chunk_items = 0;
       ctx->n_evidence = 0;
       ctx->sort_error = 0;
     }
+    if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
   }
   {
     const u32 wave_global = (blockIdx.x * kPrepThreads + threadIdx.x) / kWave;

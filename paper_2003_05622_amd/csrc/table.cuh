@@ -36,8 +36,24 @@ struct TableView {
 constexpr int kProbeThreads = 256;
 constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
 constexpr int kProbeInFlight = 4;                             // keys a group probes at a time
-constexpr int kProbeMaxBlocks = 2048;
+constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
+constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
+constexpr u32 kShortSeg = 16;            // occurrences handled serially by one lane group
+constexpr u32 kMedSeg = 512;             // occurrences handled by one wave
+constexpr u32 kChunk = 1024;             // occurrences per queued chunk of a longer key
+
+// What the pull leaves for the push about keys that occur often (push.cuh): keys with
+// kShortSeg < occurrences <= kMedSeg go to a sharded list (shard b % 64 for block b,
+// med_cap entries per shard), keys with more are cut into chunks of kChunk positions.
+struct OftenLists {
+  const u32* seg_off;
+  PullCtx* ctx;
+  u32* med_list;
+  u32 med_cap;
+  uint2* long_list;     // (unique index, first chunk item)
+  uint2* chunk_items;   // (unique index, chunk number)
+};
 
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
 __device__ __forceinline__ u32 group_bits(u64 ballot) {
@@ -69,28 +85,34 @@ __global__ void __launch_bounds__(64) clear_error(TableState* st) {
   if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
 }
 __global__ void clear_dump_count(TableState* st) { st->dump_count = 0; }
-__global__ void set_ctx_empty(PullCtx* ctx, u32* seg_off) {
-  ctx->n_unique = 0;
-  ctx->n_long = 0;
-  ctx->n_medium = 0;
-  ctx->n_chunk_items = 0;
-  ctx->n_evidence = 0;
-  ctx->sort_error = 0;
-  seg_off[0] = 0;
+__global__ void __launch_bounds__(64) set_ctx_empty(PullCtx* ctx, u32* seg_off) {
+  if (threadIdx.x == 0) {
+    ctx->n_unique = 0;
+    ctx->n_long = 0;
+    ctx->med_overflow = 0;
+    ctx->n_chunk_items = 0;
+    ctx->n_evidence = 0;
+    ctx->sort_error = 0;
+    seg_off[0] = 0;
+  }
+  if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
 }
 
 // Adds the rows insert_missing created to the table size and clears the counters.
-__global__ void __launch_bounds__(64) commit_insert(TableState* st) {
-  u32 made = threadIdx.x < kCountShards ? st->made_shard[threadIdx.x] : 0;
+// Called by one whole wave, after insert_missing has finished.
+__device__ __forceinline__ void commit_insert_wave(TableState* st) {
+  const u32 lane = lane_id();
+  u32 made = lane < kCountShards ? st->made_shard[lane] : 0;
 #pragma unroll
   for (int d = 1; d < kWave; d <<= 1) made += __shfl_xor(made, d, kWave);
-  if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
-  if (threadIdx.x == 0) {
+  if (lane < kCountShards) st->miss_shard[lane] = st->made_shard[lane] = 0;
+  if (lane == 0) {
     st->size += made;
     st->inserted = made;
     st->miss_overflow = 0;
   }
 }
+__global__ void __launch_bounds__(64) commit_insert(TableState* st) { commit_insert_wave(st); }
 
 // Walks key's probe sequence from `line` on.  Returns the slot of the key, or
 // kNoRow with `line` left at the first line that has a free slot (slot_key holds
@@ -147,12 +169,14 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
             const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
             const float* __restrict__ w_in, const float* __restrict__ acc_in,
             float* __restrict__ w_out, float* __restrict__ acc_out,
-            uint8_t* __restrict__ found_out, u32* __restrict__ miss_list, u32 shard_cap) {
-  __shared__ u32 s_missing, s_base;
+            uint8_t* __restrict__ found_out, u32* __restrict__ miss_list, u32 shard_cap,
+            OftenLists often) {
+  __shared__ u32 s_missing, s_base, s_med, s_med_base;
   __shared__ u32 s_list[MODE == 0 ? kMissLdsCap : 1];
+  __shared__ u32 s_med_list[MODE == 0 ? kMedLdsCap : 1];
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
   if (load_error(t.st) != 0) return;
-  if (threadIdx.x == 0) s_missing = 0;
+  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; }
   __syncthreads();
   const u32 sub = threadIdx.x & 7;
   const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
@@ -189,6 +213,23 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
           const u32 at = atomicAdd(&s_missing, 1u);
           if (at < kMissLdsCap) s_list[at] = (u32)u;
         }
+        // sort the key into the push's work lists by its number of occurrences
+        const u32 len = often.seg_off[u + 1] - often.seg_off[u];
+        if (len > kMedSeg) {
+          const u32 n_chunks = (len + kChunk - 1) / kChunk;
+          const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
+          often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
+          for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
+        } else if (len > kShortSeg) {
+          const u32 at = atomicAdd(&s_med, 1u);
+          if (at < kMedLdsCap) {
+            s_med_list[at] = (u32)u;
+          } else {      // buffer full: append straight to the shard
+            const u32 shard = blockIdx.x % kCountShards;
+            const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
+            if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)u;
+          }
+        }
       }
       if (MODE == 2 && row != kNoRow) {
         float* wr = t.w + (u64)row * t.dim;
@@ -214,6 +255,15 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   }
   if (MODE == 0) {
     __syncthreads();
+    const u32 n_med = min(s_med, kMedLdsCap);
+    if (n_med) {
+      const u32 shard = blockIdx.x % kCountShards;
+      if (threadIdx.x == 0) s_med_base = atomicAdd(&often.ctx->med_count[shard], n_med);
+      __syncthreads();
+      for (u32 i = threadIdx.x; i < n_med; i += kProbeThreads)
+        if (s_med_base + i < often.med_cap)
+          often.med_list[(u64)shard * often.med_cap + s_med_base + i] = s_med_list[i];
+    }
     const u32 cnt = s_missing;
     if (cnt == 0) return;
     if (threadIdx.x == 0) s_base = atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], cnt);
