@@ -35,7 +35,7 @@ struct TableView {
 
 constexpr int kProbeThreads = 256;
 constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
-constexpr int kProbeInFlight = 4;                             // keys a group probes at a time
+constexpr int kProbeInFlight = 8;                             // keys a group probes at a time
 constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
 constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
@@ -117,6 +117,7 @@ __global__ void __launch_bounds__(64) commit_insert(TableState* st) { commit_ins
 // Walks key's probe sequence from `line` on.  Returns the slot of the key, or
 // kNoRow with `line` left at the first line that has a free slot (slot_key holds
 // this lane's slot of that line).  All 8 lanes of the group call it together.
+// No kernel that calls it changes slot keys, so plain (cacheable) loads are enough.
 __device__ __forceinline__ u32 probe_find(const TableView& t, u64 key, u32 sub, u64& line,
                                           u64& slot_key) {
   for (u64 step = 0; step < t.n_lines; ++step) {
@@ -124,7 +125,7 @@ __device__ __forceinline__ u32 probe_find(const TableView& t, u64 key, u32 sub, 
     if (hit) return (u32)(line * kSlotsPerLine + (__ffs(hit) - 1));
     if (group_bits(__ballot(slot_key == kEmptyKey))) return kNoRow;
     line = line + 1 == t.n_lines ? 0 : line + 1;
-    slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);
+    slot_key = t.keys[line * kSlotsPerLine + sub];
   }
   return kNoRow;
 }
@@ -193,7 +194,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
       const u64 u = u0 + (u64)k * n_groups;
-      slot_key[k] = u < n_keys ? load_slot_key(&t.keys[line[k] * kSlotsPerLine + sub]) : 0;
+      slot_key[k] = u < n_keys ? t.keys[line[k] * kSlotsPerLine + sub] : 0;
     }
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
