@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="plain hps_pull per step (default: hps_prepare of the next mini-batch "
                          "on a second stream while the current one is pushed)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, so that a counter run of this "
+                         "command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="time budget of the CPU oracle leg (0 disables it)")
     args = ap.parse_args()
@@ -151,6 +154,14 @@ def main():
             if more:
                 prepare(i + 1)
         table.push(g)
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up, and a look at which stage dominates ---------------------------------
     table.set_stage_timing(0b11111)
