@@ -72,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.hpo_get.argtypes = [vp, vp, u64, vp, vp, vp]
         L.hpo_dump.restype = i32
         L.hpo_dump.argtypes = [vp, vp, vp, vp, u64, vp]
+        L.hpo_dump_dirty.restype = i32
+        L.hpo_dump_dirty.argtypes = [vp, vp, vp, vp, u64, vp]
+        L.hpo_accumulate.restype = i32
+        L.hpo_accumulate.argtypes = [vp, vp, u64, vp, vp]
         _lib = L
     return _lib
 
@@ -193,6 +197,29 @@ class OracleTable:
         f = np.zeros(n, dtype=np.uint8)
         _check(lib().hpo_get(self._h, _p(keys), n, _p(w), _p(a), _p(f)), "get")
         return w, a, f.astype(bool)
+
+    def accumulate(self, keys, values) -> int:
+        """Adds the value rows onto the rows of their keys; returns the number of
+        distinct keys that are not in the table (skipped)."""
+        keys = _keys(keys)
+        n = keys.shape[0]
+        values = np.ascontiguousarray(values, dtype=np.float32).reshape(n, self.dim)
+        absent = ctypes.c_uint64(0)
+        _check(lib().hpo_accumulate(self._h, _p(keys), n, _p(values), ctypes.byref(absent)),
+               "accumulate")
+        return int(absent.value)
+
+    def dump_dirty(self) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        """Rows changed by push/accumulate since the last call, ascending by key."""
+        r = self.stored_rows
+        keys = np.empty(max(r, 1), dtype=np.uint64)
+        w = np.empty((max(r, 1), self.dim), dtype=np.float32)
+        a = np.empty((max(r, 1), self.acc_len), dtype=np.float32)
+        n = ctypes.c_uint64(0)
+        _check(lib().hpo_dump_dirty(self._h, _p(keys), _p(w), _p(a), r, ctypes.byref(n)),
+               "dump_dirty")
+        n = int(n.value)
+        return keys[:n].copy(), w[:n].copy(), a[:n].copy()
 
     def dump(self) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
         r = self.stored_rows

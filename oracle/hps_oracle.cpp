@@ -61,6 +61,7 @@ struct Table {
   std::vector<uint64_t> row_key;
   std::vector<float> w;                   // [rows, dim]
   std::vector<float> acc;                 // [rows, acc_len]
+  std::vector<uint8_t> dirty;             // [rows]: updated since the last dirty dump
   uint64_t implicit_rows = 0;             // declared-resident rows not materialised
   uint64_t implicit_seen = 0;             // ... of which materialised since
 
@@ -95,6 +96,7 @@ uint64_t add_row(Table& t, uint64_t key) {
   t.w.resize((r + 1) * t.dim);
   init_weights(t, key, &t.w[r * t.dim]);
   t.acc.resize((r + 1) * t.acc_len, t.init_acc);
+  t.dirty.resize(r + 1, 0);
   return r;
 }
 
@@ -304,8 +306,41 @@ int hpo_push(void* h, const float* grads) {
         a[j] = (float)G;
       }
     }
+    t.dirty[r] = 1;
   }
   t.pulled = false;
+  return OK;
+}
+
+// Section 4.1 "Operations", accumulate, in the paper's literal form: the input is a
+// collection of (key, value row) pairs and every value row is added onto the
+// parameter row its key references; a key that comes several times receives the
+// sum of its rows.  Keys the table does not hold are skipped and counted
+// (*n_absent): nothing is created (Algorithm 1 inserts the working set before
+// the mini-batch loop, so a training run never meets one).  The optimizer state
+// is not touched.
+int hpo_accumulate(void* h, const uint64_t* keys, uint64_t n, const float* values,
+                   uint64_t* n_absent) {
+  Table& t = *static_cast<Table*>(h);
+  if (t.pulled) return ESTATE;
+  for (uint64_t i = 0; i < n; ++i)
+    if (keys[i] == kReservedKey) return ERESERVED;
+  std::vector<uint64_t> uniq;
+  std::vector<int32_t> inverse;
+  dedup(keys, n, uniq, inverse);
+  std::vector<double> sum(uniq.size() * (size_t)t.dim, 0.0);
+  for (uint64_t i = 0; i < n; ++i)
+    for (uint32_t j = 0; j < t.dim; ++j)
+      sum[(size_t)inverse[i] * t.dim + j] += (double)values[i * t.dim + j];
+  uint64_t absent = 0;
+  for (size_t u = 0; u < uniq.size(); ++u) {
+    auto it = t.index.find(uniq[u]);
+    if (it == t.index.end()) { ++absent; continue; }
+    float* w = &t.w[it->second * t.dim];
+    for (uint32_t j = 0; j < t.dim; ++j) w[j] = (float)((double)w[j] + sum[u * t.dim + j]);
+    t.dirty[it->second] = 1;
+  }
+  if (n_absent) *n_absent = absent;
   return OK;
 }
 
@@ -341,6 +376,31 @@ int hpo_dump(void* h, uint64_t* keys_out, float* w_out, float* acc_out, uint64_t
     keys_out[o] = t.row_key[r];
     std::memcpy(w_out + o * t.dim, &t.w[r * t.dim], sizeof(float) * t.dim);
     std::memcpy(acc_out + o * t.acc_len, &t.acc[r * t.acc_len], sizeof(float) * t.acc_len);
+  }
+  return OK;
+}
+
+// Section 4 (MEM-PS side of Algorithm 1's last step): the host tier collects the
+// UPDATES of the HBM tier.  This variant hands over only the rows that a push or
+// an accumulate has changed since the previous call (or since the table was
+// built), ascending by key, and forgets the marks of the rows it handed over.
+// Rows that were only inserted or only created by a pull are not updates.
+int hpo_dump_dirty(void* h, uint64_t* keys_out, float* w_out, float* acc_out, uint64_t max_rows,
+                   uint64_t* n_rows) {
+  Table& t = *static_cast<Table*>(h);
+  std::vector<uint64_t> order;
+  for (uint64_t r = 0; r < t.row_key.size(); ++r)
+    if (t.dirty[r]) order.push_back(r);
+  *n_rows = order.size();
+  if (order.size() > max_rows) return EINVAL;
+  std::sort(order.begin(), order.end(),
+            [&](uint64_t a, uint64_t b) { return t.row_key[a] < t.row_key[b]; });
+  for (uint64_t o = 0; o < order.size(); ++o) {
+    const uint64_t r = order[o];
+    keys_out[o] = t.row_key[r];
+    std::memcpy(w_out + o * t.dim, &t.w[r * t.dim], sizeof(float) * t.dim);
+    std::memcpy(acc_out + o * t.acc_len, &t.acc[r * t.acc_len], sizeof(float) * t.acc_len);
+    t.dirty[r] = 0;
   }
   return OK;
 }

@@ -562,3 +562,110 @@ def test_workload_shapes_and_zipf_mass():
     frac_fresh = (bm.ids >= mid.n_prefill).mean()
     assert abs(frac_fresh - 0.05) < 0.01
     assert abs(np.diff(bm.offsets).mean() - 5.0) < 0.2
+
+
+# ----------------------------------------------------------------------------- accumulate
+
+def test_accumulate_exact_small_binary_fractions():
+    # Section 4.1 accumulate: values add onto the rows their keys reference.  All numbers are
+    # small binary fractions, so every sum is exact and the expected rows are written out.
+    t = OracleTable(16, 4)
+    keys = np.array([10, 20, 30], dtype=np.uint64)
+    w0 = np.array([[1.0, 2.0, -3.0, 0.5], [0.25, 0.0, 8.0, -1.0], [4.0, 4.0, 4.0, 4.0]], dtype=np.float32)
+    t.insert(keys, weights=w0)
+    _, a0, _ = t.get(keys)
+    absent = t.accumulate(np.array([20, 10, 20, 99, 20], dtype=np.uint64),
+                          np.array([[0.5, 0.5, 0.5, 0.5],
+                                    [-1.0, 0.25, 0.0, 2.0],
+                                    [0.125, 0.0, -8.0, 1.0],
+                                    [7.0, 7.0, 7.0, 7.0],        # key 99 is not stored: skipped
+                                    [0.25, 1.0, 0.0, 0.0]], dtype=np.float32))
+    assert absent == 1 and t.size == 3
+    w, a, f = t.get(np.array([10, 20, 30, 99], dtype=np.uint64))
+    assert f.tolist() == [True, True, True, False]
+    assert w[0].tolist() == [0.0, 2.25, -3.0, 2.5]
+    assert w[1].tolist() == [1.125, 1.5, 0.5, 0.5]             # three value rows summed, one step
+    assert w[2].tolist() == [4.0, 4.0, 4.0, 4.0]
+    assert np.array_equal(a[:3], a0)                            # optimizer state untouched
+
+
+def test_accumulate_vs_torch_index_add():
+    rng = np.random.default_rng(77)
+    dim, n_rows, n = 8, 500, 4000
+    keys = synth.mix64(np.arange(n_rows, dtype=np.uint64))
+    t = OracleTable(1000, dim)
+    t.insert(keys)
+    w0, a0, _ = t.get(keys)
+    pick = rng.integers(0, n_rows, size=n)
+    vals = rng.normal(0, 1e-2, size=(n, dim)).astype(np.float32)
+    assert t.accumulate(keys[pick], vals) == 0
+    want = torch.from_numpy(w0.astype(np.float64)).index_add_(
+        0, torch.from_numpy(pick), torch.from_numpy(vals.astype(np.float64))).numpy()
+    w, a, _ = t.get(keys)
+    # one rounding of an exactly (double) accumulated sum: at most half an ulp from torch's
+    assert np.array_equal(w, want.astype(np.float32))
+    assert np.array_equal(a, a0)
+    untouched = ~np.isin(np.arange(n_rows), pick)
+    assert np.array_equal(w[untouched], w0[untouched])
+
+
+def test_accumulate_state_and_reserved_key():
+    t = OracleTable(8, 4)
+    t.insert(np.array([1, 2], dtype=np.uint64))
+    with pytest.raises(OracleError):
+        t.accumulate(np.array([2**64 - 1], dtype=np.uint64), np.zeros((1, 4), np.float32))
+    t.pull(np.array([1], dtype=np.uint64), np.array([0, 1], dtype=np.int32))
+    with pytest.raises(OracleError):                            # between a pull and its push
+        t.accumulate(np.array([1], dtype=np.uint64), np.zeros((1, 4), np.float32))
+    t.push(np.zeros((1, 4), np.float32))
+    assert t.accumulate(np.zeros(0, np.uint64), np.zeros((0, 4), np.float32)) == 0
+
+
+def test_push_equals_accumulate_of_the_closed_form_step():
+    # Section 4.1: the paper's push hands the table a worker-computed delta.  With one key per
+    # bag and no repeats, delta = -lr * g / (sqrt(G + mean g^2) + eps) written out here must
+    # move the weights as push(g) does.
+    rng = np.random.default_rng(5)
+    dim, n = 8, 64
+    keys = synth.mix64(np.arange(n, dtype=np.uint64))
+    g = rng.normal(0, 1e-1, size=(n, dim)).astype(np.float32)
+    a = OracleTable(100, dim, lr=0.05, eps=1e-8, init_acc=0.1)
+    b = OracleTable(100, dim, lr=0.05, eps=1e-8, init_acc=0.1)
+    a.insert(keys); b.insert(keys)
+    a.pull(keys, np.arange(n + 1, dtype=np.int32))
+    a.push(g)
+    G = float(np.float32(0.1)) + (g.astype(np.float64) ** 2).mean(axis=1, keepdims=True)
+    delta = -float(np.float32(0.05)) * g.astype(np.float64) / (np.sqrt(G) + float(np.float32(1e-8)))
+    b.accumulate(keys, delta.astype(np.float32))
+    wa, _, _ = a.get(keys)
+    wb, _, _ = b.get(keys)
+    assert np.abs(wa.astype(np.float64) - wb.astype(np.float64)).max() <= 2.0 ** -24 * np.abs(wa).max() * 2
+
+
+# ----------------------------------------------------------------------------- dirty rows
+
+def test_dump_dirty_hands_over_exactly_the_updated_rows_once():
+    cfg = synth.scaled(synth.CONFIGS["tiny"], n_prefill=3000, n_examples=32, n_slots=4, steps=3)
+    t = OracleTable(cfg.capacity, cfg.dim)
+    t.insert(synth.prefill_keys(0, cfg.n_prefill))
+    k, _, _ = t.dump_dirty()
+    assert k.size == 0                                          # inserted rows are not updates
+    stream = synth.BatchStream(cfg)
+    seen = []
+    for _ in range(2):
+        b = stream.next()
+        t.pull(b.keys, b.offsets)
+        t.push(b.grads)
+        seen.append(b.keys)
+    want = np.unique(np.concatenate(seen))                      # includes keys created by the pulls
+    k, w, a = t.dump_dirty()
+    assert np.array_equal(k, want)
+    gw, ga, f = t.get(want)
+    assert f.all() and np.array_equal(w, gw) and np.array_equal(a, ga)
+    assert t.dump_dirty()[0].size == 0                          # marks are forgotten
+    some = want[::7]
+    assert t.accumulate(np.concatenate([some, [np.uint64(12345)]]),
+                        np.ones((some.size + 1, cfg.dim), np.float32)) == 1
+    k, w, _ = t.dump_dirty()
+    assert np.array_equal(k, some) and np.array_equal(w, gw[::7] + np.float32(1.0))
+    assert np.array_equal(t.dump()[0], np.unique(np.concatenate([synth.prefill_keys(0, cfg.n_prefill), want])))
