@@ -86,6 +86,7 @@ typedef struct {
   uint64_t last_n_keys;     /* key occurrences of the last pull                    */
   uint64_t last_n_unique;   /* unique keys of the last pull                        */
   uint64_t last_n_inserted; /* keys the last pull (or insert) created              */
+  uint64_t last_n_absent;   /* distinct keys the last hps_accumulate did not find  */
   int32_t error;            /* sticky device status (0 or a negative hps_status)   */
   int32_t pull_outstanding; /* 1 between a pull and its push                       */
 } hps_stats_t;
@@ -161,6 +162,19 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream);
  * Errors: HPS_ESTATE when no pull is outstanding. */
 hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream);
 
+/* Section 4.1 "accumulate" in the paper's literal form (Algorithm 2's per-GPU accumulate):
+ * the input is a collection of (key, value row) pairs and every value row is added onto
+ * the weights its key references.
+ *   d_keys   [n] (device, 8-byte aligned), d_values [n, dim] float32 (device, 16-byte aligned)
+ * A key that comes several times receives the sum of its rows (fixed-shape fp32 sums,
+ * no floating-point atomics: two runs give the same bits).  Keys the table does not hold
+ * are skipped, nothing is created; hps_stats().last_n_absent counts them.  Optimizer
+ * state is not touched; touched rows count as updated for hps_dump_dirty.
+ * Errors: HPS_ESTATE between hps_prepare / a pull and its push; HPS_EINVAL for
+ * n > max_keys; HPS_ERESERVED (sticky, nothing is added) if a key is all ones. */
+hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_values,
+                          void* stream);
+
 /* Section 3 "union of the referenced parameters": copies the outstanding pull's
  * ascending unique keys (d_uniq_out, room for n_keys) and per-occurrence ranks
  * (d_inverse_out [n_keys] int32, uniq[inverse[i]] == keys[i]); either may be NULL.
@@ -180,6 +194,15 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
  * first max_rows found are written). */
 hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, float* d_acc_out,
                     uint64_t max_rows, uint64_t* h_n_rows, void* stream);
+
+/* Section 4 / Algorithm 1's last step, incremental: the host tier collects the UPDATES of
+ * the HBM tier.  Like hps_dump, but only rows that a push or an accumulate has changed
+ * since the previous hps_dump_dirty (or since creation); the marks of the rows written
+ * out are cleared.  Rows that were only inserted, or only created by a pull, are not
+ * updates.  HPS_ENOMEM if max_rows was too small: the first max_rows found are written
+ * and unmarked, the others stay marked.  HPS_ESTATE between a pull and its push. */
+hps_status hps_dump_dirty(hps_table* t, uint64_t* d_keys_out, float* d_weights_out,
+                          float* d_acc_out, uint64_t max_rows, uint64_t* h_n_rows, void* stream);
 
 /* Waits for the stream and fills *h_out (host). */
 hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);

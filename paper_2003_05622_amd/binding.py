@@ -12,7 +12,8 @@ ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
-           "hps_push", "hps_last_unique", "hps_get", "hps_dump", "hps_stats", "hps_clear_error",
+           "hps_push", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
+           "hps_stats", "hps_clear_error",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
 STAGES = ("sort", "unique", "lookup", "pool", "push")
@@ -28,7 +29,7 @@ class Stats(ctypes.Structure):
     _fields_ = [("size", ctypes.c_uint64), ("capacity", ctypes.c_uint64),
                 ("n_slots", ctypes.c_uint64), ("last_n_keys", ctypes.c_uint64),
                 ("last_n_unique", ctypes.c_uint64), ("last_n_inserted", ctypes.c_uint64),
-                ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
+                ("last_n_absent", ctypes.c_uint64), ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
 
 
 _lib = None
@@ -64,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.hps_get.argtypes = [vp, vp, u64, vp, vp, vp, vp]
         L.hps_dump.restype = st
         L.hps_dump.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64), vp]
+        L.hps_dump_dirty.restype = st
+        L.hps_dump_dirty.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64), vp]
+        L.hps_accumulate.restype = st
+        L.hps_accumulate.argtypes = [vp, vp, u64, vp, vp]
         L.hps_stats.restype = st
         L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
         L.hps_clear_error.restype = st
@@ -198,7 +203,16 @@ class HpsTable:
                "hps_get")
         return w, a, f.bool()
 
-    def dump(self, max_rows: Optional[int] = None):
+    def accumulate(self, keys, values) -> None:
+        """Adds values[i] onto the row of keys[i] (summed per key; absent keys are skipped)."""
+        n = keys.numel()
+        if n and tuple(values.shape) != (n, self.dim):
+            raise ValueError("values must be [n, dim]")
+        _check(lib().hps_accumulate(self._h, _ptr(keys), n, _ptr(values), _stream()),
+               "hps_accumulate")
+
+    def dump(self, max_rows: Optional[int] = None, dirty: bool = False):
+        """All rows, or with dirty=True the rows updated since the last dirty dump."""
         import torch
         if max_rows is None:
             max_rows = self.stats().size
@@ -206,8 +220,9 @@ class HpsTable:
         w = torch.empty((max(max_rows, 1), self.dim), dtype=torch.float32, device=self.device)
         a = torch.empty((max(max_rows, 1), self.acc_len), dtype=torch.float32, device=self.device)
         n = ctypes.c_uint64(0)
-        _check(lib().hps_dump(self._h, _ptr(keys), _ptr(w), _ptr(a), max_rows, ctypes.byref(n),
-                              _stream()), "hps_dump")
+        fn = lib().hps_dump_dirty if dirty else lib().hps_dump
+        _check(fn(self._h, _ptr(keys), _ptr(w), _ptr(a), max_rows, ctypes.byref(n), _stream()),
+               "hps_dump_dirty" if dirty else "hps_dump")
         r = int(n.value)
         return keys[:r], w[:r], a[:r]
 

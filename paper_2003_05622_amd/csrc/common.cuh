@@ -26,7 +26,7 @@ struct TableState {
   unsigned long long size;      // keys stored
   unsigned long long inserted;  // keys created by the last pull / insert call
   int error;                    // sticky: 0 or a negative status
-  int pad;
+  int absent;                   // distinct keys the last accumulate did not find
   unsigned long long dump_count;  // rows seen by the running dump
   // Keys the running lookup found missing / rows the running insert created, spread
   // over shards so that blocks do not all hit one address.

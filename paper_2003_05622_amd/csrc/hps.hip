@@ -37,7 +37,7 @@ uint64_t slots_for(uint64_t capacity) {
 
 bool valid_opt(const hps_optimizer* o) {
   return o && (o->kind == HPS_OPT_ADAGRAD_ROWWISE || o->kind == HPS_OPT_ADAGRAD_ELEMENTWISE) &&
-         o->init_range >= 0.f && o->eps >= 0.f;
+         o->init_range >= 0.f && o->eps >= 0.f && o->init_acc >= 0.f;
 }
 
 bool valid_shape(uint64_t capacity, uint32_t dim) {
@@ -232,6 +232,106 @@ static void launch_push(hps_table* t, uint64_t n, PushArgs& a, hipStream_t s) {
   }
 }
 
+// a1 for context c: the kernels that turn (keys, offsets) into uniq / inverse / bagperm /
+// seg_off.  d_offsets == nullptr: every occurrence is its own bag.
+static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
+                         const int32_t* d_offsets, u32 n_bags, hipStream_t s) {
+  const WorkspaceLayout& L = t->wl;
+  const ContextLayout& C = L.c[c];
+  PullCtx* ctx = t->ctx(c);
+  if (n == 0) {
+    set_ctx_empty<<<1, 64, 0, s>>>(ctx, t->w<u32>(C.seg_off));
+  } else {
+    // a1: order the occurrences by the top bits of their keys
+    stage_mark(t, HPS_STAGE_SORT, s);
+    ++t->serial;
+    const u32 epoch = (u32)(t->serial % kEpochMod) + 1;
+    if (epoch == 1 && t->serial >= kEpochMod)   // the epochs start over: forget the old words
+      fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
+    const SortPlan plan = sort_plan(n);
+    u64* kcur = t->w<u64>(L.keys_a);
+    u64* kalt = t->w<u64>(L.keys_b);
+    u32* icur = t->w<u32>(L.idx_a);
+    u32* ialt = t->w<u32>(L.idx_b);
+    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kMaxPasses * kRadix;
+    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kMaxPasses * kRadix;
+    u32* tickets = t->w<u32>(L.tickets);
+    const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
+    sort_prepare<<<n_tiles < 512 ? n_tiles : 512, kPrepThreads, 0, s>>>(
+        d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, n_bags,
+        t->w<i32>(L.bag_of));
+    for (int p = 0; p < plan.n_pass; ++p) {
+      u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
+      u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
+      const int shift = plan.low_shift + p * kRadixBits;
+      if (p == 0) {
+        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, kcur, icur, n, shift,
+                                                             ghist, tile_rows, group_rows, plan.group,
+                                                             tickets, epoch, ctx);
+      } else {
+        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(kcur, icur, kalt, ialt, n, shift,
+                                                              ghist + p * kRadix, tile_rows, group_rows,
+                                                              plan.group, tickets + p, epoch, ctx);
+        u64* tk = kcur; kcur = kalt; kalt = tk;
+        u32* ti = icur; icur = ialt; ialt = ti;
+      }
+    }
+    stage_mark(t, HPS_STAGE_SORT, s);
+    // a1: unique keys, ranks, grouping (second instance only acts after a repair)
+    stage_mark(t, HPS_STAGE_UNIQUE, s);
+    const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
+    const u32 head_group = tile_group(head_tiles);
+    u32* evidence = t->w<u32>(L.evidence);
+    unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
+        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
+        tickets + kMaxPasses, epoch, t->w<i32>(L.bag_of), n_bags, t->w<u64>(C.uniq),
+        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
+    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, icur, kalt, ialt, n, plan, ctx, evidence);
+    unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
+        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
+        t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
+        tickets + kMaxPasses + 1, epoch, t->w<i32>(L.bag_of), n_bags, t->w<u64>(C.uniq),
+        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
+    stage_mark(t, HPS_STAGE_UNIQUE, s);
+  }
+}
+
+// a2 without creating anything, for context c: rows of the unique keys (kNoRow for a
+// key the table does not hold) and the push's work lists.
+static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
+  const ContextLayout& C = t->wl.c[c];
+  PullCtx* ctx = t->ctx(c);
+  OftenLists often;
+  often.seg_off = t->w<u32>(C.seg_off);
+  often.ctx = ctx;
+  often.med_list = t->w<u32>(t->wl.med_list);
+  often.med_cap = (u32)t->wl.med_cap;
+  often.long_list = t->w<uint2>(t->wl.long_list);
+  often.chunk_items = t->w<uint2>(t->wl.chunk_items);
+  const unsigned probe_blocks = grid_for(n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+  lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0, &ctx->n_unique,
+                                                        t->w<u32>(C.rows), nullptr, nullptr, nullptr,
+                                                        nullptr, nullptr, t->w<u32>(t->wl.miss_list),
+                                                        (u32)t->wl.shard_cap, often);
+}
+
+static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, PushArgs& a) {
+  const WorkspaceLayout& L = t->wl;
+  a.seg_off = t->w<u32>(L.c[c].seg_off);
+  a.bagperm = t->w<u32>(L.c[c].bagperm);
+  a.rows = t->w<u32>(L.c[c].rows);
+  a.grads = d_rows;
+  a.ctx = t->ctx(c);
+  a.med_list = t->w<u32>(L.med_list);
+  a.med_cap = (u32)L.med_cap;
+  a.long_list = t->w<uint2>(L.long_list);
+  a.chunk_items = t->w<uint2>(L.chunk_items);
+  a.partials = t->w<float>(L.partials);
+  a.lr = t->opt.lr;
+  a.eps = t->opt.eps;
+  a.kind = kind;
+}
+
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
   switch (lpr) {                               \
     case 1: CALL(1); break;                    \
@@ -381,72 +481,15 @@ hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
   if (n_keys > t->max_keys || n_bags > t->max_bags) return HPS_EINVAL;
   if ((uintptr_t)d_keys % 8 || (uintptr_t)d_offsets % 4) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const WorkspaceLayout& L = t->wl;
   const int c = t->current == 0 ? 1 : 0;        // the context the outstanding pull does not use
-  const ContextLayout& C = L.c[c];
   hps_table::Context& cx = t->cx[c];
-  PullCtx* ctx = t->ctx(c);
   const u32 n = (u32)n_keys;
   // order after the push that last read this context, and after the previous dedup
   // (the sort scratch is shared); both may have run on other streams
   if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
   if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
 
-  if (n == 0) {
-    set_ctx_empty<<<1, 64, 0, s>>>(ctx, t->w<u32>(C.seg_off));
-  } else {
-    // a1: order the occurrences by the top bits of their keys
-    stage_mark(t, HPS_STAGE_SORT, s);
-    ++t->serial;
-    const u32 epoch = (u32)(t->serial % kEpochMod) + 1;
-    if (epoch == 1 && t->serial >= kEpochMod)   // the epochs start over: forget the old words
-      fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
-    const SortPlan plan = sort_plan(n);
-    u64* kcur = t->w<u64>(L.keys_a);
-    u64* kalt = t->w<u64>(L.keys_b);
-    u32* icur = t->w<u32>(L.idx_a);
-    u32* ialt = t->w<u32>(L.idx_b);
-    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kMaxPasses * kRadix;
-    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kMaxPasses * kRadix;
-    u32* tickets = t->w<u32>(L.tickets);
-    const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    sort_prepare<<<n_tiles < 512 ? n_tiles : 512, kPrepThreads, 0, s>>>(
-        d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, (u32)n_bags,
-        t->w<i32>(L.bag_of));
-    for (int p = 0; p < plan.n_pass; ++p) {
-      u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
-      u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
-      const int shift = plan.low_shift + p * kRadixBits;
-      if (p == 0) {
-        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, kcur, icur, n, shift,
-                                                             ghist, tile_rows, group_rows, plan.group,
-                                                             tickets, epoch, ctx);
-      } else {
-        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(kcur, icur, kalt, ialt, n, shift,
-                                                              ghist + p * kRadix, tile_rows, group_rows,
-                                                              plan.group, tickets + p, epoch, ctx);
-        u64* tk = kcur; kcur = kalt; kalt = tk;
-        u32* ti = icur; icur = ialt; ialt = ti;
-      }
-    }
-    stage_mark(t, HPS_STAGE_SORT, s);
-    // a1: unique keys, ranks, grouping (second instance only acts after a repair)
-    stage_mark(t, HPS_STAGE_UNIQUE, s);
-    const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
-    const u32 head_group = tile_group(head_tiles);
-    u32* evidence = t->w<u32>(L.evidence);
-    unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
-        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
-        tickets + kMaxPasses, epoch, t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(C.uniq),
-        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
-    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, icur, kalt, ialt, n, plan, ctx, evidence);
-    unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
-        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
-        t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
-        tickets + kMaxPasses + 1, epoch, t->w<i32>(L.bag_of), (u32)n_bags, t->w<u64>(C.uniq),
-        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
-    stage_mark(t, HPS_STAGE_UNIQUE, s);
-  }
+  launch_dedup(t, c, d_keys, n, d_offsets, (u32)n_bags, s);
   if (!launch_ok()) return HPS_EDEVICE;
   if (hipEventRecord(cx.ready, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)
     return HPS_EDEVICE;
@@ -476,17 +519,7 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
     const unsigned probe_blocks = grid_for(cx.n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
     u32* miss_list = t->w<u32>(t->wl.miss_list);
     const u32 shard_cap = (u32)t->wl.shard_cap;
-    OftenLists often;
-    often.seg_off = t->w<u32>(C.seg_off);
-    often.ctx = ctx;
-    often.med_list = t->w<u32>(t->wl.med_list);
-    often.med_cap = (u32)t->wl.med_cap;
-    often.long_list = t->w<uint2>(t->wl.long_list);
-    often.chunk_items = t->w<uint2>(t->wl.chunk_items);
-    lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
-                                                          &ctx->n_unique, t->w<u32>(C.rows), nullptr,
-                                                          nullptr, nullptr, nullptr, nullptr, miss_list,
-                                                          shard_cap, often);
+    launch_lookup(t, c, cx.n_keys, s);
     insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
                                                           nullptr, miss_list, shard_cap);
@@ -527,21 +560,9 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   t->current = -1;
   if (cx.n_keys) {
-    const WorkspaceLayout& L = t->wl;
     PushArgs a;
-    a.seg_off = t->w<u32>(L.c[c].seg_off);
-    a.bagperm = t->w<u32>(L.c[c].bagperm);
-    a.rows = t->w<u32>(L.c[c].rows);
-    a.grads = d_pooled_grads;
-    a.ctx = t->ctx(c);
-    a.med_list = t->w<u32>(L.med_list);
-    a.med_cap = (u32)L.med_cap;
-    a.long_list = t->w<uint2>(L.long_list);
-    a.chunk_items = t->w<uint2>(L.chunk_items);
-    a.partials = t->w<float>(L.partials);
-    a.lr = t->opt.lr;
-    a.eps = t->opt.eps;
-    a.elementwise = t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE;
+    fill_push_args(t, c, d_pooled_grads,
+                   t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? kStepElementwise : kStepRowwise, a);
     stage_mark(t, HPS_STAGE_PUSH, s);
 #define CALL(LPR) launch_push<LPR>(t, cx.n_keys, a, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
@@ -551,6 +572,38 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   }
   if (hipEventRecord(cx.released, s) != hipSuccess) return HPS_EDEVICE;
   cx.released_set = true;
+  return HPS_OK;
+}
+
+hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_values,
+                          void* stream) {
+  if (!t || (n && (!d_keys || !d_values))) return HPS_EINVAL;
+  if (n > t->max_keys || (uintptr_t)d_keys % 8 || (uintptr_t)d_values % 16) return HPS_EINVAL;
+  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int c = 0;
+  hps_table::Context& cx = t->cx[c];
+  if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
+  if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
+  // every (key, value row) pair is a bag of its own: the dedup groups the pairs by key,
+  // the push kernels sum each group's value rows and add the sum onto the row
+  launch_dedup(t, c, d_keys, (u32)n, nullptr, (u32)n, s);
+  if (n) {
+    launch_lookup(t, c, n, s);
+    commit_absent<<<1, 64, 0, s>>>(t->view.st);
+    PushArgs a;
+    fill_push_args(t, c, d_values, kStepAdd, a);
+#define CALL(LPR) launch_push<LPR>(t, n, a, s)
+    HPS_DISPATCH_LPR(t->lpr, CALL)
+#undef CALL
+  } else {
+    commit_absent<<<1, 64, 0, s>>>(t->view.st);
+  }
+  if (!launch_ok()) return HPS_EDEVICE;
+  if (hipEventRecord(cx.released, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)
+    return HPS_EDEVICE;
+  cx.released_set = true;
+  t->scratch_set = true;
   return HPS_OK;
 }
 
@@ -584,14 +637,18 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
-hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, float* d_acc_out,
-                    uint64_t max_rows, uint64_t* h_n_rows, void* stream) {
+static hps_status dump_impl(hps_table* t, bool dirty, uint64_t* d_keys_out, float* d_weights_out,
+                            float* d_acc_out, uint64_t max_rows, uint64_t* h_n_rows, void* stream) {
   if (!t || !h_n_rows) return HPS_EINVAL;
   if (max_rows && (!d_keys_out || !d_weights_out || !d_acc_out)) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   clear_dump_count<<<1, 1, 0, s>>>(t->view.st);
-  dump_rows<<<4096, 256, 0, s>>>(t->view, d_keys_out, d_weights_out, d_acc_out, max_rows,
-                                 &t->view.st->dump_count);
+  if (dirty)
+    dump_rows<true><<<4096, 256, 0, s>>>(t->view, d_keys_out, d_weights_out, d_acc_out, max_rows,
+                                         &t->view.st->dump_count);
+  else
+    dump_rows<false><<<4096, 256, 0, s>>>(t->view, d_keys_out, d_weights_out, d_acc_out, max_rows,
+                                          &t->view.st->dump_count);
   if (!launch_ok()) return HPS_EDEVICE;
   unsigned long long count = 0;
   if (hipMemcpyAsync(&count, &t->view.st->dump_count, sizeof(count), hipMemcpyDeviceToHost, s) != hipSuccess)
@@ -599,6 +656,17 @@ hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, fl
   if (hipStreamSynchronize(s) != hipSuccess) return HPS_EDEVICE;
   *h_n_rows = count;
   return count > max_rows ? HPS_ENOMEM : HPS_OK;
+}
+
+hps_status hps_dump(hps_table* t, uint64_t* d_keys_out, float* d_weights_out, float* d_acc_out,
+                    uint64_t max_rows, uint64_t* h_n_rows, void* stream) {
+  return dump_impl(t, false, d_keys_out, d_weights_out, d_acc_out, max_rows, h_n_rows, stream);
+}
+
+hps_status hps_dump_dirty(hps_table* t, uint64_t* d_keys_out, float* d_weights_out,
+                          float* d_acc_out, uint64_t max_rows, uint64_t* h_n_rows, void* stream) {
+  if (t && t->current >= 0) return HPS_ESTATE;
+  return dump_impl(t, true, d_keys_out, d_weights_out, d_acc_out, max_rows, h_n_rows, stream);
 }
 
 hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
@@ -618,6 +686,7 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->last_n_keys = t->last_n_keys;
   h_out->last_n_unique = ctx.n_unique;
   h_out->last_n_inserted = st.inserted;
+  h_out->last_n_absent = (uint64_t)st.absent;
   h_out->error = st.error;
   h_out->pull_outstanding = t->current >= 0 ? 1 : 0;
   return HPS_OK;

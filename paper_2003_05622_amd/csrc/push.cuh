@@ -31,6 +31,9 @@ constexpr int kPushChunkBlocks = 512;
 constexpr int kPushLongBlocks = 256;
 constexpr int kPushInFlight = 8;  // gradient rows a lane group has in flight
 constexpr u32 kBagMask = 0x7FFFFFFFu;
+constexpr int kStepRowwise = 0;      // Adagrad, one accumulator per row
+constexpr int kStepElementwise = 1;  // Adagrad, one accumulator per element
+constexpr int kStepAdd = 2;          // Section 4.1 accumulate: the summed values are added
 
 struct PushArgs {
   const u32* seg_off;
@@ -45,17 +48,31 @@ struct PushArgs {
   u32 short_blocks, medium_blocks;   // roles of push_main's blocks: short, medium, chunks
   float* partials;      // [chunk item][dim]
   float lr, eps;
-  int elementwise;
+  int kind;   // what a touched row takes: kStepRowwise, kStepElementwise or kStepAdd
 };
 
-// One optimizer step on row r with the row's summed gradient held as float4
-// columns spread over the LPR lanes of a group.
+// One step on row r with the row's summed gradient (or summed values) held as
+// float4 columns spread over the LPR lanes of a group.  Marks the row as updated.
 template <int LPR, int COLS>
 __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const float4* g, u32 sub,
-                                            float lr, float eps, int elementwise) {
+                                            float lr, float eps, int kind) {
   const u32 dim4 = t.dim >> 2;
   float4* w = reinterpret_cast<float4*>(t.w + (u64)r * t.dim);
-  if (!elementwise) {
+  if (kind == kStepAdd) {
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+      const u32 col = sub + c * LPR;
+      if (col < dim4) {
+        float4 v = w[col];
+        v.x += g[c].x; v.y += g[c].y; v.z += g[c].z; v.w += g[c].w;
+        w[col] = v;
+      }
+    }
+    if (sub == 0) {
+      float* G = t.acc + (u64)r * t.acc_len;
+      *G = acc_marked(*G);
+    }
+  } else if (kind == kStepRowwise) {
     float ss = 0.f;
 #pragma unroll
     for (int c = 0; c < COLS; ++c)
@@ -63,7 +80,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
 #pragma unroll
     for (int d = LPR / 2; d > 0; d >>= 1) ss += __shfl_xor(ss, d, kWave);
     float* G = t.acc + (u64)r;
-    const float Gn = *G + ss / (float)t.dim;
+    const float Gn = acc_value(*G) + ss / (float)t.dim;
     const float scale = lr / (sqrtf(Gn) + eps);
 #pragma unroll
     for (int c = 0; c < COLS; ++c) {
@@ -74,7 +91,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
         w[col] = v;
       }
     }
-    if (sub == 0) *G = Gn;
+    if (sub == 0) *G = acc_marked(Gn);
   } else {
     float4* G = reinterpret_cast<float4*>(t.acc + (u64)r * t.dim);
 #pragma unroll
@@ -82,11 +99,12 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
       const u32 col = sub + c * LPR;
       if (col < dim4) {
         float4 a = G[col], v = w[col];
-        a.x += g[c].x * g[c].x; a.y += g[c].y * g[c].y; a.z += g[c].z * g[c].z; a.w += g[c].w * g[c].w;
+        a.x = acc_value(a.x) + g[c].x * g[c].x; a.y += g[c].y * g[c].y; a.z += g[c].z * g[c].z; a.w += g[c].w * g[c].w;
         v.x -= lr * g[c].x / (sqrtf(a.x) + eps);
         v.y -= lr * g[c].y / (sqrtf(a.y) + eps);
         v.z -= lr * g[c].z / (sqrtf(a.z) + eps);
         v.w -= lr * g[c].w / (sqrtf(a.w) + eps);
+        if (col == 0) a.x = acc_marked(a.x);
         G[col] = a;
         w[col] = v;
       }
@@ -164,7 +182,7 @@ __device__ __forceinline__ void push_short_role(const TableView& t, const PushAr
 #pragma unroll
     for (int c = 0; c < COLS; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     add_positions<LPR, COLS>(g, a, lo, hi, 1, t.dim, sub);
-    adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+    adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.kind);
   }
 }
 
@@ -197,7 +215,7 @@ __device__ __forceinline__ void push_medium_role(const TableView& t, const PushA
       }
     }
     const u32 r = a.rows[u];
-    if (group == 0 && r != kNoRow) adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+    if (group == 0 && r != kNoRow) adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.kind);
   }
 }
 
@@ -280,7 +298,7 @@ __global__ void __launch_bounds__(kPushThreads) push_long(TableView t, PushArgs 
     add_grad_row<LPR, COLS>(g, a.partials, seg.y + c, t.dim, sub);
   block_tree_sum<LPR, COLS>(g, lds, t.dim >> 2);
   const u32 r = a.rows[seg.x];
-  if (group == 0 && r != kNoRow) adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.elementwise);
+  if (group == 0 && r != kNoRow) adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.kind);
   }
 }
 

@@ -177,7 +177,10 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
     }
     if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
   }
-  {
+  if (offsets == nullptr) {     // every occurrence is its own bag
+    for (u32 i = blockIdx.x * kPrepThreads + threadIdx.x; i < n; i += gridDim.x * kPrepThreads)
+      bag_of[i] = (i32)i;
+  } else {
     const u32 wave_global = (blockIdx.x * kPrepThreads + threadIdx.x) / kWave;
     const u32 n_waves = gridDim.x * (kPrepThreads / kWave);
     for (u32 b0 = wave_global * kWave; b0 < n_bags; b0 += n_waves * kWave) {

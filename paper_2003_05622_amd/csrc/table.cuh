@@ -55,6 +55,18 @@ struct OftenLists {
   uint2* chunk_items;   // (unique index, chunk number)
 };
 
+// "Updated since the last dirty dump" is kept in the sign bit of a row's first
+// accumulator element: accumulators are sums of squares, never negative, so the bit
+// is free, and the push rewrites that element anyway -- marking costs no traffic.
+// Every reader takes the absolute value.
+__device__ __forceinline__ float acc_value(float stored) { return fabsf(stored); }
+__device__ __forceinline__ float acc_marked(float value) {
+  return __uint_as_float(__float_as_uint(value) | 0x80000000u);
+}
+__device__ __forceinline__ bool acc_is_marked(float stored) {
+  return (__float_as_uint(stored) & 0x80000000u) != 0;
+}
+
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
 __device__ __forceinline__ u32 group_bits(u64 ballot) {
   return (u32)(ballot >> (lane_id() & ~7u)) & 0xFFu;
@@ -74,7 +86,7 @@ __global__ void __launch_bounds__(64) reset_state(TableState* st) {
     st->size = 0;
     st->inserted = 0;
     st->error = 0;
-    st->pad = 0;
+    st->absent = 0;
     st->dump_count = 0;
   }
   if (threadIdx.x < kCountShards) st->miss_shard[threadIdx.x] = st->made_shard[threadIdx.x] = 0;
@@ -113,6 +125,20 @@ __device__ __forceinline__ void commit_insert_wave(TableState* st) {
   }
 }
 __global__ void __launch_bounds__(64) commit_insert(TableState* st) { commit_insert_wave(st); }
+
+// After a lookup that creates nothing (accumulate): the number of keys not found
+// goes to st->absent, the counters are cleared.
+__global__ void __launch_bounds__(64) commit_absent(TableState* st) {
+  const u32 lane = lane_id();
+  u32 missing = lane < kCountShards ? st->miss_shard[lane] : 0;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) missing += __shfl_xor(missing, d, kWave);
+  if (lane < kCountShards) st->miss_shard[lane] = 0;
+  if (lane == 0) {
+    st->absent = (int)missing;
+    st->miss_overflow = 0;
+  }
+}
 
 // Walks key's probe sequence from `line` on.  Returns the slot of the key, or
 // kNoRow with `line` left at the first line that has a free slot (slot_key holds
@@ -236,7 +262,8 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         float* wr = t.w + (u64)row * t.dim;
         for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
         float* ar = t.acc + (u64)row * t.acc_len;
-        for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = acc_in ? acc_in[u * t.acc_len + j] : t.init_acc;
+        for (u32 j = sub; j < t.acc_len; j += 8)
+          ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
       }
       if (MODE == 3) {
         if (sub == 0) found_out[u] = row != kNoRow;
@@ -244,7 +271,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
           const float* wr = t.w + (u64)row * t.dim;
           for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = wr[j];
           const float* ar = t.acc + (u64)row * t.acc_len;
-          for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = ar[j];
+          for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = acc_value(ar[j]);
         }
       }
     }
@@ -336,7 +363,8 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
     float* ar = t.acc + (u64)row * t.acc_len;
     if (w_in) {
       for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
-      for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = acc_in ? acc_in[u * t.acc_len + j] : t.init_acc;
+      for (u32 j = sub; j < t.acc_len; j += 8)
+        ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
     } else {
       const u64 base = mix64(key ^ t.init_seed);
       for (u32 j = sub; j < t.dim; j += 8) wr[j] = init_weight(base, j, t.init_range);
@@ -348,8 +376,10 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
 }
 
-// dump: every occupied slot, compacted through one counter per block of slots
-// (order unspecified).
+// dump: every occupied slot (DIRTY: every occupied slot whose row is marked as
+// updated; the mark of a row that is written out is cleared), compacted through one
+// counter per block of slots (order unspecified).
+template <bool DIRTY>
 __global__ void __launch_bounds__(256)
 dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
           float* __restrict__ acc_out, u64 max_rows, unsigned long long* __restrict__ counter) {
@@ -360,7 +390,8 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
   for (u64 round = blockIdx.x; round < n_rounds; round += gridDim.x) {
     const u64 s = round * 256 + threadIdx.x;
     const u64 key = s < n_slots ? t.keys[s] : kEmptyKey;
-    const bool used = key != kEmptyKey;
+    bool used = key != kEmptyKey;
+    if (DIRTY && used) used = acc_is_marked(t.acc[s * t.acc_len]);
     u32 total;
     const u32 before = block_excl_sum<256>(used ? 1u : 0u, scratch, &total);
     if (threadIdx.x == 0 && total) s_base = atomicAdd(counter, (unsigned long long)total);
@@ -370,7 +401,8 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
       if (o < max_rows) {
         keys_out[o] = key;
         for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = t.w[s * t.dim + j];
-        for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = t.acc[s * t.acc_len + j];
+        for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = acc_value(t.acc[s * t.acc_len + j]);
+        if (DIRTY) t.acc[s * t.acc_len] = acc_value(t.acc[s * t.acc_len]);
       }
     }
     __syncthreads();

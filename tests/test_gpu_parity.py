@@ -33,7 +33,9 @@ def assert_close(got, want, what):
         what, err.max(), np.unravel_index(err.argmax(), err.shape))
 
 
-def compare_tables(gt, ot, what):
+def compare_tables(gt, ot, what, touched_keys=None):
+    """touched_keys: keys whose rows may differ in the last bits (default: the rows whose
+    accumulator has moved; an accumulate leaves no such trace, so its tests pass the keys)."""
     k, w, a = gt.dump()
     k, w, a = host_keys(k), w.cpu().numpy(), a.cpu().numpy()
     order = np.argsort(k, kind="stable")
@@ -43,6 +45,8 @@ def compare_tables(gt, ot, what):
     assert_close(w, ow, what + " weights")
     assert_close(a, oa, what + " accumulators")
     untouched = (oa == np.float32(ot_init_acc(ot))).all(axis=1)
+    if touched_keys is not None:
+        untouched &= ~np.isin(ok, touched_keys)
     assert np.array_equal(w[untouched].view(np.uint32), ow[untouched].view(np.uint32)), \
         what + ": rows that were only initialised must be bit-identical"
     assert gt.stats().size == ot.size
@@ -256,3 +260,126 @@ def test_dump_insert_roundtrip():
     o1, o2 = torch.argsort(k), torch.argsort(k2)
     assert torch.equal(k[o1], k2[o2]) and torch.equal(w[o1], w2[o2]) and torch.equal(a[o1], a2[o2])
     assert g2.stats().size == k.numel()
+
+
+def zipf_pairs(rng, keys, n, dim, s=1.2):
+    """n (key, value row) pairs whose keys repeat with a Zipf-like skew: a few keys come
+    thousands of times (long / chunked reductions), most once or twice."""
+    w = 1.0 / np.arange(1, keys.size + 1) ** s
+    pick = rng.choice(keys.size, size=n, p=w / w.sum())
+    return keys[pick], rng.normal(0, 1e-3, size=(n, dim)).astype(np.float32)
+
+
+@pytest.mark.parametrize("opt", [hps.ADAGRAD_ROWWISE, hps.ADAGRAD_ELEMENTWISE])
+def test_accumulate_literal_form(opt):
+    # Section 4.1 accumulate: value rows are added onto the rows of their keys
+    rng = np.random.default_rng(9)
+    cfg = synth.scaled(synth.CONFIGS["mid"], n_prefill=50_000, n_examples=64, n_slots=8)
+    gt, ot = make_pair(cfg, 300_000, opt)
+    pre = synth.prefill_keys(0, cfg.n_prefill)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+    touched = []
+    for n in (250_000, 0, 1, 70_001):
+        k, v = zipf_pairs(rng, pre, n, cfg.dim)
+        touched.append(k)
+        if n > 1:      # some keys the table does not hold: skipped, counted, nothing created
+            k = k.copy()
+            k[:: 997] = synth.mix64(np.arange(2**50, 2**50 + k[::997].size, dtype=np.uint64))
+        print("accumulate", n, flush=True)
+        gt.accumulate(dev_keys(k), torch.from_numpy(v).cuda())
+        absent = ot.accumulate(k, v)
+        st = gt.stats()
+        assert st.error == 0 and st.last_n_absent == absent and st.size == ot.size
+    touched = np.concatenate(touched)
+    compare_tables(gt, ot, "after accumulate", touched)
+    # works between training steps, and not inside one
+    b = synth.BatchStream(cfg).next()
+    dk, do = dev_keys(b.keys), torch.from_numpy(b.offsets).cuda()
+    pooled = gt.pull(dk, do, cfg.n_examples, cfg.n_slots)
+    assert_close(pooled.cpu().numpy(), ot.pull(b.keys, b.offsets), "pooled after accumulate")
+    with pytest.raises(hps.HpsError):
+        gt.accumulate(dk[:4], torch.zeros((4, cfg.dim), device="cuda"))
+    gt.push(torch.from_numpy(b.grads).cuda())
+    ot.push(b.grads)
+    compare_tables(gt, ot, "step after accumulate", touched)
+
+
+def test_accumulate_is_deterministic_and_rejects_the_reserved_key():
+    rng = np.random.default_rng(10)
+    pre = synth.prefill_keys(0, 20_000)
+    k, v = zipf_pairs(rng, pre, 200_000, 16, s=1.4)
+    dumps = []
+    for _ in range(2):
+        gt = hps.HpsTable(40_000, 16, 200_000, 16)
+        gt.insert(dev_keys(pre))
+        gt.accumulate(dev_keys(k), torch.from_numpy(v).cuda())
+        kk, w, a = gt.dump()
+        order = np.argsort(host_keys(kk), kind="stable")
+        dumps.append((host_keys(kk)[order], w.cpu().numpy()[order], a.cpu().numpy()[order]))
+    for x, y in zip(*dumps):
+        assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+    bad = k[:100].copy()
+    bad[50] = np.uint64(2**64 - 1)
+    gt.accumulate(dev_keys(bad), torch.ones((100, 16), device="cuda"))
+    assert gt.stats().error == hps.ERESERVED
+    gt.clear_error()
+    kk, w, _ = gt.dump()
+    order = np.argsort(host_keys(kk), kind="stable")
+    assert np.array_equal(w.cpu().numpy()[order], dumps[1][1])      # nothing was added
+
+
+@pytest.mark.parametrize("opt", [hps.ADAGRAD_ROWWISE, hps.ADAGRAD_ELEMENTWISE])
+def test_dump_dirty_rows(opt):
+    cfg = synth.scaled(synth.CONFIGS["insert_heavy"], n_prefill=40_000, n_examples=128, n_slots=10)
+    gt, ot = make_pair(cfg, 20_000, opt)
+    pre = synth.prefill_keys(0, cfg.n_prefill)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+
+    def compare_dirty(what):
+        k, w, a = gt.dump(dirty=True)
+        k, w, a = host_keys(k), w.cpu().numpy(), a.cpu().numpy()
+        order = np.argsort(k, kind="stable")
+        ok, ow, oa = ot.dump_dirty()
+        assert np.array_equal(k[order], ok), what + ": dirty key sets differ"
+        assert_close(w[order], ow, what + " weights")
+        assert_close(a[order], oa, what + " accumulators")
+        return ok
+
+    assert compare_dirty("after insert").size == 0
+    stream = synth.BatchStream(cfg)
+    for step in range(3):
+        b = stream.next()
+        dk, do = dev_keys(b.keys), torch.from_numpy(b.offsets).cuda()
+        gt.pull(dk, do, cfg.n_examples, cfg.n_slots)
+        ot.pull(b.keys, b.offsets)
+        if step == 2:
+            with pytest.raises(hps.HpsError):                   # not inside a step
+                gt.dump(dirty=True)
+        gt.push(torch.from_numpy(b.grads).cuda())
+        ot.push(b.grads)
+        if step == 0:
+            assert compare_dirty("after step 0").size == np.unique(b.keys).size
+    assert compare_dirty("after steps 1-2").size > 0
+    assert compare_dirty("nothing since").size == 0
+    rng = np.random.default_rng(3)
+    k, v = zipf_pairs(rng, pre, 5000, cfg.dim)
+    gt.accumulate(dev_keys(k), torch.from_numpy(v).cuda())
+    ot.accumulate(k, v)
+    assert compare_dirty("after accumulate").size == np.unique(k).size
+    # too small a buffer: what fits is handed over, the rest stays marked
+    b = stream.next()
+    gt.pull(dev_keys(b.keys), torch.from_numpy(b.offsets).cuda(), cfg.n_examples, cfg.n_slots)
+    gt.push(torch.from_numpy(b.grads).cuda())
+    want = np.unique(b.keys)
+    with pytest.raises(hps.HpsError):
+        gt.dump(max_rows=want.size // 2, dirty=True)
+    rest, _, _ = gt.dump(dirty=True)
+    assert rest.numel() == want.size - want.size // 2
+    assert np.isin(host_keys(rest), want).all()
+    compare_tables_keys_only = gt.dump()[0]
+    assert compare_tables_keys_only.numel() == gt.stats().size
+    # accumulators read back without the mark
+    _, a, f = gt.get(dev_keys(want))
+    assert f.all().item() and (a >= 0).all().item()
