@@ -48,6 +48,36 @@ struct PullCtx {
   u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
 };
 
+// Keys that make up a large share of a mini-batch (bucket.cuh).  HeavySet: ascending,
+// padded with all-ones.  HeavyRaw: the keys the last lookup saw often, in arrival
+// order; only a hint, readers cope with any content.
+constexpr int kMaxHeavy = 255;
+constexpr int kHeavyTopBits = 10;
+struct HeavySet {
+  u32 count;
+  u32 pad;
+  u64 keys[kMaxHeavy + 1];
+  // per value of a key's top kHeavyTopBits bits: index of the first heavy key with these
+  // top bits (low half) and how many there are (high half)
+  u32 span[1 << kHeavyTopBits];
+};
+struct HeavyRaw {
+  u32 count;
+  u32 pad;
+  u64 keys[kMaxHeavy + 1];
+};
+// Lookup s (s = 1, 2, ...) fills raw[s % 3]; the kernel after it puts that list in order
+// as set[s % 3] and empties raw[(s + 1) % 3] for the next lookup.  A dedup issued when s
+// lookups have been issued reads set[(s - 1) % 3]: that lookup is certainly complete (the
+// dedup's context was released by a later push) and nobody writes the slot again before
+// lookup s + 2, which needs this dedup's result.  So every kernel of a dedup sees the
+// same, unchanging list, whatever streams the calls were issued on.
+constexpr u32 kHeavyRing = 3;
+struct HeavyRing {
+  HeavyRaw raw[kHeavyRing];
+  HeavySet set[kHeavyRing];
+};
+
 // SplitMix64 output function for state x (Steele, Lea, Flood 2014).  The row
 // initialiser is defined on top of it.
 __device__ __forceinline__ u64 mix64(u64 x) {

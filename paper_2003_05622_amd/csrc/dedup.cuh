@@ -1,5 +1,5 @@
 // Key dedup, part 2: from the occurrences sorted by the top bits of their keys
-// (skeys[j], sidx[j]) to
+// (skeys[j], spay[j]; payload = occurrence index | bag << 32) to
 //   uniq[U]      ascending unique keys
 //   inverse[N]   rank of each occurrence's key among them
 //   bagperm[N]   bag of each occurrence, occurrences grouped by key (ascending key)
@@ -40,7 +40,7 @@ struct FixLds {
   u32 scratch[kFixThreads / kWave + 1];
 };
 
-__device__ void wg_radix_pass(const u64* ksrc, const u32* isrc, u64* kdst, u32* idst, u32 a, u32 b,
+__device__ void wg_radix_pass(const u64* ksrc, const u64* isrc, u64* kdst, u64* idst, u32 a, u32 b,
                               int shift, FixLds& L) {
   const u32 tid = threadIdx.x, wave = tid / kWave;
   const u64 lt = lanemask_lt();
@@ -56,7 +56,7 @@ __device__ void wg_radix_pass(const u64* ksrc, const u32* isrc, u64* kdst, u32* 
     const u32 j = base + tid;
     const bool valid = j < b;
     const u64 key = valid ? ksrc[j] : 0;
-    const u32 idx = valid ? isrc[j] : 0;
+    const u64 idx = valid ? isrc[j] : 0;
     const u32 d = key_digit(key, shift);
     u32 before, same;
     match_digit(d, valid, lt, &before, &same);
@@ -80,7 +80,7 @@ __device__ void wg_radix_pass(const u64* ksrc, const u32* isrc, u64* kdst, u32* 
 
 // Orders the pairs in [a, b) by full key; equal keys keep their order.  Eight passes
 // (an even number), so the result ends up in (skeys, sidx) again.
-__device__ void wg_sort_range_full(u64* skeys, u32* sidx, u64* kalt, u32* ialt, u32 a, u32 b,
+__device__ void wg_sort_range_full(u64* skeys, u64* sidx, u64* kalt, u64* ialt, u32 a, u32 b,
                                    FixLds& L) {
   for (int w = threadIdx.x; w < kFixWaves * kRadix; w += kFixThreads) (&L.wave_cnt[0][0])[w] = 0;
   __syncthreads();
@@ -91,8 +91,8 @@ __device__ void wg_sort_range_full(u64* skeys, u32* sidx, u64* kalt, u32* ialt, 
 }
 
 __global__ void __launch_bounds__(kFixThreads)
-fix_mixed_runs(u64* __restrict__ skeys, u32* __restrict__ sidx, u64* __restrict__ kalt,
-               u32* __restrict__ ialt, u32 n, SortPlan plan, const PullCtx* __restrict__ ctx,
+fix_mixed_runs(u64* __restrict__ skeys, u64* __restrict__ sidx, u64* __restrict__ kalt,
+               u64* __restrict__ ialt, u32 n, SortPlan plan, const PullCtx* __restrict__ ctx,
                const u32* __restrict__ evidence) {
   const u32 E = ctx->n_evidence;
   if (E == 0) return;
@@ -145,14 +145,13 @@ fix_mixed_runs(u64* __restrict__ skeys, u32* __restrict__ sidx, u64* __restrict_
   for (u32 r = wave; r < E; r += kFixWaves) {
     const u32 a = run_lo[r], len = run_hi[r] - a;
     if (len == 0 || len > (u32)kWave) continue;
-    u64 key = 0;
-    u32 idx = 0;
+    u64 key = 0, idx = 0;       // idx: the payload; its low half (the index) breaks ties
     if (lane < len) { key = skeys[a + lane]; idx = sidx[a + lane]; }
     u32 rank = 0;
     for (u32 m = 0; m < len; ++m) {
       const u64 okey = __shfl(key, (int)m, kWave);
-      const u32 oidx = __shfl(idx, (int)m, kWave);
-      rank += (okey < key || (okey == key && oidx < idx)) ? 1u : 0u;
+      const u64 oidx = __shfl(idx, (int)m, kWave);
+      rank += (okey < key || (okey == key && (u32)oidx < (u32)idx)) ? 1u : 0u;
     }
     if (lane < len) { skeys[a + rank] = key; sidx[a + rank] = idx; }
   }
@@ -172,16 +171,17 @@ fix_mixed_runs(u64* __restrict__ skeys, u32* __restrict__ sidx, u64* __restrict_
 // fix_mixed_runs; returns at once unless there was evidence.
 template <bool REDO>
 __global__ void __launch_bounds__(kHeadThreads)
-unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, int low_shift,
+unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n, int low_shift,
             u32* __restrict__ head_rows, u32* __restrict__ head_groups, u32 group,
             u32* __restrict__ ticket, u32 epoch,
-            const i32* __restrict__ bag_of, u32 n_bags, u64* __restrict__ uniq,
+            u32 n_bags, u64* __restrict__ uniq,
             i32* __restrict__ inverse, u32* __restrict__ bagperm, u32* __restrict__ seg_off,
             PullCtx* __restrict__ ctx, u32* __restrict__ evidence, TableState* __restrict__ st) {
   __shared__ u32 scratch[kHeadThreads / kWave + 1];
   __shared__ u32 s_tile, s_earlier;
   __shared__ u64 lds_key[kHeadTile];     // the tile, read coalesced, handed out in runs of 8
-  __shared__ u32 lds_idx[kHeadTile];     // later reused for the bagperm words going out
+  __shared__ u64 lds_pay[kHeadTile];
+  __shared__ u32 lds_out[kHeadTile];     // the bagperm words going out
   if (REDO && ctx->n_evidence == 0) return;
   if (threadIdx.x == 0) s_tile = atomicAdd(ticket, 1u);
   __syncthreads();
@@ -192,7 +192,7 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
     const u32 p = k * kHeadThreads + threadIdx.x;
     const u32 j = tile_base + p;
     lds_key[p] = (j < n) ? skeys[j] : 0;
-    lds_idx[p] = (j < n) ? sidx[j] : 0;
+    lds_pay[p] = (j < n) ? spay[j] : 0;
   }
   __syncthreads();
   const u32 first = tile_base + threadIdx.x * kHeadItems;
@@ -205,14 +205,14 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {
     key[k] = lds_key[threadIdx.x * kHeadItems + k];
-    idx[k] = lds_idx[threadIdx.x * kHeadItems + k];
+    const u64 pay = lds_pay[threadIdx.x * kHeadItems + k];
+    idx[k] = (u32)pay;
+    // clamped: whatever the offsets said, the push must stay inside the gradient buffer
+    bag[k] = min((u32)(pay >> 32), n_bags - 1);
   }
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {
     const u32 j = first + k;
-    // clamped: a stale entry (offsets that do not cover every occurrence) must not
-    // send the push outside the gradient buffer
-    bag[k] = (j < n) ? min((u32)bag_of[idx[k]], n_bags - 1) : 0;
     head[k] = (j < n) && (j == 0 || key[k] != prev);
     heads += head[k] ? 1u : 0u;
     if (!REDO && head[k] && j > 0 && (key[k] >> low_shift) == (prev >> low_shift)) {
@@ -258,7 +258,7 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
         if (key[k] == kEmptyKey) raise_error(st, kErrReserved);
         ++rank;
       }
-      lds_idx[threadIdx.x * kHeadItems + k] = bag[k] | (head[k] ? 0x80000000u : 0u);
+      lds_out[threadIdx.x * kHeadItems + k] = bag[k] | (head[k] ? 0x80000000u : 0u);
       inverse[idx[k]] = (i32)(rank - 1);
     }
   }
@@ -266,7 +266,7 @@ unique_emit(const u64* __restrict__ skeys, const u32* __restrict__ sidx, u32 n, 
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {
     const u32 p = k * kHeadThreads + threadIdx.x;
-    if (tile_base + p < n) bagperm[tile_base + p] = lds_idx[p];
+    if (tile_base + p < n) bagperm[tile_base + p] = lds_out[p];
   }
 }
 

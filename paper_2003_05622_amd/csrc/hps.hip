@@ -7,11 +7,13 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
 
 #include "common.cuh"
+#include "bucket.cuh"
 #include "dedup.cuh"
 #include "pool.cuh"
 #include "push.cuh"
@@ -67,7 +69,7 @@ struct ContextLayout {
 };
 
 struct WorkspaceLayout {
-  size_t keys_a, keys_b, idx_a, idx_b, ghist, tickets, tile_rows, group_rows, head_rows,
+  size_t keys_a, keys_b, keys_c, idx_a, idx_b, idx_c, id16, heavy_raw, ghist, tickets, tile_rows, group_rows, head_rows,
       head_groups, evidence, bag_of, miss_list, med_list, long_list, chunk_items, partials, total;
   ContextLayout c[2];
   uint64_t med_cap, max_long, max_items, sort_tiles, head_tiles, shard_cap;
@@ -85,16 +87,20 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   size_t o = 0;
   L.keys_a = o;      o = align_up(o + n1 * 8);
   L.keys_b = o;      o = align_up(o + n1 * 8);
-  L.idx_a = o;       o = align_up(o + n1 * 4);
-  L.idx_b = o;       o = align_up(o + n1 * 4);
+  L.keys_c = o;      o = align_up(o + n1 * 8);    // scratch of a region ordered the slow way
+  L.idx_a = o;       o = align_up(o + n1 * 8);    // payloads: occurrence index | bag << 32
+  L.idx_b = o;       o = align_up(o + n1 * 8);
+  L.idx_c = o;       o = align_up(o + n1 * 8);
+  L.id16 = o;        o = align_up(o + n1 * 2);    // bucket id of every occurrence
   // from here to `evidence`: cleared at creation, never again (see sort.cuh)
-  L.ghist = o;       o = align_up(o + 2 * kMaxPasses * kRadix * 4);
+  L.ghist = o;       o = align_up(o + 2 * (size_t)kHistWords * 4);
   L.tickets = o;     o = align_up(o + (kMaxPasses + 2) * 4);
   L.tile_rows = o;   o = align_up(o + (size_t)kMaxPasses * L.sort_tiles * kRadix * 4);
   L.group_rows = o;  o = align_up(o + (size_t)kMaxPasses * (L.sort_tiles / kMinTileGroup + 1) * kRadix * 4);
   L.head_rows = o;   o = align_up(o + 2 * L.head_tiles * 4);
   L.head_groups = o; o = align_up(o + 2 * (L.head_tiles / kMinTileGroup + 1) * 4);
   L.evidence = o;    o = align_up(o + kMaxEvidence * 4);
+  L.heavy_raw = o;   o = align_up(o + sizeof(HeavyRing));
   L.bag_of = o;      o = align_up(o + n1 * 4);
   L.shard_cap = n1 / kCountShards + kMissLdsCap;
   L.miss_list = o;   o = align_up(o + (size_t)kCountShards * L.shard_cap * 4);
@@ -124,8 +130,32 @@ uint32_t tile_group(uint64_t n_tiles) {
   return g;
 }
 
+// Largest dedup the bucket path takes: beyond it a heavy key the hint misses could
+// hold more occurrences than a region has room for.
+constexpr uint64_t kBucketPathMaxKeys = 12ull << 20;
+// Smallest one: below it the fixed costs of the bucket path outweigh the passes it saves.
+constexpr uint64_t kBucketPathMinKeys = 1ull << 17;
+
+// Bucket path: enough leading key bits that a natural bucket holds kNaturalBucket
+// occurrences on average at most; the passes sort by the bytes of the bucket id.
+SortPlan bucket_plan(uint64_t n) {
+  SortPlan p;
+  int bits = 1;
+  while (bits < 24 && ((n + kNaturalBucket - 1) / kNaturalBucket) > (1ull << bits)) ++bits;
+  const uint64_t max_id = (1ull << bits) + 2 * kMaxHeavy + 1;
+  p.n_pass = 2;      // ids stay below 2^16 for every n the bucket path takes
+  (void)max_id;
+  p.low_shift = 0;
+  p.group = tile_group((n + kSortTile - 1) / kSortTile);
+  p.by_id = 1;
+  p.nat_shift = 64 - bits;
+  return p;
+}
+
 SortPlan sort_plan(uint64_t n) {
   SortPlan p;
+  p.by_id = 0;
+  p.nat_shift = 0;
   int log2n = 1;
   while ((1ull << log2n) < n) ++log2n;
   int want = (2 * log2n - 2 + 7) / 8;
@@ -161,6 +191,8 @@ struct hps_table {
   char* ws;
   WorkspaceLayout wl;
   int lpr;
+  uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
+  int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
   uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
 
   // Pull contexts.  `current` is the context of the outstanding pull (-1: none),
@@ -248,50 +280,76 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
     const u32 epoch = (u32)(t->serial % kEpochMod) + 1;
     if (epoch == 1 && t->serial >= kEpochMod)   // the epochs start over: forget the old words
       fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
-    const SortPlan plan = sort_plan(n);
+    // The bucket path needs to know the heavy keys, which it learns from the lookups: the
+    // first two dedups of a table take the plain passes, as do small and very large ones.
+    const bool buckets = n <= kBucketPathMaxKeys && t->dedup_mode != 1 &&
+                         (t->dedup_mode == 2 || (n >= kBucketPathMinKeys && t->lookup_serial >= 2));
+    const SortPlan plan = buckets ? bucket_plan(n) : sort_plan(n);
     u64* kcur = t->w<u64>(L.keys_a);
     u64* kalt = t->w<u64>(L.keys_b);
-    u32* icur = t->w<u32>(L.idx_a);
-    u32* ialt = t->w<u32>(L.idx_b);
-    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kMaxPasses * kRadix;
-    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kMaxPasses * kRadix;
+    u64* pcur = t->w<u64>(L.idx_a);
+    u64* palt = t->w<u64>(L.idx_b);
+    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kHistWords;
+    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kHistWords;
     u32* tickets = t->w<u32>(L.tickets);
+    // the most recent list of frequent keys that is certainly complete (common.cuh)
+    const HeavySet* heavy =
+        &t->w<HeavyRing>(L.heavy_raw)->set[(t->lookup_serial + kHeavyRing - 1) % kHeavyRing];
     const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    sort_prepare<<<n_tiles < 512 ? n_tiles : 512, kPrepThreads, 0, s>>>(
+    const unsigned hist_blocks = n_tiles < 768 ? n_tiles : 768;
+    const unsigned bag_blocks = grid_for(d_offsets ? n_bags : n, kPrepThreads, 256);
+    sort_prepare<<<hist_blocks + bag_blocks, kPrepThreads, 0, s>>>(
         d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, n_bags,
-        t->w<i32>(L.bag_of));
+        t->w<i32>(L.bag_of), heavy, t->w<uint16_t>(L.id16), hist_blocks);
     for (int p = 0; p < plan.n_pass; ++p) {
       u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
       u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
       const int shift = plan.low_shift + p * kRadixBits;
+#define HPS_PASS(FIRST, IDS, KIN, PIN, KOUT, POUT)                                              \
+  onesweep_pass<FIRST, IDS><<<n_tiles, kSortThreads, 0, s>>>(                                  \
+      KIN, PIN, t->w<i32>(L.bag_of), KOUT, POUT, n, shift, ghist + p * kRadix, tile_rows,      \
+      group_rows, plan.group, tickets + p, epoch, ctx, t->w<uint16_t>(L.id16))
       if (p == 0) {
-        onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(d_keys, nullptr, kcur, icur, n, shift,
-                                                             ghist, tile_rows, group_rows, plan.group,
-                                                             tickets, epoch, ctx);
+        if (buckets) HPS_PASS(true, true, d_keys, nullptr, kcur, pcur);
+        else HPS_PASS(true, false, d_keys, nullptr, kcur, pcur);
       } else {
-        onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(kcur, icur, kalt, ialt, n, shift,
-                                                              ghist + p * kRadix, tile_rows, group_rows,
-                                                              plan.group, tickets + p, epoch, ctx);
+        if (buckets) HPS_PASS(false, true, kcur, pcur, kalt, palt);
+        else HPS_PASS(false, false, kcur, pcur, kalt, palt);
         u64* tk = kcur; kcur = kalt; kalt = tk;
-        u32* ti = icur; icur = ialt; ialt = ti;
+        tk = pcur; pcur = palt; palt = tk;
       }
+#undef HPS_PASS
     }
     stage_mark(t, HPS_STAGE_SORT, s);
-    // a1: unique keys, ranks, grouping (second instance only acts after a repair)
+    // a1: unique keys, ranks, grouping
     stage_mark(t, HPS_STAGE_UNIQUE, s);
-    const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
-    const u32 head_group = tile_group(head_tiles);
-    u32* evidence = t->w<u32>(L.evidence);
-    unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
-        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
-        tickets + kMaxPasses, epoch, t->w<i32>(L.bag_of), n_bags, t->w<u64>(C.uniq),
-        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
-    fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, icur, kalt, ialt, n, plan, ctx, evidence);
-    unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
-        kcur, icur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
-        t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
-        tickets + kMaxPasses + 1, epoch, t->w<i32>(L.bag_of), n_bags, t->w<u64>(C.uniq),
-        t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
+    if (buckets) {
+      const unsigned n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
+#define HPS_CHUNKS(ITEMS)                                                                          \
+  chunk_sort_emit<ITEMS><<<n_chunks, kChunkThreads, 0, s>>>(                                       \
+      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, plan.nat_shift, heavy,    \
+      t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), tile_group(n_chunks), tickets + kMaxPasses, \
+      epoch, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm),                 \
+      t->w<u32>(C.seg_off), ctx, t->view.st)
+      if (chunk_items(n) == 8) HPS_CHUNKS(8);
+      else HPS_CHUNKS(kChunkItemsMax);
+#undef HPS_CHUNKS
+    } else {
+      // the second unique_emit only acts after a repair
+      const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
+      const u32 head_group = tile_group(head_tiles);
+      u32* evidence = t->w<u32>(L.evidence);
+      unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
+          kcur, pcur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
+          tickets + kMaxPasses, epoch, n_bags, t->w<u64>(C.uniq),
+          t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
+      fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, pcur, kalt, palt, n, plan, ctx, evidence);
+      unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
+          kcur, pcur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
+          t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
+          tickets + kMaxPasses + 1, epoch, n_bags, t->w<u64>(C.uniq),
+          t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
+    }
     stage_mark(t, HPS_STAGE_UNIQUE, s);
   }
 }
@@ -308,6 +366,9 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
   often.med_cap = (u32)t->wl.med_cap;
   often.long_list = t->w<uint2>(t->wl.long_list);
   often.chunk_items = t->w<uint2>(t->wl.chunk_items);
+  ++t->lookup_serial;
+  often.heavy_raw = &t->w<HeavyRing>(t->wl.heavy_raw)->raw[t->lookup_serial % kHeavyRing];
+  often.heavy_min = (u32)(n_keys / kHeavyShare > kHeavyMin ? n_keys / kHeavyShare : kHeavyMin);
   const unsigned probe_blocks = grid_for(n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0, &ctx->n_unique,
                                                         t->w<u32>(C.rows), nullptr, nullptr, nullptr,
@@ -428,11 +489,19 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
   t->serial = 0;
+  t->lookup_serial = 0;
+  {
+    // HPS_DEDUP=radix / bucket pins the dedup to one of its two forms (comparison runs, tests)
+    const char* mode = std::getenv("HPS_DEDUP");
+    t->dedup_mode = !mode ? 0 : std::strcmp(mode, "radix") == 0 ? 1 : std::strcmp(mode, "bucket") == 0 ? 2 : 0;
+  }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
   // look-back status words and digit histograms start at zero
   fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.bag_of - wl.ghist) / 8, 0);
+  for (u32 k = 0; k < kHeavyRing; ++k)      // no frequent keys known yet: all-ones padding only
+    fill_u64<<<1, 256, 0, s>>>(t->w<HeavyRing>(wl.heavy_raw)->set[k].keys, kMaxHeavy + 1, ~0ull);
   reset_state<<<1, 64, 0, s>>>(t->view.st);
   for (int k = 0; k < 2; ++k)
     set_ctx_empty<<<1, 64, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
@@ -467,7 +536,7 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
       lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
                                                       nullptr, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                    d_acc, nullptr, 0);
+                                                    d_acc, nullptr, 0, nullptr, 0);
   }
   commit_insert<<<1, 64, 0, s>>>(t->view.st);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
@@ -522,7 +591,9 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
     launch_lookup(t, c, cx.n_keys, s);
     insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
-                                                          nullptr, miss_list, shard_cap);
+                                                          nullptr, miss_list, shard_cap,
+                                                          t->w<HeavyRing>(t->wl.heavy_raw),
+                                                          (u32)(t->lookup_serial % kHeavyRing));
   }
   if (!cx.n_bags) commit_insert<<<1, 64, 0, s>>>(t->view.st);   // else the pooling kernel does it
   stage_mark(t, HPS_STAGE_LOOKUP, s);
@@ -590,14 +661,15 @@ hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, cons
   launch_dedup(t, c, d_keys, (u32)n, nullptr, (u32)n, s);
   if (n) {
     launch_lookup(t, c, n, s);
-    commit_absent<<<1, 64, 0, s>>>(t->view.st);
+    commit_absent<<<1, 256, 0, s>>>(t->view.st, t->w<HeavyRing>(t->wl.heavy_raw),
+                                   (u32)(t->lookup_serial % kHeavyRing));
     PushArgs a;
     fill_push_args(t, c, d_values, kStepAdd, a);
 #define CALL(LPR) launch_push<LPR>(t, n, a, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
   } else {
-    commit_absent<<<1, 64, 0, s>>>(t->view.st);
+    commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0);
   }
   if (!launch_ok()) return HPS_EDEVICE;
   if (hipEventRecord(cx.released, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)

@@ -1,6 +1,7 @@
 // Key dedup, part 1: ordering the key occurrences.
 //
-// The occurrences (key, index) are sorted by the keys' top `8 * n_pass` bits with a
+// The occurrences (key, payload) -- payload = occurrence index and bag number in one
+// 64-bit word -- are sorted by the keys' top `8 * n_pass` bits with a
 // stable least-significant-digit radix sort, 8 bits per pass, ONE kernel per pass:
 //
 //   sort_prepare    digit histograms of all passes in one read of the keys (also
@@ -42,6 +43,11 @@ constexpr int kSortItems = 16;                         // per worker thread
 constexpr int kSortTile = kSortWorkers * kSortItems;   // 3072 elements
 constexpr int kSortWaveSpan = kWave * kSortItems;      // 1024 consecutive elements per wave
 constexpr int kPrepThreads = 256;
+// The global digit histograms are kept in kHistShards copies (block b adds to copy b %
+// kHistShards; readers add the copies up): hundreds of blocks adding to ONE set of
+// counters queue up behind each other, same-address device atomics being slow.
+constexpr int kHistShards = 16;
+constexpr int kHistWords = kHistShards * kMaxPasses * kRadix;   // one pull's histograms
 
 constexpr u32 kSpinLimit = 1u << 22;
 constexpr u32 kEpochMod = 4095;        // epochs run 1..4095
@@ -53,12 +59,46 @@ static_assert(kRadix == 4 * kWave, "each look-back lane owns four digits");
 
 struct SortPlan {
   int n_pass;       // digits sorted
-  int low_shift;    // 64 - 8 * n_pass: position of the least significant sorted digit
+  int low_shift;    // plain mode: 64 - 8 * n_pass, position of the least significant sorted digit
   u32 group;        // tiles per group
+  int by_id;        // 1: the passes sort by the bucket id of the key (see bucket_id) instead
+  int nat_shift;    // by_id: 64 - number of leading key bits that make the natural bucket
 };
 
 __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
   return (u32)(k >> shift) & (kRadix - 1);
+}
+
+// ---- bucket ids ---------------------------------------------------------------------
+// Keys that make up a large share of a mini-batch ("heavy" keys; found from a sample,
+// bucket.cuh) get buckets of their own, so that every other bucket stays small enough
+// to be sorted inside one workgroup.  With the heavy keys h_0 < h_1 < ... the id of a
+// key is
+//     (key >> nat_shift) + 2 * #{i : h_i < key} + (key is heavy ? 1 : 0),
+// which is monotone in the key; keys share an id only if they share the leading bits
+// and no heavy key lies between them, and a heavy key shares its id with nothing.
+
+// The heavy keys in LDS, with their spans per value of the top bits, so that a lookup
+// costs one LDS read unless heavy keys share the key's top bits.
+struct HeavyLds {
+  u64 keys[kMaxHeavy + 1];
+  u32 span[1 << kHeavyTopBits];
+};
+
+// All threads of the block; the caller's next barrier makes the copy visible.
+__device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set) {
+  for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += blockDim.x) H.keys[i] = set->keys[i];
+  for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += blockDim.x) H.span[i] = set->span[i];
+}
+
+// *heavy tells whether the key is one of the heavy keys.
+__device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, int nat_shift, bool* heavy) {
+  const u32 sp = H.span[(u32)(key >> (64 - kHeavyTopBits))];
+  u32 m = sp & 0xFFFFu;
+  const u32 end = m + (sp >> 16);
+  while (m < end && H.keys[m] < key) ++m;
+  *heavy = m < end && H.keys[m] == key;
+  return (u32)(key >> nat_shift) + 2 * m + (*heavy ? 1u : 0u);
 }
 
 // ---- status words -------------------------------------------------------------------
@@ -152,37 +192,29 @@ __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* befo
   *count = __popcll(same);
 }
 
-// Histograms of every pass's digit over all keys; also resets what the passes need
-// and writes bag_of[i] (a wave takes 64 bags at a time; bags of more than 8
-// occurrences are filled by the whole wave).
-//   ghist      [kMaxPasses][kRadix] of this pull (zero on entry), ghist_next the
+// Histograms of every pass's digit over all keys (the first hist_blocks blocks, which
+// also reset what the passes need) and bag_of[i] (the other blocks, at least one: a wave
+// takes 64 bags at a time; bags of more than 8 occurrences are filled by the whole wave).
+//   ghist      [kHistShards][kMaxPasses][kRadix] of this pull (zero on entry), ghist_next the
 //              buffer the next pull will use (cleared here)
 //   tickets    [kMaxPasses + 2] tile tickets of the passes and of the two unique scans
+//   id16       by_id plans only: receives every key's bucket id (the first pass reads
+//              it, and hands the id's high byte on to the second inside the payload)
 __global__ void __launch_bounds__(kPrepThreads)
 sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict__ ghist,
              u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx,
-             const i32* __restrict__ offsets, u32 n_bags, i32* __restrict__ bag_of) {
-  __shared__ u32 h[kMaxPasses][kRadix];
-  for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) (&h[0][0])[i] = 0;
-  if (blockIdx.x == 0) {
-    for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) ghist_next[i] = 0;
-    if (threadIdx.x < kMaxPasses + 2) tickets[threadIdx.x] = 0;
-    if (threadIdx.x == 0) {
-      ctx->n_unique = 0;
-      ctx->n_long = 0;
-      ctx->med_overflow = 0;
-      ctx->n_chunk_items = 0;
-      ctx->n_evidence = 0;
-      ctx->sort_error = 0;
+             const i32* __restrict__ offsets, u32 n_bags, i32* __restrict__ bag_of,
+             const HeavySet* __restrict__ heavy_set, uint16_t* __restrict__ id16, u32 hist_blocks) {
+  if (blockIdx.x >= hist_blocks) {
+    // ---- the blocks behind the first hist_blocks write bag_of ----
+    const u32 block = blockIdx.x - hist_blocks, n_blocks = gridDim.x - hist_blocks;
+    if (offsets == nullptr) {     // every occurrence is its own bag
+      for (u32 i = block * kPrepThreads + threadIdx.x; i < n; i += n_blocks * kPrepThreads)
+        bag_of[i] = (i32)i;
+      return;
     }
-    if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
-  }
-  if (offsets == nullptr) {     // every occurrence is its own bag
-    for (u32 i = blockIdx.x * kPrepThreads + threadIdx.x; i < n; i += gridDim.x * kPrepThreads)
-      bag_of[i] = (i32)i;
-  } else {
-    const u32 wave_global = (blockIdx.x * kPrepThreads + threadIdx.x) / kWave;
-    const u32 n_waves = gridDim.x * (kPrepThreads / kWave);
+    const u32 wave_global = (block * kPrepThreads + threadIdx.x) / kWave;
+    const u32 n_waves = n_blocks * (kPrepThreads / kWave);
     for (u32 b0 = wave_global * kWave; b0 < n_bags; b0 += n_waves * kWave) {
       const u32 b = b0 + lane_id();
       i32 lo = 0, hi = 0;
@@ -199,38 +231,71 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
         for (i32 i = blo + (i32)lane_id(); i < bhi; i += kWave) bag_of[i] = (i32)(b0 + src);
       }
     }
+    return;
+  }
+  // ---- the first hist_blocks blocks: resets and histograms ----
+  __shared__ u32 h[kMaxPasses][kRadix];
+  __shared__ HeavyLds hv;
+  if (plan.by_id) load_heavy(hv, heavy_set);
+  for (u32 sh = blockIdx.x; sh < (u32)kHistShards; sh += hist_blocks)     // the next pull's counters
+    for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads)
+      ghist_next[sh * kMaxPasses * kRadix + i] = 0;
+  for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) (&h[0][0])[i] = 0;
+  if (blockIdx.x == 0) {
+    if (threadIdx.x < kMaxPasses + 2) tickets[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+      ctx->n_unique = 0;
+      ctx->n_long = 0;
+      ctx->med_overflow = 0;
+      ctx->n_chunk_items = 0;
+      ctx->n_evidence = 0;
+      ctx->sort_error = 0;
+    }
+    if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
   }
   __syncthreads();
   const u32 n_tiles = (n + kSortTile - 1) / kSortTile;
-  for (u32 tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  for (u32 tile = blockIdx.x; tile < n_tiles; tile += hist_blocks) {
     const u32 base = tile * kSortTile;
 #pragma unroll 4
     for (int k = 0; k < kSortTile / kPrepThreads; ++k) {
       const u32 i = base + k * kPrepThreads + threadIdx.x;
       if (i < n) {
         const u64 key = keys[i];
-        for (int p = 0; p < plan.n_pass; ++p)
-          atomicAdd(&h[p][key_digit(key, plan.low_shift + p * kRadixBits)], 1u);
+        if (plan.by_id) {
+          bool heavy;
+          const u32 id = bucket_id(key, hv, plan.nat_shift, &heavy);
+          id16[i] = (uint16_t)id;         // by_id plans have ids below 2^16: two passes
+          for (int p = 0; p < plan.n_pass; ++p)
+            atomicAdd(&h[p][(id >> (p * kRadixBits)) & (kRadix - 1)], 1u);
+        } else {
+          for (int p = 0; p < plan.n_pass; ++p)
+            atomicAdd(&h[p][key_digit(key, plan.low_shift + p * kRadixBits)], 1u);
+        }
       }
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < plan.n_pass * kRadix; i += kPrepThreads) {
     const u32 c = (&h[0][0])[i];
-    if (c) atomicAdd(&ghist[i], c);
+    if (c) atomicAdd(&ghist[(blockIdx.x % kHistShards) * kMaxPasses * kRadix + i], c);
   }
 }
 
-// One stable radix pass over (key, idx) pairs.  FIRST: idx is the position itself
-// and is not read.  `ghist` is this pass's global digit histogram; tile_rows
+// One stable radix pass over (key, payload) pairs; payload = index | bag << 32.
+// FIRST: the payload is built from the position and bag_of (read in order).
+// IDS: the passes sort by the 16-bit bucket id instead of key bits: the first by its low
+// byte (read from id16; the high byte goes into bits 24..31 of the payload, which limits
+// such dedups to 2^24 occurrences), the second by that high byte.  `ghist` is this pass's global digit histogram; tile_rows
 // [n_tiles][kRadix] and group_rows [n_groups][kRadix] are this pass's status words.
-template <bool FIRST>
+template <bool FIRST, bool IDS>
 __global__ void __launch_bounds__(kSortThreads)
-onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
-              u64* __restrict__ keys_out, u32* __restrict__ idx_out, u32 n, int shift,
+onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
+              const i32* __restrict__ bag_of, u64* __restrict__ keys_out,
+              u64* __restrict__ pay_out, u32 n, int shift,
               const u32* __restrict__ ghist, u32* __restrict__ tile_rows,
               u32* __restrict__ group_rows, u32 group, u32* __restrict__ ticket, u32 epoch,
-              PullCtx* __restrict__ ctx) {
+              PullCtx* __restrict__ ctx, const uint16_t* __restrict__ id16) {
   __shared__ u32 tile_hist[kRadix];              // digit counts of the tile
   __shared__ u32 earlier[kRadix];                // same-digit elements in earlier tiles
   __shared__ u32 wave_cnt[kSortWaves][kRadix];   // per-wave digit counts, then wave offsets
@@ -238,7 +303,8 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
   __shared__ u32 out_base[kRadix];               // global position of the digit's run - local_start
   __shared__ u32 scratch[kSortThreads / kWave + 1];
   __shared__ u32 s_tile;
-  __shared__ u64 stage[kSortTile];               // keys first, then (as u32) the indices
+  __shared__ u64 stage[kSortTile];               // keys first, then the payloads
+  __shared__ uint8_t stage_digit[kSortTile];     // digit of each staged key
 
   const u32 tid = threadIdx.x;
   const bool worker = tid < kSortWorkers;
@@ -253,19 +319,32 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
   const u32 wave_base = tile_base + wave * kSortWaveSpan;
 
   u64 key[kSortItems];
-  u32 idx[kSortItems];
+  u64 pay[kSortItems];
   u32 rank[kSortItems];
+  u32 digit[kSortItems];
   if (worker) {
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
       key[r] = (i < n) ? keys_in[i] : ~0ull;
-      idx[r] = FIRST ? i : ((i < n) ? idx_in[i] : 0u);
+      if (FIRST)
+        pay[r] = (i < n) ? ((u64)i | ((u64)(u32)bag_of[i] << 32)) : 0ull;
+      else
+        pay[r] = (i < n) ? pay_in[i] : 0ull;
+      if (IDS && FIRST) {
+        const u32 id = (i < n) ? id16[i] : 0u;
+        digit[r] = id & (kRadix - 1);
+        pay[r] |= (u64)(id >> kRadixBits) << 24;
+      } else if (IDS) {
+        digit[r] = (u32)(pay[r] >> 24) & (kRadix - 1);
+      } else {
+        digit[r] = key_digit(key[r], shift);
+      }
     }
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
-      if (i < n) atomicAdd(&tile_hist[key_digit(key[r], shift)], 1u);
+      if (i < n) atomicAdd(&tile_hist[digit[r]], 1u);
     }
   }
   __syncthreads();
@@ -297,7 +376,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
       const bool valid = i < n;
-      const u32 d = key_digit(key[r], shift);
+      const u32 d = digit[r];
       u32 before, same;
       match_digit(d, valid, lt, &before, &same);
       u32 old = 0;
@@ -319,7 +398,10 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
     digit_total += c;
   }
   u32 total;
-  const u32 gbase = block_excl_sum<kSortThreads>(ghist[tid], scratch, &total);
+  u32 digit_count = 0;
+#pragma unroll
+  for (int sh = 0; sh < kHistShards; ++sh) digit_count += ghist[sh * kMaxPasses * kRadix + tid];
+  const u32 gbase = block_excl_sum<kSortThreads>(digit_count, scratch, &total);
   const u32 start = block_excl_sum<kSortThreads>(digit_total, scratch, &total);
   local_start[tid] = start;
   out_base[tid] = gbase + earlier[tid] - start;
@@ -332,9 +414,10 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
       const u32 i = wave_base + r * kWave + lane;
       pos[r] = 0;
       if (i < n) {
-        const u32 d = key_digit(key[r], shift);
+        const u32 d = digit[r];
         pos[r] = local_start[d] + wave_cnt[wave][d] + rank[r];
         stage[pos[r]] = key[r];
+        stage_digit[pos[r]] = (uint8_t)d;
       }
     }
   }
@@ -346,19 +429,17 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
       const u32 p = k * kSortWorkers + tid;
       dest[k] = 0;
       if (p < tile_n) {
-        const u64 kk = stage[p];
-        dest[k] = out_base[key_digit(kk, shift)] + p;
-        keys_out[dest[k]] = kk;
+        dest[k] = out_base[stage_digit[p]] + p;
+        keys_out[dest[k]] = stage[p];
       }
     }
   }
   __syncthreads();
-  u32* stage_idx = reinterpret_cast<u32*>(stage);
   if (worker) {
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
-      if (i < n) stage_idx[pos[r]] = idx[r];
+      if (i < n) stage[pos[r]] = pay[r];
     }
   }
   __syncthreads();
@@ -366,7 +447,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u32* __restrict__ idx_in,
 #pragma unroll
     for (int k = 0; k < kSortItems; ++k) {
       const u32 p = k * kSortWorkers + tid;
-      if (p < tile_n) idx_out[dest[k]] = stage_idx[p];
+      if (p < tile_n) pay_out[dest[k]] = stage[p];
     }
   }
 }

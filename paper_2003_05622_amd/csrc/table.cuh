@@ -53,6 +53,8 @@ struct OftenLists {
   u32 med_cap;
   uint2* long_list;     // (unique index, first chunk item)
   uint2* chunk_items;   // (unique index, chunk number)
+  HeavyRaw* heavy_raw;  // keys with at least heavy_min occurrences are listed for the next dedup
+  u32 heavy_min;
 };
 
 // "Updated since the last dirty dump" is kept in the sign bit of a row's first
@@ -65,6 +67,50 @@ __device__ __forceinline__ float acc_marked(float value) {
 }
 __device__ __forceinline__ bool acc_is_marked(float stored) {
   return (__float_as_uint(stored) & 0x80000000u) != 0;
+}
+
+// Called by all threads of one block (exactly 256) once lookup `slot`'s list of frequent
+// keys is complete: orders it into the ring's set and empties the next list.
+__device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
+  __shared__ u64 k[kMaxHeavy + 1];
+  __shared__ u64 sorted[kMaxHeavy + 1];
+  const u32 tid = threadIdx.x;
+  const HeavyRaw& raw = ring->raw[slot];
+  HeavySet& set = ring->set[slot];
+  const u32 count = min(raw.count, (u32)kMaxHeavy);
+  k[tid] = tid < count ? raw.keys[tid] : ~0ull;
+  __syncthreads();
+  const u64 mine = k[tid];
+  u32 rank = 0;
+#pragma unroll 8
+  for (u32 i = 0; i <= (u32)kMaxHeavy; ++i) {
+    const u64 o = k[i];
+    rank += (o < mine || (o == mine && i < tid)) ? 1u : 0u;
+  }
+  sorted[rank] = mine;                 // the ranks are a permutation of 0..kMaxHeavy
+  set.keys[rank] = mine;
+  __syncthreads();
+  // spans: thread t takes top-bit values 4t .. 4t+3
+  u32 first[5];
+#pragma unroll
+  for (int e = 0; e < 5; ++e) {
+    const u32 v = 4 * tid + e;
+    u32 m = count;
+    if (v < (1u << kHeavyTopBits)) {
+      const u64 bound = (u64)v << (64 - kHeavyTopBits);
+      m = 0;
+#pragma unroll
+      for (u32 step = (kMaxHeavy + 1) / 2; step >= 1; step >>= 1)
+        if (sorted[m + step - 1] < bound) m += step;     // the all-ones padding is never below
+    }
+    first[e] = m;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) set.span[4 * tid + e] = first[e] | ((first[e + 1] - first[e]) << 16);
+  if (tid == 0) {
+    set.count = count;
+    ring->raw[(slot + 1) % kHeavyRing].count = 0;
+  }
 }
 
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
@@ -128,7 +174,9 @@ __global__ void __launch_bounds__(64) commit_insert(TableState* st) { commit_ins
 
 // After a lookup that creates nothing (accumulate): the number of keys not found
 // goes to st->absent, the counters are cleared.
-__global__ void __launch_bounds__(64) commit_absent(TableState* st) {
+__global__ void __launch_bounds__(256) commit_absent(TableState* st, HeavyRing* ring, u32 slot) {
+  if (ring) finalize_heavy(ring, slot);
+  if (threadIdx.x >= kWave) return;
   const u32 lane = lane_id();
   u32 missing = lane < kCountShards ? st->miss_shard[lane] : 0;
 #pragma unroll
@@ -242,6 +290,10 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         }
         // sort the key into the push's work lists by its number of occurrences
         const u32 len = often.seg_off[u + 1] - often.seg_off[u];
+        if (len >= often.heavy_min) {
+          const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
+          if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = key[k];
+        }
         if (len > kMedSeg) {
           const u32 n_chunks = (len + kChunk - 1) / kChunk;
           const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
@@ -311,13 +363,16 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
 // rows != null (pull): the listed missing keys are visited (or, after a list overflow,
 // all keys with rows[u] == kNoRow); rows[u] is set.
 // rows == null (bulk insert): every key is probed again.
+// ring != null (pull): block 0 first puts the lookup's list of frequent keys in order.
 // w_in == null: new rows get the deterministic initial row; else the given values.
 __global__ void __launch_bounds__(kProbeThreads)
 insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
                const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
                const float* __restrict__ w_in, const float* __restrict__ acc_in,
-               const u32* __restrict__ miss_list, u32 shard_cap) {
+               const u32* __restrict__ miss_list, u32 shard_cap, HeavyRing* ring, u32 ring_slot) {
   __shared__ u32 s_total, s_made, s_mine;
+  // the lookup before this kernel has finished: its list of frequent keys is complete
+  if (ring && blockIdx.x == 0) finalize_heavy(ring, ring_slot);
   if (load_error(t.st) != 0) return;
   if (threadIdx.x < kWave) {
     const u32 mine = threadIdx.x < kCountShards ? t.st->miss_shard[threadIdx.x] : 0;

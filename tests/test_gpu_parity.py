@@ -13,6 +13,19 @@ from oracle import OracleTable
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(params=["auto", "bucket", "radix"], autouse=True)
+def dedup_form(request, monkeypatch):
+    """Every test runs with the dedup chosen by size and history (small batches and a table's
+    first two take the plain radix passes), pinned to the bucket path (so that tiny and odd
+    inputs, and batches without a hint about heavy keys, go through it too) and pinned to the
+    plain passes.  The library reads the variable when a table is created."""
+    if request.param == "auto":
+        monkeypatch.delenv("HPS_DEDUP", raising=False)
+    else:
+        monkeypatch.setenv("HPS_DEDUP", request.param)
+    return request.param
+
 ATOL, RTOL = 1e-6, 1e-5
 
 
