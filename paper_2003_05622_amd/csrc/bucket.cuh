@@ -66,19 +66,22 @@ __device__ __forceinline__ void lds_radix_sort(u64* words, u32 cnt, int first_bi
     uint4* h4 = reinterpret_cast<uint4*>(h);             // [digit]: waves 0..7, 16 bits each
     u64 wd[ITEMS];
     u32 rank[ITEMS];
-    volatile uint16_t* cntw = h + wave;                  // this wave's counter of digit d: cntw[8 * d]
+    // This wave's counter of digit d is the 16-bit word h[8 * d + wave]; the atomic works
+    // on the 32-bit word it shares with the neighbouring wave's (counts stay below 2^16,
+    // so nothing carries over).
+    u32* pairs = reinterpret_cast<u32*>(h) + (wave >> 1);
+    const int half = (wave & 1) * 16;
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
       if ((u32)r < items) {
         wd[r] = words[wave_first + r * kWave + lane];
         const u32 d = (u32)(wd[r] >> bit) & (kRadix - 1);
-        u32 before, same;
-        match_digit(d, true, lt, &before, &same);
-        const u32 old = cntw[WAVES * d];
-        __builtin_amdgcn_wave_barrier();
-        if (before == 0) cntw[WAVES * d] = (uint16_t)(old + same);
-        __builtin_amdgcn_wave_barrier();
-        rank[r] = old + before;
+        const u64 same = match_mask(d, true);
+        const u32 before = __popcll(same & lt);
+        u32 old = 0;
+        if (before == 0) old = atomicAdd(pairs + (WAVES / 2) * d, (u32)__popcll(same) << half);
+        old = __shfl(old, __ffsll((unsigned long long)same) - 1, kWave);
+        rank[r] = ((old >> half) & 0xFFFFu) + before;
       }
     }
     __syncthreads();

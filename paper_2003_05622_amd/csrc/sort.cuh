@@ -178,6 +178,33 @@ __device__ __forceinline__ u32 wave_sum_words(const u32* words, u32 first, u32 l
   return c;
 }
 
+// The lanes of the wave (among `valid` ones) whose digit equals this lane's.
+__device__ __forceinline__ u64 match_mask(u32 d, bool valid) {
+  u64 same = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < kRadixBits; ++b) {
+    const bool bit = (d >> b) & 1;
+    const u64 bb = __ballot(bit);
+    same &= bit ? bb : ~bb;
+  }
+  return same;
+}
+
+// Rank of this lane's element among the wave's elements with the same digit, counted
+// over all calls so far: `counter` (LDS) holds the digit's running count for this wave.
+// The first lane of each group adds the group's size with ONE returning atomic and hands
+// the old value to the others by a shuffle, so consecutive calls do not wait for each
+// other (LDS executes a wave's operations in order; nothing has to come back before the
+// next call's atomic is issued).
+__device__ __forceinline__ u32 digit_rank(u32* counter, u32 d, bool valid, u64 lt) {
+  const u64 same = match_mask(d, valid);
+  const u32 before = __popcll(same & lt);
+  u32 old = 0;
+  if (valid && before == 0) old = atomicAdd(counter, (u32)__popcll(same));
+  old = __shfl(old, same ? __ffsll((unsigned long long)same) - 1 : 0, kWave);
+  return old + before;
+}
+
 // Number of lanes of the wave (among `valid` ones) whose digit equals this lane's,
 // and how many of them have a lower lane id.
 __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* before, u32* count) {
@@ -370,21 +397,11 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
   } else {
     // Workers: rank each element among the wave's earlier elements with the same
     // digit (element order inside a wave: round by round, then by lane).
-    volatile u32* cnt = &wave_cnt[wave][0];
     const u64 lt = lanemask_lt();
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
-      const bool valid = i < n;
-      const u32 d = digit[r];
-      u32 before, same;
-      match_digit(d, valid, lt, &before, &same);
-      u32 old = 0;
-      if (valid) old = cnt[d];
-      __builtin_amdgcn_wave_barrier();
-      if (valid && before == 0) cnt[d] = old + same;
-      __builtin_amdgcn_wave_barrier();
-      rank[r] = old + before;
+      rank[r] = digit_rank(&wave_cnt[wave][digit[r]], digit[r], i < n, lt);
     }
   }
   __syncthreads();
