@@ -348,7 +348,7 @@ __device__ __forceinline__ u32 count_distinct(const u64* key, u32 items, u32 cnt
 
 // A whole region the slow way: ordered in global memory, then walked.  Kept out of line
 // so that its registers do not weigh on the usual path.
-__device__ __noinline__ void slow_region(const u64* skeys, const u64* spay, u64* ka, u64* pa, u64* kb,
+__device__ __forceinline__ void slow_region(const u64* skeys, const u64* spay, u64* ka, u64* pa, u64* kb,
                                          u64* pb, u32 n, u32 start, u32 end, u32 chunk, bool last,
                                          SlowLds& slow, u32* scratch, u32* s_earlier, u32* head_rows,
                                          u32* head_groups, u32 group, u32 epoch, u32 n_bags, u64* uniq,
@@ -393,7 +393,7 @@ __device__ __noinline__ void slow_region(const u64* skeys, const u64* spay, u64*
 // equal: order by the bits below lo first, then (stable) by the bits above, so that all
 // 64 bits count.  Rare; out of line.
 template <int ITEMS>
-__device__ __noinline__ void resort_all_bits(u64* words, uint16_t* hist, const u64* skeys, u32 start,
+__device__ __forceinline__ void resort_all_bits(u64* words, uint16_t* hist, const u64* skeys, u32 start,
                                              u32 cnt, int lo, u64 bit_mask, int top_pass) {
   const u32 tid = threadIdx.x;
   const u32 items = (cnt + kChunkThreads - 1) / kChunkThreads;
