@@ -396,3 +396,50 @@ def test_dump_dirty_rows(opt):
     # accumulators read back without the mark
     _, a, f = gt.get(dev_keys(want))
     assert f.all().item() and (a >= 0).all().item()
+
+
+def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
+    """The dedup alone (unique keys and inverse ranks, bit-exact) on mid-sized batches whose
+    heavy keys change from batch to batch: the bucket form learns heavy keys from earlier
+    lookups, so a key that turns hot without warning makes a region too large for LDS and
+    takes the route through global memory; unhashed, consecutive keys put everything into
+    one bucket.  Each case must give the oracle's result whichever form runs."""
+    rng = np.random.default_rng(21)
+    dim, n_bags = 8, 4096
+    gt = hps.HpsTable(600_000, dim, 400_000, n_bags, lr=0.05)
+    ids = synth.mix64(np.arange(500_000, dtype=np.uint64))
+    offsets = None
+
+    def batch(n, hot, share, plain_ids=False):
+        cold = rng.integers(0, 400_000, size=n)
+        keys = ids[cold]
+        if plain_ids:
+            keys = (np.uint64(1) << np.uint64(40)) + cold.astype(np.uint64)   # unhashed
+        for h, s in zip(hot, share):
+            keys[rng.random(n) < s] = ids[400_000 + h]
+        return keys
+
+    cases = [
+        (300_000, [], []),
+        (300_000, [1, 2, 3], [0.2, 0.05, 0.01]),       # first hot keys: no hint yet
+        (300_000, [1, 2, 3], [0.2, 0.05, 0.01]),
+        (300_000, [1, 2, 3], [0.2, 0.05, 0.01]),       # hinted from here on
+        (350_000, [7, 8], [0.3, 0.02]),                # new hot keys without warning
+        (350_000, [7, 8, 1], [0.1, 0.1, 0.1]),
+        (200_000, [7], [0.9]),                         # one key nearly everything
+        (150_000, [], [], True),                       # consecutive integers: one natural bucket
+        (300_000, [9], [0.001]),                       # back to ordinary
+    ]
+    for case in cases:
+        keys = batch(*case)
+        n = keys.size
+        offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+        print("dedup case", case[:3], "n", n, flush=True)
+        gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+        ou, oi = oracle.dedup(keys)
+        uniq, inv = gt.last_unique()
+        st = gt.stats()
+        assert st.error == 0 and st.last_n_unique == ou.size
+        assert np.array_equal(host_keys(uniq)[: ou.size], ou), "unique keys"
+        assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+        gt.push(torch.zeros((n_bags, dim), device="cuda"))
