@@ -502,11 +502,35 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   // to wait for this one's sort: it is the number of distinct keys, less one if the
   // region starts inside a heavy key's bucket whose earlier part belongs to the region before.
   const bool first_continues = cnt && start > 0 && skeys[start - 1] == key0;
+  if (hb == 0) {
+    // One key only (part of a heavy key's bucket, typically), or nothing: the region is
+    // in order as it stands, its pairs are read in place.
+    const u32 n_heads = cnt && !first_continues ? 1u : 0u;
+    publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
+    const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
+    if (last && tid == 0) { ctx->n_unique = earlier + n_heads; seg_off[earlier + n_heads] = n; }
+    const u32 rank = earlier + n_heads - 1;      // of the key (cnt > 0: earlier + n_heads >= 1)
+    if (n_heads && tid == 0) {
+      uniq[rank] = key0;
+      seg_off[rank] = start;
+      if (key0 == kEmptyKey) raise_error(st, kErrReserved);
+    }
+#pragma unroll
+    for (int r = 0; r < kChunkItems; ++r) {
+      const u32 p = r * kChunkThreads + tid;
+      if ((u32)r < items && p < cnt) {
+        const u64 pay = spay[start + p];
+        bagperm[start + p] = min((u32)(pay >> 32), n_bags - 1) | (p == 0 && n_heads ? 0x80000000u : 0u);
+        inverse[(u32)pay & kIndexMask] = (i32)rank;
+      }
+    }
+    return;
+  }
   const bool early = cnt <= kCountMax;
   u32 n_heads = 0;
   if (early) {
-    const u32 distinct = hb == 0 ? (cnt ? 1u : 0u) : count_distinct<ITEMS>(key, items, cnt, L.words, L.scratch);
-    n_heads = distinct - (first_continues && distinct ? 1u : 0u);
+    const u32 distinct = count_distinct<ITEMS>(key, items, cnt, L.words, L.scratch);
+    n_heads = distinct - (first_continues ? 1u : 0u);
     publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
   }
   HPS_T(2);
