@@ -439,7 +439,7 @@ template <int ITEMS>
 __global__ void __launch_bounds__(kChunkThreads, 4)
 chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
                 u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
-                int nat_shift,
+                int nat_shift, u32 max_heavy,
                 const HeavySet* __restrict__ heavy_set, u32* __restrict__ head_rows,
                 u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
                 u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
@@ -451,7 +451,7 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   __shared__ ChunkLds<ITEMS> L;
   const u32 tid = threadIdx.x;
   if (tid == 0) L.s_chunk = atomicAdd(ticket, 1u);
-  load_heavy(L.hv, heavy_set);
+  load_heavy(L.hv, heavy_set, max_heavy);
   __syncthreads();
   const u32 chunk = L.s_chunk;
   const u32 n_chunks = (n + kChunkSpan - 1) / kChunkSpan;

@@ -133,18 +133,23 @@ uint32_t tile_group(uint64_t n_tiles) {
 // Largest dedup the bucket path takes: beyond it a heavy key the hint misses could
 // hold more occurrences than a region has room for.
 constexpr uint64_t kBucketPathMaxKeys = 12ull << 20;
-// Smallest one: below it the fixed costs of the bucket path outweigh the passes it saves.
-constexpr uint64_t kBucketPathMinKeys = 1ull << 17;
 
 // Bucket path: enough leading key bits that a natural bucket holds kNaturalBucket
-// occurrences on average at most; the passes sort by the bytes of the bucket id.
+// occurrences on average at most; the passes sort by the bytes of the bucket id.  Up to
+// kOnePassMaxKeys occurrences 7 leading bits and 63 heavy keys do: ids below 256, one pass.
+constexpr uint64_t kOnePassMaxKeys = 1ull << 16;
+
 SortPlan bucket_plan(uint64_t n) {
   SortPlan p;
   int bits = 1;
-  while (bits < 24 && ((n + kNaturalBucket - 1) / kNaturalBucket) > (1ull << bits)) ++bits;
-  const uint64_t max_id = (1ull << bits) + 2 * kMaxHeavy + 1;
+  while (bits < 15 && ((n + kNaturalBucket - 1) / kNaturalBucket) > (1ull << bits)) ++bits;
+  p.max_heavy = kMaxHeavy;
   p.n_pass = 2;      // ids stay below 2^16 for every n the bucket path takes
-  (void)max_id;
+  if (n <= kOnePassMaxKeys) {
+    if (bits > 7) bits = 7;
+    p.max_heavy = 63;
+    p.n_pass = 1;
+  }
   p.low_shift = 0;
   p.group = tile_group((n + kSortTile - 1) / kSortTile);
   p.by_id = 1;
@@ -156,6 +161,7 @@ SortPlan sort_plan(uint64_t n) {
   SortPlan p;
   p.by_id = 0;
   p.nat_shift = 0;
+  p.max_heavy = 0;
   int log2n = 1;
   while ((1ull << log2n) < n) ++log2n;
   int want = (2 * log2n - 2 + 7) / 8;
@@ -281,9 +287,9 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
     if (epoch == 1 && t->serial >= kEpochMod)   // the epochs start over: forget the old words
       fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
     // The bucket path needs to know the heavy keys, which it learns from the lookups: the
-    // first two dedups of a table take the plain passes, as do small and very large ones.
+    // first two dedups of a table take the plain passes, as do very large ones.
     const bool buckets = n <= kBucketPathMaxKeys && t->dedup_mode != 1 &&
-                         (t->dedup_mode == 2 || (n >= kBucketPathMinKeys && t->lookup_serial >= 2));
+                         (t->dedup_mode == 2 || t->lookup_serial >= 2);
     const SortPlan plan = buckets ? bucket_plan(n) : sort_plan(n);
     u64* kcur = t->w<u64>(L.keys_a);
     u64* kalt = t->w<u64>(L.keys_b);
@@ -327,7 +333,8 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       const unsigned n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
 #define HPS_CHUNKS(ITEMS)                                                                          \
   chunk_sort_emit<ITEMS><<<n_chunks, kChunkThreads, 0, s>>>(                                       \
-      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, plan.nat_shift, heavy,    \
+      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, plan.nat_shift,            \
+      plan.max_heavy, heavy,                                                                        \
       t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), tile_group(n_chunks), tickets + kMaxPasses, \
       epoch, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm),                 \
       t->w<u32>(C.seg_off), ctx, t->view.st)

@@ -63,6 +63,7 @@ struct SortPlan {
   u32 group;        // tiles per group
   int by_id;        // 1: the passes sort by the bucket id of the key (see bucket_id) instead
   int nat_shift;    // by_id: 64 - number of leading key bits that make the natural bucket
+  u32 max_heavy;    // by_id: heavy keys that get buckets of their own, at most
 };
 
 __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
@@ -83,21 +84,25 @@ __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
 struct HeavyLds {
   u64 keys[kMaxHeavy + 1];
   u32 span[1 << kHeavyTopBits];
+  u32 max_heavy;     // only the max_heavy smallest heavy keys get buckets of their own
 };
 
 // All threads of the block; the caller's next barrier makes the copy visible.
-__device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set) {
+__device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set, u32 max_heavy) {
   for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += blockDim.x) H.keys[i] = set->keys[i];
   for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += blockDim.x) H.span[i] = set->span[i];
+  if (threadIdx.x == 0) H.max_heavy = max_heavy;
 }
 
-// *heavy tells whether the key is one of the heavy keys.
+// *heavy tells whether the key is one of the heavy keys (that count: see max_heavy;
+// limiting them keeps the ids of a small dedup below 256, one pass, and the id monotone).
 __device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, int nat_shift, bool* heavy) {
   const u32 sp = H.span[(u32)(key >> (64 - kHeavyTopBits))];
   u32 m = sp & 0xFFFFu;
   const u32 end = m + (sp >> 16);
   while (m < end && H.keys[m] < key) ++m;
-  *heavy = m < end && H.keys[m] == key;
+  *heavy = m < end && m < H.max_heavy && H.keys[m] == key;
+  m = min(m, H.max_heavy);
   return (u32)(key >> nat_shift) + 2 * m + (*heavy ? 1u : 0u);
 }
 
@@ -263,7 +268,7 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
   // ---- the first hist_blocks blocks: resets and histograms ----
   __shared__ u32 h[kMaxPasses][kRadix];
   __shared__ HeavyLds hv;
-  if (plan.by_id) load_heavy(hv, heavy_set);
+  if (plan.by_id) load_heavy(hv, heavy_set, plan.max_heavy);
   for (u32 sh = blockIdx.x; sh < (u32)kHistShards; sh += hist_blocks)     // the next pull's counters
     for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads)
       ghist_next[sh * kMaxPasses * kRadix + i] = 0;
