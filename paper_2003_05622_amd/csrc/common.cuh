@@ -40,7 +40,7 @@ struct TableState {
 struct PullCtx {
   u32 n_unique;        // U
   u32 n_long;          // keys the push handles chunk by chunk
-  u32 med_overflow;    // unused
+  u32 reserved0;
   u32 n_chunk_items;   // (key, chunk) work items of the push
   u32 n_evidence;      // sorted positions where a run of equal sorted bits mixes keys
   u32 sort_error;      // set if a look-back wait gave up (never expected)

@@ -1,4 +1,5 @@
-// Key dedup, part 2: from the occurrences sorted by the top bits of their keys
+// Key dedup, part 2, plain form (a table's first dedups and very large ones; the usual
+// form is in bucket.cuh): from the occurrences sorted by the top bits of their keys
 // (skeys[j], spay[j]; payload = occurrence index | bag << 32) to
 //   uniq[U]      ascending unique keys
 //   inverse[N]   rank of each occurrence's key among them

@@ -1,8 +1,8 @@
 // Key dedup, part 1: ordering the key occurrences.
 //
 // The occurrences (key, payload) -- payload = occurrence index and bag number in one
-// 64-bit word -- are sorted by the keys' top `8 * n_pass` bits with a
-// stable least-significant-digit radix sort, 8 bits per pass, ONE kernel per pass:
+// 64-bit word -- are ordered with a stable least-significant-digit radix sort, 8 bits per
+// pass, ONE kernel per pass:
 //
 //   sort_prepare    digit histograms of all passes in one read of the keys (also
 //                   writes bag_of[i], the bag of occurrence i);
@@ -13,9 +13,14 @@
 //                   wave ballots; the tile is staged in LDS and each digit's run is
 //                   written contiguously.
 //
-// Mini-batch keys are hashed feature ids, so the top 8*n_pass bits separate
-// almost all distinct keys; the rare runs that still mix different keys are
-// found and put right afterwards (dedup.cuh), so the result is exact for any input.
+// What the passes sort by comes in two forms.
+//   Bucket ids (by_id plans; the usual form): one or two passes by a 16-bit id made of the
+//   key's leading bits and its place among the heavy keys (bucket_id below); the rest of
+//   the ordering happens per region inside one workgroup (bucket.cuh).
+//   Key bits (plain plans): the keys' top 8 * n_pass bits.  Mini-batch keys are hashed
+//   feature ids, so these bits separate almost all distinct keys; the rare runs that
+//   still mix different keys are found and put right afterwards (dedup.cuh).
+// Either way the dedup's result is exact for any input.
 //
 // Cross-tile counts without a serial chain: tiles are grouped, `group` consecutive
 // tiles (by ticket) per group.  Every tile publishes its digit counts (a row of 256
@@ -278,7 +283,6 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
     if (threadIdx.x == 0) {
       ctx->n_unique = 0;
       ctx->n_long = 0;
-      ctx->med_overflow = 0;
       ctx->n_chunk_items = 0;
       ctx->n_evidence = 0;
       ctx->sort_error = 0;

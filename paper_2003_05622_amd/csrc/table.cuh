@@ -147,7 +147,6 @@ __global__ void __launch_bounds__(64) set_ctx_empty(PullCtx* ctx, u32* seg_off) 
   if (threadIdx.x == 0) {
     ctx->n_unique = 0;
     ctx->n_long = 0;
-    ctx->med_overflow = 0;
     ctx->n_chunk_items = 0;
     ctx->n_evidence = 0;
     ctx->sort_error = 0;
