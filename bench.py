@@ -57,8 +57,8 @@ def stage_bytes(n, u, bags, d):
 
 STAGE_BITS = {"dedup": 0b00011, "lookup": 0b00100, "pool": 0b01000, "push": 0b10000}
 STAGE_KERNELS = {
-    "dedup": "sort_prepare, 2 x onesweep_pass (by bucket id), chunk_sort_emit "
-             "(a table's first two dedups, and very small or very large ones: sort_prepare, "
+    "dedup": "sort_prepare, 1-2 x onesweep_pass (by bucket id), chunk_sort_emit "
+             "(a table's first two dedups, and very large ones: sort_prepare, "
              "n_pass x onesweep_pass, unique_emit, fix_mixed_runs, unique_emit)",
     "lookup": "lookup_keys<0>, insert_missing",
     "pool": "pool_bags",

@@ -29,13 +29,10 @@ namespace hps {
 
 constexpr int kChunkThreads = 512;
 constexpr int kChunkWaves = kChunkThreads / kWave;
-// Elements per thread: 8 or 12, i.e. regions of up to 4096 or 6144 elements in LDS.  The
-// smaller form (less LDS, fewer registers) serves as long as a key the hint misses cannot
-// overflow a region: chunk_items() below.
-constexpr int kChunkItemsMax = 12;
+constexpr int kChunkItems = 8;                                // per thread: regions of up to 4096 elements in LDS
 constexpr u32 kChunkSpan = 2048;                              // positions between nominal cuts
 constexpr u32 kNaturalBucket = 512;                           // mean size of a leading-bits bucket, at most
-constexpr u32 kHeavyShare = 4096;                             // heavy: more than n / kHeavyShare occurrences
+constexpr u32 kHeavyShare = 16384;                            // heavy: more than n / kHeavyShare occurrences
 constexpr u32 kHeavyMin = 64;
 constexpr int kSortBits = 32;
 constexpr u32 kIndexMask = 0xFFFFFFu;   // payload: occurrence index in bits 0..23, bag in 32..63      // key bits a region is ordered by at first (all of them if that fails)
@@ -414,14 +411,6 @@ __device__ __forceinline__ void resort_all_bits(u64* words, uint16_t* hist, cons
   }
   __syncthreads();
   lds_radix_sort<kChunkThreads, ITEMS>(words, cnt, 16, top_pass, hist);
-}
-
-// Elements per thread for a dedup of n occurrences: a region holds kChunkSpan positions,
-// the rest of a natural bucket (kNaturalBucket on average, rarely twice that) and, if the
-// hint misses it, a key of up to n / kHeavyShare occurrences.
-inline int chunk_items(unsigned long long n) {
-  const unsigned long long need = kChunkSpan + 2 * kNaturalBucket + n / kHeavyShare;
-  return need <= (unsigned long long)kChunkThreads * 8 ? 8 : kChunkItemsMax;
 }
 
 // Phase timing for development builds only (-DHPS_CHUNK_TIMING adds a kernel argument).

@@ -51,7 +51,7 @@ struct PullCtx {
 // Keys that make up a large share of a mini-batch (bucket.cuh).  HeavySet: ascending,
 // padded with all-ones.  HeavyRaw: the keys the last lookup saw often, in arrival
 // order; only a hint, readers cope with any content.
-constexpr int kMaxHeavy = 255;
+constexpr int kMaxHeavy = 1023;
 constexpr int kHeavyTopBits = 10;
 struct HeavySet {
   u32 count;
@@ -66,12 +66,14 @@ struct HeavyRaw {
   u32 pad;
   u64 keys[kMaxHeavy + 1];
 };
-// Lookup s (s = 1, 2, ...) fills raw[s % 3]; the kernel after it puts that list in order
-// as set[s % 3] and empties raw[(s + 1) % 3] for the next lookup.  A dedup issued when s
-// lookups have been issued reads set[(s - 1) % 3]: that lookup is certainly complete (the
-// dedup's context was released by a later push) and nobody writes the slot again before
-// lookup s + 2, which needs this dedup's result.  So every kernel of a dedup sees the
-// same, unchanging list, whatever streams the calls were issued on.
+// Lookup s (s = 1, 2, ...) fills raw[s % 3]; the push of the same pull (an extra block of
+// its kernel; for an accumulate the kernel after the lookup) puts that list in order as
+// set[s % 3] and empties raw[(s + 1) % 3] for the next lookup.  A dedup issued when s
+// lookups have been issued reads set[(s - 1) % 3]: the push of pull s - 1 is certainly
+// complete (the dedup waits for the push that released its context, which is that push or a
+// later one) and nobody writes the slot again before push s + 2, which comes after this
+// dedup's pull.  So every kernel of a dedup sees the same, unchanging list, whatever
+// streams the calls were issued on.
 constexpr u32 kHeavyRing = 3;
 struct HeavyRing {
   HeavyRaw raw[kHeavyRing];

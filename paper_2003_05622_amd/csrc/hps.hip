@@ -133,6 +133,8 @@ uint32_t tile_group(uint64_t n_tiles) {
 // Largest dedup the bucket path takes: beyond it a heavy key the hint misses could
 // hold more occurrences than a region has room for.
 constexpr uint64_t kBucketPathMaxKeys = 12ull << 20;
+static_assert(kChunkSpan + 2 * kNaturalBucket + kBucketPathMaxKeys / kHeavyShare + 64 <= kChunkThreads * kChunkItems,
+              "a region must have room for its span, a natural bucket and one heavy key the hint missed");
 
 // Bucket path: enough leading key bits that a natural bucket holds kNaturalBucket
 // occurrences on average at most; the passes sort by the bytes of the bucket id.  Up to
@@ -259,7 +261,7 @@ static void launch_push(hps_table* t, uint64_t n, PushArgs& a, hipStream_t s) {
   a.short_blocks = grid_for(n, kPushThreads / LPR, kPushShortBlocks);
   a.medium_blocks = kPushMediumBlocks;
   const unsigned chunk_blocks = grid_for(n / kChunk + 1, 1, kPushChunkBlocks);
-  const unsigned main_blocks = a.short_blocks + a.medium_blocks + chunk_blocks;
+  const unsigned main_blocks = a.short_blocks + a.medium_blocks + chunk_blocks + (a.ring ? 1 : 0);
   const unsigned long_blocks = grid_for(n / (kMedSeg + 1) + 1, 1, kPushLongBlocks);
   if (t->dim <= (uint32_t)LPR * 4) {
     push_main<LPR, 1><<<main_blocks, kPushThreads, 0, s>>>(t->view, a);
@@ -338,8 +340,7 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), tile_group(n_chunks), tickets + kMaxPasses, \
       epoch, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm),                 \
       t->w<u32>(C.seg_off), ctx, t->view.st)
-      if (chunk_items(n) == 8) HPS_CHUNKS(8);
-      else HPS_CHUNKS(kChunkItemsMax);
+      HPS_CHUNKS(kChunkItems);
 #undef HPS_CHUNKS
     } else {
       // the second unique_emit only acts after a repair
@@ -398,6 +399,8 @@ static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, P
   a.lr = t->opt.lr;
   a.eps = t->opt.eps;
   a.kind = kind;
+  a.ring = nullptr;
+  a.ring_slot = 0;
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -543,7 +546,7 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
       lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
                                                       nullptr, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                    d_acc, nullptr, 0, nullptr, 0);
+                                                    d_acc, nullptr, 0);
   }
   commit_insert<<<1, 64, 0, s>>>(t->view.st);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
@@ -598,9 +601,7 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
     launch_lookup(t, c, cx.n_keys, s);
     insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
-                                                          nullptr, miss_list, shard_cap,
-                                                          t->w<HeavyRing>(t->wl.heavy_raw),
-                                                          (u32)(t->lookup_serial % kHeavyRing));
+                                                          nullptr, miss_list, shard_cap);
   }
   if (!cx.n_bags) commit_insert<<<1, 64, 0, s>>>(t->view.st);   // else the pooling kernel does it
   stage_mark(t, HPS_STAGE_LOOKUP, s);
@@ -641,6 +642,8 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
     PushArgs a;
     fill_push_args(t, c, d_pooled_grads,
                    t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? kStepElementwise : kStepRowwise, a);
+    a.ring = t->w<HeavyRing>(t->wl.heavy_raw);       // the pull's lookup listed the frequent keys
+    a.ring_slot = (u32)(t->lookup_serial % kHeavyRing);
     stage_mark(t, HPS_STAGE_PUSH, s);
 #define CALL(LPR) launch_push<LPR>(t, cx.n_keys, a, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)

@@ -49,6 +49,8 @@ struct PushArgs {
   float* partials;      // [chunk item][dim]
   float lr, eps;
   int kind;   // what a touched row takes: kStepRowwise, kStepElementwise or kStepAdd
+  HeavyRing* ring;   // != null: one more block puts the pull's list of frequent keys in order
+  u32 ring_slot;
 };
 
 // One step on row r with the row's summed gradient (or summed values) held as
@@ -270,13 +272,21 @@ __global__ void __launch_bounds__(kPushThreads) push_main(TableView t, PushArgs 
   __shared__ float4 lds[kPushThreads];
   if (load_error(t.st) != 0) return;
   const u32 b = blockIdx.x;
+  if (a.ring && b == gridDim.x - 1) {
+    // Not part of the push: the list of frequent keys the pull's lookup left (common.cuh) is
+    // put in order here, where it costs nothing -- the next dedup that reads it starts after
+    // this push, and the push takes several times longer than this block.
+    finalize_heavy(a.ring, a.ring_slot);
+    return;
+  }
+  const u32 role_blocks = a.ring ? gridDim.x - 1 : gridDim.x;
   if (b < a.short_blocks) {
     push_short_role<LPR, COLS>(t, a, b, a.short_blocks);
   } else if (b < a.short_blocks + a.medium_blocks) {
     push_medium_role<LPR, COLS>(t, a, b - a.short_blocks, a.medium_blocks);
   } else {
     push_chunks_role<LPR, COLS>(t, a, b - a.short_blocks - a.medium_blocks,
-                          gridDim.x - a.short_blocks - a.medium_blocks, lds);
+                          role_blocks - a.short_blocks - a.medium_blocks, lds);
   }
 }
 

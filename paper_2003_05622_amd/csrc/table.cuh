@@ -72,24 +72,32 @@ __device__ __forceinline__ bool acc_is_marked(float stored) {
 // Called by all threads of one block (exactly 256) once lookup `slot`'s list of frequent
 // keys is complete: orders it into the ring's set and empties the next list.
 __device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
-  __shared__ u64 k[kMaxHeavy + 1];
-  __shared__ u64 sorted[kMaxHeavy + 1];
+  constexpr u32 kSize = kMaxHeavy + 1;             // a power of two
+  __shared__ u64 sorted[kSize];
   const u32 tid = threadIdx.x;
   const HeavyRaw& raw = ring->raw[slot];
   HeavySet& set = ring->set[slot];
   const u32 count = min(raw.count, (u32)kMaxHeavy);
-  k[tid] = tid < count ? raw.keys[tid] : ~0ull;
-  __syncthreads();
-  const u64 mine = k[tid];
-  u32 rank = 0;
-#pragma unroll 8
-  for (u32 i = 0; i <= (u32)kMaxHeavy; ++i) {
-    const u64 o = k[i];
-    rank += (o < mine || (o == mine && i < tid)) ? 1u : 0u;
+  for (u32 i = tid; i < kSize; i += 256) sorted[i] = i < count ? raw.keys[i] : ~0ull;
+  // bitonic sorting network over the smallest power of two that holds the listed keys
+  // (the order of equal keys does not matter; everything behind is all-ones already)
+  u32 size = 2;
+  while (size < count) size <<= 1;
+  for (u32 k = 2; k <= size; k <<= 1) {
+    for (u32 j = k >> 1; j > 0; j >>= 1) {
+      __syncthreads();
+      for (u32 i = tid; i < size; i += 256) {
+        const u32 partner = i ^ j;
+        if (partner > i) {
+          const u64 x = sorted[i], y = sorted[partner];
+          const bool up = (i & k) == 0;
+          if ((x > y) == up) { sorted[i] = y; sorted[partner] = x; }
+        }
+      }
+    }
   }
-  sorted[rank] = mine;                 // the ranks are a permutation of 0..kMaxHeavy
-  set.keys[rank] = mine;
   __syncthreads();
+  for (u32 i = tid; i < kSize; i += 256) set.keys[i] = sorted[i];
   // spans: thread t takes top-bit values 4t .. 4t+3
   u32 first[5];
 #pragma unroll
@@ -362,16 +370,14 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
 // rows != null (pull): the listed missing keys are visited (or, after a list overflow,
 // all keys with rows[u] == kNoRow); rows[u] is set.
 // rows == null (bulk insert): every key is probed again.
-// ring != null (pull): block 0 first puts the lookup's list of frequent keys in order.
 // w_in == null: new rows get the deterministic initial row; else the given values.
 __global__ void __launch_bounds__(kProbeThreads)
 insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
                const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
                const float* __restrict__ w_in, const float* __restrict__ acc_in,
-               const u32* __restrict__ miss_list, u32 shard_cap, HeavyRing* ring, u32 ring_slot) {
+               const u32* __restrict__ miss_list, u32 shard_cap) {
   __shared__ u32 s_total, s_made, s_mine;
-  // the lookup before this kernel has finished: its list of frequent keys is complete
-  if (ring && blockIdx.x == 0) finalize_heavy(ring, ring_slot);
+  const u32 block = blockIdx.x, n_blocks = gridDim.x;
   if (load_error(t.st) != 0) return;
   if (threadIdx.x < kWave) {
     const u32 mine = threadIdx.x < kCountShards ? t.st->miss_shard[threadIdx.x] : 0;
@@ -379,7 +385,7 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
     if (threadIdx.x == 0) { s_total = c; s_made = 0; }
-    if (threadIdx.x == blockIdx.x % kCountShards) s_mine = mine;
+    if (threadIdx.x == block % kCountShards) s_mine = mine;
   }
   __syncthreads();
   const u32 total = s_total;
@@ -391,14 +397,14 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   }
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
   const u32 sub = threadIdx.x & 7;
-  const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
-  const u64 n_groups = (u64)gridDim.x * kProbeGroups;
+  const u64 group = (u64)block * kProbeGroups + (threadIdx.x >> 3);
+  const u64 n_groups = (u64)n_blocks * kProbeGroups;
   u32 made = 0;
   const bool listed = rows != nullptr && t.st->miss_overflow == 0;
   // listed: this block's share of its shard's list; else every key
-  const u32 shard = blockIdx.x % kCountShards;
-  const u32 shard_blocks = (gridDim.x - shard + kCountShards - 1) / kCountShards;
-  const u64 first = listed ? (u64)(blockIdx.x / kCountShards) * kProbeGroups + (threadIdx.x >> 3) : group;
+  const u32 shard = block % kCountShards;
+  const u32 shard_blocks = (n_blocks - shard + kCountShards - 1) / kCountShards;
+  const u64 first = listed ? (u64)(block / kCountShards) * kProbeGroups + (threadIdx.x >> 3) : group;
   const u64 stride = listed ? (u64)shard_blocks * kProbeGroups : n_groups;
   const u64 count = listed ? (u64)s_mine : n_keys;
   for (u64 e = first; e < count; e += stride) {
@@ -427,7 +433,7 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   }
   if (sub == 0 && made) atomicAdd(&s_made, made);
   __syncthreads();
-  if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
+  if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[block % kCountShards], s_made);
 }
 
 // dump: every occupied slot (DIRTY: every occupied slot whose row is marked as
