@@ -40,6 +40,10 @@
  *     be issued on one stream at a time (or be ordered by the caller).  hps_prepare
  *     does not touch the table and may run on another stream; the library orders it
  *     against the calls that share its buffers with HIP events.
+ *   - The key dedup has two forms with identical results; the library picks one per call
+ *     from the mini-batch's size and the table's history (its third and later dedups use
+ *     the keys that earlier lookups found frequent).  The environment variable HPS_DEDUP,
+ *     read by hps_create, pins the form: "radix" or "bucket" (tests, comparison runs).
  */
 #ifndef HPS_H_
 #define HPS_H_
