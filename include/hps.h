@@ -63,7 +63,8 @@ typedef enum {
   HPS_EFULL = -2,     /* more keys than the table's capacity                        */
   HPS_ERESERVED = -3, /* the reserved key appeared in the input                     */
   HPS_ESTATE = -4,    /* push without an outstanding pull, or similar misuse        */
-  HPS_EDEVICE = -5,   /* a HIP call failed / no usable GPU                          */
+  HPS_EDEVICE = -5,   /* a HIP call failed / no usable GPU; as sticky device status: an
+                         internal wait between workgroups gave up (never expected)     */
   HPS_ENOMEM = -6     /* storage or workspace buffer too small                      */
 } hps_status;
 

@@ -18,6 +18,7 @@ constexpr int kSlotsPerLine = 8;     // 8 keys of 8 bytes = one 64-byte line, pr
 // Device-side status values mirror hps_status.
 constexpr int kErrFull = -2;
 constexpr int kErrReserved = -3;
+constexpr int kErrInternal = -5;   // HPS_EDEVICE: a dedup's cross-workgroup wait gave up (never expected)
 
 constexpr int kCountShards = 64;   // counters that many blocks add to are spread over this many words
 

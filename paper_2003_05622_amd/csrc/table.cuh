@@ -257,6 +257,10 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   __shared__ u32 s_list[MODE == 0 ? kMissLdsCap : 1];
   __shared__ u32 s_med_list[MODE == 0 ? kMedLdsCap : 1];
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
+  if (MODE == 0 && often.ctx->sort_error != 0) {     // the dedup before this lookup failed
+    if (threadIdx.x == 0) raise_error(t.st, kErrInternal);
+    return;
+  }
   if (load_error(t.st) != 0) return;
   if (threadIdx.x == 0) { s_missing = 0; s_med = 0; }
   __syncthreads();
