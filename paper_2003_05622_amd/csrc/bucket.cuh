@@ -413,15 +413,6 @@ __device__ __forceinline__ void resort_all_bits(u64* words, uint16_t* hist, cons
   lds_radix_sort<kChunkThreads, ITEMS>(words, cnt, 16, top_pass, hist);
 }
 
-// Phase timing for development builds only (-DHPS_CHUNK_TIMING adds a kernel argument).
-#ifdef HPS_CHUNK_TIMING
-#define HPS_CHUNK_DBG_PARAM , unsigned long long* __restrict__ dbg
-#define HPS_T(k) do { if (threadIdx.x == 0) dbg[(size_t)chunk * 16 + (k)] = wall_clock64(); } while (0)
-#else
-#define HPS_CHUNK_DBG_PARAM
-#define HPS_T(k) do { } while (0)
-#endif
-
 // skeys/spay: the pairs ordered by bucket id (payload = occurrence index | bag << 32),
 // read only; ka/pa and kb/pb: scratch of the same shape (only touched the slow way).
 template <int ITEMS>
@@ -433,7 +424,7 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
                 u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
                 u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
                 u32* __restrict__ bagperm, u32* __restrict__ seg_off, PullCtx* __restrict__ ctx,
-                TableState* __restrict__ st HPS_CHUNK_DBG_PARAM) {
+                TableState* __restrict__ st) {
   constexpr int kChunkItems = ITEMS;
   constexpr u32 kChunkCap = kChunkThreads * ITEMS;
   constexpr u32 kCountMax = kChunkCap * 3 / 4;      // beyond this the table of the distinct count is too full
@@ -445,7 +436,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   const u32 chunk = L.s_chunk;
   const u32 n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
   const bool last = chunk + 1 == n_chunks;
-  HPS_T(0);
   if (tid == 0) {
     L.s_border[0] = chunk == 0 ? 0u : ~0u;
     L.s_border[1] = last ? n : ~0u;
@@ -455,7 +445,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   find_borders(skeys, n, chunk * kChunkSpan, (chunk + 1) * kChunkSpan, L.hv, nat_shift, L.s_border);
   const u32 start = L.s_border[0], end = L.s_border[1];
   const u32 cnt = end - start;       // start <= end: both borders come from the same rule
-  HPS_T(1);
 
   if (cnt > kChunkCap) {
     slow_region(skeys, spay, ka, pa, kb, pb, n, start, end, chunk, last, L.slow, L.scratch, &L.s_earlier,
@@ -522,7 +511,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
     n_heads = distinct - (first_continues ? 1u : 0u);
     publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
   }
-  HPS_T(2);
 
   u64 prev_key = 0;
   const u32 j0 = tid * items;          // this thread's run of sorted positions
@@ -542,7 +530,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
       }
       __syncthreads();
       lds_radix_sort<kChunkThreads, kChunkItems>(L.words, cnt, 16, top_pass, L.hist);
-      HPS_T(3);
     } else {
       resort_all_bits<ITEMS>(L.words, L.hist, skeys, start, cnt, lo, bit_mask, top_pass);
     }
@@ -571,7 +558,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
     mixed = __syncthreads_or(bad && lo > 0 && attempt == 0);
     if (!mixed) break;
   }
-  HPS_T(4);
 
   bool head[kChunkItems];
   u32 heads = 0;
@@ -602,11 +588,9 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   }
   u32 total;
   const u32 before = block_excl_sum<kChunkThreads>(heads, L.scratch, &total);
-  HPS_T(5);
   if (early && total != n_heads && tid == 0) ctx->sort_error = 1;     // never expected
   if (!early) publish_heads(chunk, total, group, epoch, head_rows, head_groups, ctx);
   const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
-  HPS_T(6);
   if (last && tid == 0) { ctx->n_unique = earlier + total; seg_off[earlier + total] = n; }
   u32 rank = earlier + before;         // heads before this thread's first position
 #pragma unroll
@@ -622,10 +606,6 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
       inverse[(u32)pay[k] & kIndexMask] = (i32)(rank - 1);
     }
   }
-  HPS_T(7);
-#ifdef HPS_CHUNK_TIMING
-  if (tid == 0) { dbg[(size_t)chunk * 16 + 8] = cnt; dbg[(size_t)chunk * 16 + 9] = top_pass; }
-#endif
 }
 
 }  // namespace hps
