@@ -443,3 +443,32 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         assert np.array_equal(host_keys(uniq)[: ou.size], ou), "unique keys"
         assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
         gt.push(torch.zeros((n_bags, dim), device="cuda"))
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 4097, 6143, 6144, 6145,
+                               65535, 65536, 65537, 131072])
+def test_dedup_sizes_around_tile_and_region_borders(n, dedup_form):
+    """Unique keys and inverse ranks (bit-exact) for batch sizes at and next to the sizes where
+    the dedup changes shape: a wave, a sort tile (3072), a region span (2048) and capacity
+    (4096), one pass or two (65536).  Three key mixes per size: all distinct, few distinct
+    (long runs of equal keys across region borders), and one heavy key among distinct ones."""
+    rng = np.random.default_rng(n)
+    dim = 4
+    gt = hps.HpsTable(400_000, dim, 140_000, 64, lr=0.05)
+    pool = synth.mix64(np.arange(300_000, dtype=np.uint64))
+    mixes = [
+        pool[rng.permutation(300_000)[:n]],
+        pool[rng.integers(0, 7, size=n)],
+        np.where(rng.random(n) < 0.6, pool[5], pool[rng.integers(0, 300_000, size=n)]),
+    ]
+    for rounds in range(2):            # the second round runs with a hint about heavy keys
+        for keys in mixes:
+            offsets = np.minimum(np.arange(65, dtype=np.int64) * ((n + 63) // 64), n).astype(np.int32)
+            gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), 64, 1)
+            ou, oi = oracle.dedup(keys)
+            uniq, inv = gt.last_unique()
+            st = gt.stats()
+            assert st.error == 0 and st.last_n_unique == ou.size
+            assert np.array_equal(host_keys(uniq), ou), "unique keys"
+            assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+            gt.push(torch.zeros((64, dim), device="cuda"))
