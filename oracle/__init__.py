@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.hpo_dump.argtypes = [vp, vp, vp, vp, u64, vp]
         L.hpo_dump_dirty.restype = i32
         L.hpo_dump_dirty.argtypes = [vp, vp, vp, vp, u64, vp]
+        L.hpo_set_pooling.restype = i32
+        L.hpo_set_pooling.argtypes = [vp, ctypes.c_int]
         L.hpo_accumulate.restype = i32
         L.hpo_accumulate.argtypes = [vp, vp, u64, vp, vp]
         _lib = L
@@ -197,6 +199,9 @@ class OracleTable:
         f = np.zeros(n, dtype=np.uint8)
         _check(lib().hpo_get(self._h, _p(keys), n, _p(w), _p(a), _p(f)), "get")
         return w, a, f.astype(bool)
+
+    def set_pooling(self, mean: bool) -> None:
+        _check(lib().hpo_set_pooling(self._h, 1 if mean else 0), "set_pooling")
 
     def accumulate(self, keys, values) -> int:
         """Adds the value rows onto the rows of their keys; returns the number of

@@ -70,7 +70,9 @@ struct Table {
   std::vector<uint64_t> uniq;
   std::vector<int32_t> inverse;
   std::vector<int32_t> bag_of;
+  std::vector<int32_t> bag_len;           // occurrences in each bag of the outstanding pull
   uint64_t n_bags = 0;
+  int mean_pooling = 0;                   // 0: a bag's rows are summed; 1: averaged
 
   uint64_t size() const { return row_key.size() + implicit_rows - implicit_seen; }
 };
@@ -239,6 +241,7 @@ int hpo_pull(void* h, const uint64_t* keys, uint64_t n, const int32_t* offsets, 
   if (status != OK) { t.pulled = false; return status; }
 
   t.bag_of.resize(n);
+  t.bag_len.assign(n_bags, 0);
   std::vector<double> sum(t.dim);
   for (uint64_t b = 0; b < n_bags; ++b) {
     std::fill(sum.begin(), sum.end(), 0.0);
@@ -247,10 +250,25 @@ int hpo_pull(void* h, const uint64_t* keys, uint64_t n, const int32_t* offsets, 
       const float* row = &t.w[row_of[t.inverse[i]] * t.dim];
       for (uint32_t j = 0; j < t.dim; ++j) sum[j] += (double)row[j];
     }
-    for (uint32_t j = 0; j < t.dim; ++j) pooled[b * t.dim + j] = (float)sum[j];
+    const int32_t len = offsets[b + 1] - offsets[b];
+    t.bag_len[b] = len;
+    const double scale = t.mean_pooling && len > 0 ? 1.0 / (double)len : 1.0;
+    for (uint32_t j = 0; j < t.dim; ++j) pooled[b * t.dim + j] = (float)(sum[j] * scale);
   }
   t.n_bags = n_bags;
   t.pulled = true;
+  return OK;
+}
+
+// Pooling of the bags: sum (0, the default) or mean (1: the pooled row is the average of
+// the bag's rows, and the bag's upstream gradient reaches each of its occurrences divided
+// by the bag's length).  Not from the paper, which leaves the embedding layer's reduction
+// to the trainer; takes effect from the next pull on.
+int hpo_set_pooling(void* h, int mean) {
+  Table& t = *static_cast<Table*>(h);
+  if (t.pulled) return ESTATE;
+  if (mean != 0 && mean != 1) return EINVAL;
+  t.mean_pooling = mean;
   return OK;
 }
 
@@ -286,8 +304,11 @@ int hpo_push(void* h, const float* grads) {
   for (size_t u = 0; u < U; ++u) {
     std::fill(g.begin(), g.end(), 0.0);
     for (uint64_t p = start[u]; p < start[u + 1]; ++p) {
-      const float* row = grads + (uint64_t)t.bag_of[occ[p]] * t.dim;
-      for (uint32_t j = 0; j < t.dim; ++j) g[j] += (double)row[j];
+      const int32_t bag = t.bag_of[occ[p]];
+      const float* row = grads + (uint64_t)bag * t.dim;
+      // mean pooling: an occurrence's share of its bag's gradient is 1 / (bag length)
+      const double share = t.mean_pooling ? 1.0 / (double)t.bag_len[bag] : 1.0;
+      for (uint32_t j = 0; j < t.dim; ++j) g[j] += (double)row[j] * share;
     }
     const uint64_t r = t.index.at(t.uniq[u]);
     float* w = &t.w[r * t.dim];

@@ -669,3 +669,63 @@ def test_dump_dirty_hands_over_exactly_the_updated_rows_once():
     k, w, _ = t.dump_dirty()
     assert np.array_equal(k, some) and np.array_equal(w, gw[::7] + np.float32(1.0))
     assert np.array_equal(t.dump()[0], np.unique(np.concatenate([synth.prefill_keys(0, cfg.n_prefill), want])))
+
+
+# ----------------------------------------------------------------------------- mean pooling
+
+def test_mean_pooling_whole_step_vs_torch_autograd():
+    # EmbeddingBag(mode="mean") forward, torch autograd for the routing of the bag gradients
+    # (each occurrence gets 1/len of it), torch's sparse Adagrad for the step: three library
+    # routines the oracle's mean pooling has to agree with over several steps.
+    rng = np.random.default_rng(43)
+    n_keys, d, nb = 50, 6, 48
+    t, keys, w = _table_with_values(rng, n_keys, d, opt=oracle.ADAGRAD_ELEMENTWISE, lr=0.05,
+                                    eps=1e-8, init_acc=0.1)
+    t.set_pooling(True)
+    emb = torch.nn.EmbeddingBag(n_keys, d, mode="mean", sparse=True).double()
+    with torch.no_grad():
+        emb.weight.copy_(torch.from_numpy(w.astype(np.float64)))
+    opt = torch.optim.Adagrad(emb.parameters(), lr=float(np.float32(0.05)),
+                              initial_accumulator_value=float(np.float32(0.1)),
+                              eps=float(np.float32(1e-8)))
+    for step in range(4):
+        sizes = rng.integers(0, 6, size=nb)               # includes empty bags
+        offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+        idx = rng.integers(0, n_keys, size=int(offsets[-1]))
+        grads = rng.normal(0, 0.1, size=(nb, d)).astype(np.float32)
+        pooled = t.pull(keys[idx], offsets)
+        opt.zero_grad()
+        out = emb(torch.from_numpy(idx), torch.from_numpy(offsets[:-1].astype(np.int64)))
+        assert close(pooled, out.detach().numpy())
+        assert not pooled[sizes == 0].any()
+        out.backward(torch.from_numpy(grads.astype(np.float64)))
+        opt.step()
+        t.push(grads)
+        wo, ao, f = t.get(keys)
+        assert f.all() and close(wo, emb.weight.detach().numpy())
+    assert close(ao, opt.state[emb.weight]["sum"].numpy())
+
+
+def test_mean_pooling_closed_forms_and_state():
+    t = OracleTable(16, 4, lr=0.5, eps=0.0, init_acc=0.0)
+    keys = np.array([3, 4], dtype=np.uint64)
+    t.insert(keys, weights=np.array([[1, 2, 3, 4], [3, 2, 1, 0]], np.float32))
+    t.set_pooling(True)
+    # bag 0 = {3, 3, 4, 4}: mean = (2, 2, 2, 2); bag 1 = {4}: the row itself
+    pooled = t.pull(np.array([3, 3, 4, 4, 4], dtype=np.uint64), np.array([0, 4, 5], np.int32))
+    assert pooled.tolist() == [[2.0, 2.0, 2.0, 2.0], [3.0, 2.0, 1.0, 0.0]]
+    with pytest.raises(OracleError):
+        t.set_pooling(False)                               # not inside a step
+    # key 3: two occurrences in a bag of four -> 2 * g0 / 4; key 4: 2 * g0 / 4 + g1
+    g = np.array([[4, 0, -4, 8], [1, 1, 1, 1]], np.float32)
+    t.push(g)
+    w, a, _ = t.get(keys)
+    g3 = np.array([2, 0, -2, 4], np.float64)
+    g4 = np.array([3, 1, -1, 5], np.float64)
+    for row, acc, w0, gk in ((w[0], a[0], [1, 2, 3, 4], g3), (w[1], a[1], [3, 2, 1, 0], g4)):
+        G = (gk ** 2).mean()
+        assert acc[0] == np.float32(G)
+        assert np.array_equal(row, (np.array(w0, np.float64) - 0.5 * gk / np.sqrt(G)).astype(np.float32))
+    t.set_pooling(False)                                   # back to sums
+    pooled = t.pull(np.array([3, 3], dtype=np.uint64), np.array([0, 2], np.int32))
+    assert np.array_equal(pooled[0], (w[0].astype(np.float64) * 2).astype(np.float32))
