@@ -167,6 +167,14 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream);
  * Errors: HPS_ESTATE when no pull is outstanding. */
 hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream);
 
+/* Pooling of the bags: 0 = sum (the default), 1 = mean: the pooled row is the average of
+ * the bag's rows (an empty bag still gives zeros), and in the push every occurrence
+ * receives its bag's gradient row divided by the bag's length.  Not from the paper, which
+ * leaves the reduction over a slot's features to the trainer; offered because averaged
+ * slots are the other common embedding-layer form.  Takes effect from the next
+ * hps_prepare / hps_pull on.  Errors: HPS_ESTATE between hps_prepare / a pull and its push. */
+hps_status hps_set_pooling(hps_table* t, int mean);
+
 /* Section 4.1 "accumulate" in the paper's literal form (Algorithm 2's per-GPU accumulate):
  * the input is a collection of (key, value row) pairs and every value row is added onto
  * the weights its key references.

@@ -12,7 +12,7 @@ ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
-           "hps_push", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
+           "hps_push", "hps_set_pooling", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
            "hps_stats", "hps_clear_error",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.hps_dump.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64), vp]
         L.hps_dump_dirty.restype = st
         L.hps_dump_dirty.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64), vp]
+        L.hps_set_pooling.restype = st
+        L.hps_set_pooling.argtypes = [vp, ctypes.c_int]
         L.hps_accumulate.restype = st
         L.hps_accumulate.argtypes = [vp, vp, u64, vp, vp]
         L.hps_stats.restype = st
@@ -202,6 +204,10 @@ class HpsTable:
         _check(lib().hps_get(self._h, _ptr(keys), n, _ptr(w), _ptr(a), _ptr(f), _stream()),
                "hps_get")
         return w, a, f.bool()
+
+    def set_pooling(self, mean: bool) -> None:
+        """Bags are summed (False, the default) or averaged (True) from the next pull on."""
+        _check(lib().hps_set_pooling(self._h, 1 if mean else 0), "hps_set_pooling")
 
     def accumulate(self, keys, values) -> None:
         """Adds values[i] onto the row of keys[i] (summed per key; absent keys are skipped)."""

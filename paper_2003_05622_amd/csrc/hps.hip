@@ -65,7 +65,7 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
 // Per pull context (two of them, so that the dedup of the next mini-batch can run
 // while the current one is still between pull and push).
 struct ContextLayout {
-  size_t ctx, uniq, rows, inverse, bagperm, seg_off;
+  size_t ctx, uniq, rows, inverse, bagperm, seg_off, inv_len;
 };
 
 struct WorkspaceLayout {
@@ -76,7 +76,6 @@ struct WorkspaceLayout {
 };
 
 WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
-  (void)bags;
   WorkspaceLayout L;
   const uint64_t n1 = n ? n : 1;
   L.sort_tiles = (n1 + kSortTile - 1) / kSortTile;
@@ -111,6 +110,7 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
     L.c[k].inverse = o; o = align_up(o + n1 * 4);
     L.c[k].bagperm = o; o = align_up(o + n1 * 4);
     L.c[k].seg_off = o; o = align_up(o + (n1 + 1) * 4);
+    L.c[k].inv_len = o; o = align_up(o + (bags ? bags : 1) * 4);    // mean pooling: 1 / bag length
   }
   L.med_list = o;    o = align_up(o + (size_t)kCountShards * L.med_cap * 4);
   L.long_list = o;   o = align_up(o + L.max_long * 8);
@@ -199,6 +199,7 @@ struct hps_table {
   char* ws;
   WorkspaceLayout wl;
   int lpr;
+  bool mean_pooling;        // bags are averaged instead of summed (hps_set_pooling)
   uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
   int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
   uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
@@ -208,6 +209,7 @@ struct hps_table {
   struct Context {
     uint64_t n_keys, n_bags;
     const int32_t* d_offsets;
+    bool mean;            // pooling of this pull (fixed when it is prepared)
     hipEvent_t ready;     // recorded after the dedup kernels
     hipEvent_t released;  // recorded after the push that used the context
     bool ready_set, released_set;
@@ -246,14 +248,15 @@ template <int LPR>
 static void launch_pool(hps_table* t, int c, float* d_pooled, hipStream_t s) {
   const hps_table::Context& cx = t->cx[c];
   const unsigned blocks = grid_for(cx.n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
+  float* inv_len = cx.mean ? t->w<float>(t->wl.c[c].inv_len) : nullptr;
   if (t->dim <= (uint32_t)LPR * 4)
     pool_bags<LPR, 1><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
                                                       (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
-                                                      t->w<u32>(t->wl.c[c].rows), d_pooled);
+                                                      t->w<u32>(t->wl.c[c].rows), d_pooled, inv_len);
   else
     pool_bags<LPR, 4><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
                                                       (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
-                                                      t->w<u32>(t->wl.c[c].rows), d_pooled);
+                                                      t->w<u32>(t->wl.c[c].rows), d_pooled, inv_len);
 }
 
 template <int LPR>
@@ -390,6 +393,7 @@ static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, P
   a.bagperm = t->w<u32>(L.c[c].bagperm);
   a.rows = t->w<u32>(L.c[c].rows);
   a.grads = d_rows;
+  a.inv_len = nullptr;
   a.ctx = t->ctx(c);
   a.med_list = t->w<u32>(L.med_list);
   a.med_cap = (u32)L.med_cap;
@@ -499,6 +503,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
   t->serial = 0;
+  t->mean_pooling = false;
   t->lookup_serial = 0;
   {
     // HPS_DEDUP=radix / bucket pins the dedup to one of its two forms (comparison runs, tests)
@@ -577,6 +582,7 @@ hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
   cx.n_keys = n_keys;
   cx.n_bags = n_bags;
   cx.d_offsets = d_offsets;
+  cx.mean = t->mean_pooling;
   t->prepared = c;
   return HPS_OK;
 }
@@ -642,6 +648,7 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
     PushArgs a;
     fill_push_args(t, c, d_pooled_grads,
                    t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? kStepElementwise : kStepRowwise, a);
+    if (cx.mean) a.inv_len = t->w<float>(t->wl.c[c].inv_len);
     a.ring = t->w<HeavyRing>(t->wl.heavy_raw);       // the pull's lookup listed the frequent keys
     a.ring_slot = (u32)(t->lookup_serial % kHeavyRing);
     stage_mark(t, HPS_STAGE_PUSH, s);
@@ -653,6 +660,13 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   }
   if (hipEventRecord(cx.released, s) != hipSuccess) return HPS_EDEVICE;
   cx.released_set = true;
+  return HPS_OK;
+}
+
+hps_status hps_set_pooling(hps_table* t, int mean) {
+  if (!t || (mean != 0 && mean != 1)) return HPS_EINVAL;
+  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
+  t->mean_pooling = mean != 0;
   return HPS_OK;
 }
 

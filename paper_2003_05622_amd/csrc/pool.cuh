@@ -1,5 +1,7 @@
-// Row gather + per-bag sum pooling: pooled[b, :] = sum over the bag's occurrences
-// of the row of that occurrence's key.  A group of LPR lanes owns one bag at a time;
+// Row gather + per-bag pooling: pooled[b, :] = sum over the bag's occurrences of the
+// row of that occurrence's key (inv_len == null), or their mean (inv_len != null: it
+// also receives 1 / (bag length) per bag, which the push needs to hand every occurrence
+// its share of the bag's gradient).  A group of LPR lanes owns one bag at a time;
 // each lane carries COLS float4 columns (lane*4 + k*LPR*4; COLS = 1 up to dim 256).
 // Eight occurrences are in flight at a time: their ranks, then their row numbers,
 // then their rows.  Block 0 also books the rows the preceding insert created.
@@ -18,7 +20,7 @@ template <int LPR, int COLS>
 __global__ void __launch_bounds__(kPoolThreads)
 pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
           const i32* __restrict__ inverse, const u32* __restrict__ rows,
-          float* __restrict__ pooled) {
+          float* __restrict__ pooled, float* __restrict__ inv_len) {
   const u32 sub = threadIdx.x % LPR;
   if (load_error(t.st) != 0) return;
   if (blockIdx.x == 0 && threadIdx.x < kWave) commit_insert_wave(t.st);
@@ -54,6 +56,12 @@ pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
           acc[c].x += v[k][c].x; acc[c].y += v[k][c].y; acc[c].z += v[k][c].z; acc[c].w += v[k][c].w;
         }
       }
+    }
+    if (inv_len) {
+      const float len = (float)max(hi - lo, 1);
+      if (sub == 0) inv_len[b] = 1.0f / len;
+#pragma unroll
+      for (int c = 0; c < COLS; ++c) { acc[c].x /= len; acc[c].y /= len; acc[c].z /= len; acc[c].w /= len; }
     }
     float4* out = reinterpret_cast<float4*>(pooled + (u64)b * t.dim);
 #pragma unroll

@@ -40,6 +40,7 @@ struct PushArgs {
   const u32* bagperm;
   const u32* rows;
   const float* grads;
+  const float* inv_len;   // != null (mean pooling): per bag, the share of its gradient an occurrence gets
   const PullCtx* ctx;
   const u32* med_list;  // unique indices, kCountShards shards of med_cap entries
   u32 med_cap;
@@ -145,6 +146,9 @@ __device__ __forceinline__ void add_positions(float4* g, const PushArgs& a, u32 
       bag[k] = on[k] ? (a.bagperm[j] & kBagMask) : 0u;
     }
     float4 v[kPushInFlight][COLS];
+    float share[kPushInFlight];
+#pragma unroll
+    for (int k = 0; k < kPushInFlight; ++k) share[k] = (a.inv_len && on[k]) ? a.inv_len[bag[k]] : 1.0f;
 #pragma unroll
     for (int k = 0; k < kPushInFlight; ++k) {
       const float4* row = reinterpret_cast<const float4*>(a.grads + (u64)bag[k] * dim);
@@ -153,6 +157,14 @@ __device__ __forceinline__ void add_positions(float4* g, const PushArgs& a, u32 
         const u32 col = sub + c * LPR;
         v[k][c] = (on[k] && col < dim4) ? row[col] : make_float4(0.f, 0.f, 0.f, 0.f);
       }
+    }
+    if (a.inv_len) {
+#pragma unroll
+      for (int k = 0; k < kPushInFlight; ++k)
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+          v[k][c].x *= share[k]; v[k][c].y *= share[k]; v[k][c].z *= share[k]; v[k][c].w *= share[k];
+        }
     }
 #pragma unroll
     for (int c = 0; c < COLS; ++c) {
