@@ -61,6 +61,12 @@ struct HeavySet {
   // per value of a key's top kHeavyTopBits bits: index of the first heavy key with these
   // top bits (low half) and how many there are (high half)
   u32 span[1 << kHeavyTopBits];
+  // Where that mini-batch's keys lay: its smallest key and the bit length of (largest -
+  // smallest).  Natural buckets divide THIS range evenly (hashed keys fill all 64 bits,
+  // but raw ids may all share their leading bits); also only a hint.
+  u64 range_lo;
+  u32 range_bits;
+  u32 pad2;
 };
 struct HeavyRaw {
   u32 count;

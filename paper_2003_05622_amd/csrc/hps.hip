@@ -405,6 +405,7 @@ static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, P
   a.kind = kind;
   a.ring = nullptr;
   a.ring_slot = 0;
+  a.uniq = t->w<u64>(L.c[c].uniq);
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -515,8 +516,8 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
   // look-back status words and digit histograms start at zero
   fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.bag_of - wl.ghist) / 8, 0);
-  for (u32 k = 0; k < kHeavyRing; ++k)      // no frequent keys known yet: all-ones padding only
-    fill_u64<<<1, 256, 0, s>>>(t->w<HeavyRing>(wl.heavy_raw)->set[k].keys, kMaxHeavy + 1, ~0ull);
+  for (u32 k = 0; k < kHeavyRing; ++k)
+    init_heavy_set<<<1, 256, 0, s>>>(&t->w<HeavyRing>(wl.heavy_raw)->set[k]);
   reset_state<<<1, 64, 0, s>>>(t->view.st);
   for (int k = 0; k < 2; ++k)
     set_ctx_empty<<<1, 64, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
@@ -686,14 +687,15 @@ hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, cons
   if (n) {
     launch_lookup(t, c, n, s);
     commit_absent<<<1, 256, 0, s>>>(t->view.st, t->w<HeavyRing>(t->wl.heavy_raw),
-                                   (u32)(t->lookup_serial % kHeavyRing));
+                                   (u32)(t->lookup_serial % kHeavyRing), t->w<u64>(t->wl.c[c].uniq),
+                                   &t->ctx(c)->n_unique);
     PushArgs a;
     fill_push_args(t, c, d_values, kStepAdd, a);
 #define CALL(LPR) launch_push<LPR>(t, n, a, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
   } else {
-    commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0);
+    commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0, nullptr, nullptr);
   }
   if (!launch_ok()) return HPS_EDEVICE;
   if (hipEventRecord(cx.released, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)

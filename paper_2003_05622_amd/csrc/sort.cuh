@@ -80,7 +80,10 @@ __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
 // bucket.cuh) get buckets of their own, so that every other bucket stays small enough
 // to be sorted inside one workgroup.  With the heavy keys h_0 < h_1 < ... the id of a
 // key is
-//     (key >> nat_shift) + 2 * #{i : h_i < key} + (key is heavy ? 1 : 0),
+//     natural(key) + 2 * #{i : h_i < key} + (key is heavy ? 1 : 0),
+// natural(key) = the leading 64 - nat_shift bits of the key's place in the range the
+// earlier mini-batch's keys spanned (clamped at both ends; for hashed keys simply the key's
+// leading bits),
 // which is monotone in the key; keys share an id only if they share the leading bits
 // and no heavy key lies between them, and a heavy key shares its id with nothing.
 
@@ -89,6 +92,8 @@ __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
 struct HeavyLds {
   u64 keys[kMaxHeavy + 1];
   u32 span[1 << kHeavyTopBits];
+  u64 range_lo;      // see HeavySet
+  u32 range_bits;
   u32 max_heavy;     // only the max_heavy smallest heavy keys get buckets of their own
 };
 
@@ -96,7 +101,11 @@ struct HeavyLds {
 __device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set, u32 max_heavy) {
   for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += blockDim.x) H.keys[i] = set->keys[i];
   for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += blockDim.x) H.span[i] = set->span[i];
-  if (threadIdx.x == 0) H.max_heavy = max_heavy;
+  if (threadIdx.x == 0) {
+    H.max_heavy = max_heavy;
+    H.range_lo = set->range_lo;
+    H.range_bits = min(set->range_bits, 64u);
+  }
 }
 
 // *heavy tells whether the key is one of the heavy keys (that count: see max_heavy;
@@ -108,7 +117,12 @@ __device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, int nat_shi
   while (m < end && H.keys[m] < key) ++m;
   *heavy = m < end && m < H.max_heavy && H.keys[m] == key;
   m = min(m, H.max_heavy);
-  return (u32)(key >> nat_shift) + 2 * m + (*heavy ? 1u : 0u);
+  const int nat_bits = 64 - nat_shift;                       // 1 .. 15
+  const int shift = (int)H.range_bits > nat_bits ? (int)H.range_bits - nat_bits : 0;
+  const u64 rel = key > H.range_lo ? key - H.range_lo : 0;
+  const u64 last = (1ull << nat_bits) - 1;
+  const u32 natural = (u32)min(rel >> shift, last);
+  return natural + 2 * m + (*heavy ? 1u : 0u);
 }
 
 // ---- status words -------------------------------------------------------------------

@@ -426,7 +426,7 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
     one bucket.  Each case must give the oracle's result whichever form runs."""
     rng = np.random.default_rng(21)
     dim, n_bags = 8, 4096
-    gt = hps.HpsTable(600_000, dim, 400_000, n_bags, lr=0.05)
+    gt = hps.HpsTable(1_000_000, dim, 400_000, n_bags, lr=0.05)
     ids = synth.mix64(np.arange(500_000, dtype=np.uint64))
     offsets = None
 
@@ -447,8 +447,12 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         (350_000, [7, 8], [0.3, 0.02]),                # new hot keys without warning
         (350_000, [7, 8, 1], [0.1, 0.1, 0.1]),
         (200_000, [7], [0.9]),                         # one key nearly everything
-        (150_000, [], [], True),                       # consecutive integers: one natural bucket
+        (150_000, [], [], True),                       # consecutive integers: one natural bucket ...
+        (150_000, [], [], True),
+        (200_000, [], [], True),                       # ... until the keys' range is known
+        (200_000, [3], [0.3], True),                   # a hashed hot key far outside that range
         (300_000, [9], [0.001]),                       # back to ordinary
+        (300_000, [9], [0.001]),
     ]
     for case in cases:
         keys = batch(*case)
