@@ -211,16 +211,16 @@ __device__ void slow_sort_region(const u64* skeys, const u64* spay, u64* ka, u64
 constexpr u32 kBorderWindow = kChunkThreads;     // positions per border per round
 
 __device__ __forceinline__ bool is_border(const u64* __restrict__ skeys, u32 p, u32 p0,
-                                          const HeavyLds& hv, int nat_shift) {
+                                          const HeavyLds& hv) {
   bool heavy, heavy_prev;
-  const u32 id = bucket_id(skeys[p], hv, nat_shift, &heavy);
-  const u32 id_prev = bucket_id(skeys[p - 1], hv, nat_shift, &heavy_prev);
+  const u32 id = bucket_id(skeys[p], hv, &heavy);
+  const u32 id_prev = bucket_id(skeys[p - 1], hv, &heavy_prev);
   return id != id_prev || (p == p0 && heavy);
 }
 
 // s_border[0] / [1] (LDS) must hold ~0u for a border still to be found, else its value.
 __device__ void find_borders(const u64* __restrict__ skeys, u32 n, u32 p0_lo, u32 p0_hi,
-                             const HeavyLds& hv, int nat_shift, u32* s_border) {
+                             const HeavyLds& hv, u32* s_border) {
   const u32 half = threadIdx.x / (kChunkThreads / 2);          // which border this thread serves
   const u32 t = threadIdx.x % (kChunkThreads / 2);
   const u32 p0 = half ? p0_hi : p0_lo;
@@ -231,7 +231,7 @@ __device__ void find_borders(const u64* __restrict__ skeys, u32 n, u32 p0_lo, u3
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
         const u32 p = p0 + round * kBorderWindow + k * (kChunkThreads / 2) + t;
-        if (p < n && is_border(skeys, p, p0, hv, nat_shift)) atomicMin(&s_border[half], p);
+        if (p < n && is_border(skeys, p, p0, hv)) atomicMin(&s_border[half], p);
       }
     }
     __syncthreads();
@@ -419,7 +419,7 @@ template <int ITEMS>
 __global__ void __launch_bounds__(kChunkThreads, 4)
 chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
                 u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
-                int nat_shift, u32 max_heavy,
+                u32 max_heavy,
                 const HeavySet* __restrict__ heavy_set, u32* __restrict__ head_rows,
                 u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
                 u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
@@ -432,6 +432,7 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   const u32 tid = threadIdx.x;
   if (tid == 0) L.s_chunk = atomicAdd(ticket, 1u);
   load_heavy(L.hv, heavy_set, max_heavy);
+  if (tid == 0) L.hv.range = ctx->range;
   __syncthreads();
   const u32 chunk = L.s_chunk;
   const u32 n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
@@ -442,7 +443,7 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
     L.s_or = 0;
   }
   __syncthreads();
-  find_borders(skeys, n, chunk * kChunkSpan, (chunk + 1) * kChunkSpan, L.hv, nat_shift, L.s_border);
+  find_borders(skeys, n, chunk * kChunkSpan, (chunk + 1) * kChunkSpan, L.hv, L.s_border);
   const u32 start = L.s_border[0], end = L.s_border[1];
   const u32 cnt = end - start;       // start <= end: both borders come from the same rule
 

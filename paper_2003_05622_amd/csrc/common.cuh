@@ -37,6 +37,19 @@ struct TableState {
   u32 pad2;
 };
 
+// Where a mini-batch's keys lie, estimated from a sample of them (sort_prepare).  The
+// dedup orders keys by rel = clamp(key - lo, 0, span) instead of by the key itself, which
+// is the same order, but raw ids that all share their leading bits spread over the
+// buckets / digits like hashed keys do (sort.cuh: range_rel, natural_bucket).
+struct KeyRange {
+  u64 lo;
+  u64 span;      // largest rel
+  u32 mult;      // bucket form: natural bucket = ((rel >> pre) * mult) >> 32
+  u32 pre;       //   (rel >> pre fits 32 bits)
+  u32 direct;    // bucket form: span is below the number of natural buckets, natural bucket = rel
+  u32 base;      // plain form: the sorted digits start at this bit of rel
+};
+
 // Lives in the workspace; describes the outstanding pull.
 struct PullCtx {
   u32 n_unique;        // U
@@ -47,6 +60,7 @@ struct PullCtx {
   u32 sort_error;      // set if a look-back wait gave up (never expected)
   u32 pad[2];
   u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
+  KeyRange range;                // written by the dedup's first kernel for the later ones
 };
 
 // Keys that make up a large share of a mini-batch (bucket.cuh).  HeavySet: ascending,
@@ -61,12 +75,6 @@ struct HeavySet {
   // per value of a key's top kHeavyTopBits bits: index of the first heavy key with these
   // top bits (low half) and how many there are (high half)
   u32 span[1 << kHeavyTopBits];
-  // Where that mini-batch's keys lay: its smallest key and the bit length of (largest -
-  // smallest).  Natural buckets divide THIS range evenly (hashed keys fill all 64 bits,
-  // but raw ids may all share their leading bits); also only a hint.
-  u64 range_lo;
-  u32 range_bits;
-  u32 pad2;
 };
 struct HeavyRaw {
   u32 count;

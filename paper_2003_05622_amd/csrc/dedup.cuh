@@ -93,7 +93,7 @@ __device__ void wg_sort_range_full(u64* skeys, u64* sidx, u64* kalt, u64* ialt, 
 
 __global__ void __launch_bounds__(kFixThreads)
 fix_mixed_runs(u64* __restrict__ skeys, u64* __restrict__ sidx, u64* __restrict__ kalt,
-               u64* __restrict__ ialt, u32 n, SortPlan plan, const PullCtx* __restrict__ ctx,
+               u64* __restrict__ ialt, u32 n, const PullCtx* __restrict__ ctx,
                const u32* __restrict__ evidence) {
   const u32 E = ctx->n_evidence;
   if (E == 0) return;
@@ -124,17 +124,18 @@ fix_mixed_runs(u64* __restrict__ skeys, u64* __restrict__ sidx, u64* __restrict_
   // same run is dropped (run_lo = run_hi)
   if (tid < E) {
     const u32 j = ev[tid];
-    const u64 v = skeys[j] >> plan.low_shift;
+    const KeyRange range = ctx->range;
+    const u64 v = sorted_prefix(skeys[j], range);
     u32 lo = 0, hi = j;                       // first position with top bits >= v
     while (lo < hi) {
       const u32 mid = lo + (hi - lo) / 2;
-      if ((skeys[mid] >> plan.low_shift) < v) lo = mid + 1; else hi = mid;
+      if (sorted_prefix(skeys[mid], range) < v) lo = mid + 1; else hi = mid;
     }
     const u32 a = lo;
     lo = j; hi = n;                           // first position with top bits > v
     while (lo < hi) {
       const u32 mid = lo + (hi - lo) / 2;
-      if ((skeys[mid] >> plan.low_shift) <= v) lo = mid + 1; else hi = mid;
+      if (sorted_prefix(skeys[mid], range) <= v) lo = mid + 1; else hi = mid;
     }
     const bool first = tid == 0 || ev[tid - 1] < a;
     run_lo[tid] = a;
@@ -172,7 +173,7 @@ fix_mixed_runs(u64* __restrict__ skeys, u64* __restrict__ sidx, u64* __restrict_
 // fix_mixed_runs; returns at once unless there was evidence.
 template <bool REDO>
 __global__ void __launch_bounds__(kHeadThreads)
-unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n, int low_shift,
+unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n,
             u32* __restrict__ head_rows, u32* __restrict__ head_groups, u32 group,
             u32* __restrict__ ticket, u32 epoch,
             u32 n_bags, u64* __restrict__ uniq,
@@ -184,6 +185,7 @@ unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n, 
   __shared__ u64 lds_pay[kHeadTile];
   __shared__ u32 lds_out[kHeadTile];     // the bagperm words going out
   if (REDO && ctx->n_evidence == 0) return;
+  const KeyRange range = ctx->range;
   if (threadIdx.x == 0) s_tile = atomicAdd(ticket, 1u);
   __syncthreads();
   const u32 tile = s_tile;
@@ -216,7 +218,7 @@ unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n, 
     const u32 j = first + k;
     head[k] = (j < n) && (j == 0 || key[k] != prev);
     heads += head[k] ? 1u : 0u;
-    if (!REDO && head[k] && j > 0 && (key[k] >> low_shift) == (prev >> low_shift)) {
+    if (!REDO && head[k] && j > 0 && sorted_prefix(key[k], range) == sorted_prefix(prev, range)) {
       const u32 slot = atomicAdd(&ctx->n_evidence, 1u);
       if (slot < kMaxEvidence) evidence[slot] = j;
     }

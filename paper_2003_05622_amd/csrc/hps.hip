@@ -315,7 +315,7 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
     for (int p = 0; p < plan.n_pass; ++p) {
       u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
       u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
-      const int shift = plan.low_shift + p * kRadixBits;
+      const int shift = p * kRadixBits;     // within the key's sorted prefix
 #define HPS_PASS(FIRST, IDS, KIN, PIN, KOUT, POUT)                                              \
   onesweep_pass<FIRST, IDS><<<n_tiles, kSortThreads, 0, s>>>(                                  \
       KIN, PIN, t->w<i32>(L.bag_of), KOUT, POUT, n, shift, ghist + p * kRadix, tile_rows,      \
@@ -338,7 +338,7 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       const unsigned n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
 #define HPS_CHUNKS(ITEMS)                                                                          \
   chunk_sort_emit<ITEMS><<<n_chunks, kChunkThreads, 0, s>>>(                                       \
-      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, plan.nat_shift,            \
+      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n,                            \
       plan.max_heavy, heavy,                                                                        \
       t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), tile_group(n_chunks), tickets + kMaxPasses, \
       epoch, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm),                 \
@@ -351,12 +351,12 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       const u32 head_group = tile_group(head_tiles);
       u32* evidence = t->w<u32>(L.evidence);
       unique_emit<false><<<head_tiles, kHeadThreads, 0, s>>>(
-          kcur, pcur, n, plan.low_shift, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
+          kcur, pcur, n, t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), head_group,
           tickets + kMaxPasses, epoch, n_bags, t->w<u64>(C.uniq),
           t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
-      fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, pcur, kalt, palt, n, plan, ctx, evidence);
+      fix_mixed_runs<<<1, kFixThreads, 0, s>>>(kcur, pcur, kalt, palt, n, ctx, evidence);
       unique_emit<true><<<head_tiles, kHeadThreads, 0, s>>>(
-          kcur, pcur, n, plan.low_shift, t->w<u32>(L.head_rows) + L.head_tiles,
+          kcur, pcur, n, t->w<u32>(L.head_rows) + L.head_tiles,
           t->w<u32>(L.head_groups) + (L.head_tiles / kMinTileGroup + 1), head_group,
           tickets + kMaxPasses + 1, epoch, n_bags, t->w<u64>(C.uniq),
           t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, evidence, t->view.st);
@@ -405,7 +405,6 @@ static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, P
   a.kind = kind;
   a.ring = nullptr;
   a.ring_slot = 0;
-  a.uniq = t->w<u64>(L.c[c].uniq);
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -687,15 +686,14 @@ hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, cons
   if (n) {
     launch_lookup(t, c, n, s);
     commit_absent<<<1, 256, 0, s>>>(t->view.st, t->w<HeavyRing>(t->wl.heavy_raw),
-                                   (u32)(t->lookup_serial % kHeavyRing), t->w<u64>(t->wl.c[c].uniq),
-                                   &t->ctx(c)->n_unique);
+                                   (u32)(t->lookup_serial % kHeavyRing));
     PushArgs a;
     fill_push_args(t, c, d_values, kStepAdd, a);
 #define CALL(LPR) launch_push<LPR>(t, n, a, s)
     HPS_DISPATCH_LPR(t->lpr, CALL)
 #undef CALL
   } else {
-    commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0, nullptr, nullptr);
+    commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0);
   }
   if (!launch_ok()) return HPS_EDEVICE;
   if (hipEventRecord(cx.released, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)

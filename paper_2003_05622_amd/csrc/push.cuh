@@ -51,7 +51,6 @@ struct PushArgs {
   float lr, eps;
   int kind;   // what a touched row takes: kStepRowwise, kStepElementwise or kStepAdd
   HeavyRing* ring;   // != null: one more block puts the pull's list of frequent keys in order
-  const u64* uniq;   // (the pull's unique keys: that block also notes their range)
   u32 ring_slot;
 };
 
@@ -289,7 +288,7 @@ __global__ void __launch_bounds__(kPushThreads) push_main(TableView t, PushArgs 
     // Not part of the push: the list of frequent keys the pull's lookup left (common.cuh) is
     // put in order here, where it costs nothing -- the next dedup that reads it starts after
     // this push, and the push takes several times longer than this block.
-    finalize_heavy(a.ring, a.ring_slot, a.uniq, a.ctx->n_unique);
+    finalize_heavy(a.ring, a.ring_slot);
     return;
   }
   const u32 role_blocks = a.ring ? gridDim.x - 1 : gridDim.x;

@@ -54,7 +54,11 @@ constexpr int kPrepThreads = 256;
 constexpr int kHistShards = 16;
 constexpr int kHistWords = kHistShards * kMaxPasses * kRadix;   // one pull's histograms
 
-constexpr u32 kSpinLimit = 1u << 22;
+// A wait for another workgroup's status word gives up after this long (100 MHz ticks: one
+// minute).  Nothing legitimate comes near: the slowest producer is a workgroup that sorts
+// one oversized bucket through global memory (bucket.cuh), seconds at the very worst.
+constexpr u64 kWaitTicks = 6000000000ull;
+constexpr u32 kRangeSamples = 2048;    // keys sampled for the key range (sort_prepare)
 constexpr u32 kEpochMod = 4095;        // epochs run 1..4095
 constexpr u32 kMaxTileGroup = 64;      // tiles per group at most (count fits 19 bits)
 constexpr int kLookChunk = 8;          // status rows read per round trip
@@ -64,15 +68,53 @@ static_assert(kRadix == 4 * kWave, "each look-back lane owns four digits");
 
 struct SortPlan {
   int n_pass;       // digits sorted
-  int low_shift;    // plain mode: 64 - 8 * n_pass, position of the least significant sorted digit
+  int low_shift;    // plain mode: 64 - 8 * n_pass: so many low bits stay unsorted if keys fill 64 bits
   u32 group;        // tiles per group
   int by_id;        // 1: the passes sort by the bucket id of the key (see bucket_id) instead
-  int nat_shift;    // by_id: 64 - number of leading key bits that make the natural bucket
+  int nat_shift;    // by_id: 64 - log2 of the number of natural buckets
   u32 max_heavy;    // by_id: heavy keys that get buckets of their own, at most
 };
 
 __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
   return (u32)(k >> shift) & (kRadix - 1);
+}
+
+// ---- key range ------------------------------------------------------------------------
+// A key's place in the range its mini-batch's keys span: monotone in the key, and the
+// same for keys outside the (sampled, slightly widened) range as for the range's ends.
+__device__ __forceinline__ u64 range_rel(u64 key, const KeyRange& r) {
+  const u64 rel = key > r.lo ? key - r.lo : 0;
+  return min(rel, r.span);
+}
+// Plain form: the bits of a key the passes sort by (and which unique_emit compares).
+__device__ __forceinline__ u64 sorted_prefix(u64 key, const KeyRange& r) {
+  return range_rel(key, r) >> r.base;
+}
+// Bucket form: the range cut into 2^nat_bits equal parts.
+__device__ __forceinline__ u32 natural_bucket(u64 key, const KeyRange& r) {
+  const u64 rel = range_rel(key, r);
+  return r.direct ? (u32)rel : (u32)(((rel >> r.pre) * r.mult) >> 32);
+}
+// From the smallest and largest sampled key.  The range is widened by 1/256 of its length
+// at both ends: with kRangeSamples samples of evenly spread keys, the share of keys
+// beyond the widened ends (they all land in the first / last part) is then far below one
+// part's share.
+__device__ __forceinline__ KeyRange make_range(u64 lo, u64 hi, const SortPlan& plan) {
+  const u64 widen = (hi - lo) >> 8;
+  lo = lo > widen ? lo - widen : 0;
+  hi = hi + widen >= hi ? hi + widen : ~0ull;
+  KeyRange r;
+  r.lo = lo;
+  r.span = hi - lo;
+  const u32 bits = r.span ? 64 - __clzll((long long)r.span) : 0;
+  r.pre = bits > 32 ? bits - 32 : 0;
+  const u32 nat_bits = plan.by_id ? 64 - plan.nat_shift : 0;
+  r.direct = (r.span >> nat_bits) == 0;
+  // span >= 2^nat_bits here, so the quotient is below 2^32 and parts are numbered below 2^nat_bits
+  r.mult = r.direct ? 0u : (u32)((1ull << (32 + nat_bits)) / ((r.span >> r.pre) + 1));
+  const u32 sorted_bits = plan.by_id ? 0 : 64 - plan.low_shift;
+  r.base = bits > sorted_bits ? bits - sorted_bits : 0;
+  return r;
 }
 
 // ---- bucket ids ---------------------------------------------------------------------
@@ -81,48 +123,38 @@ __device__ __forceinline__ u32 key_digit(u64 k, int shift) {
 // to be sorted inside one workgroup.  With the heavy keys h_0 < h_1 < ... the id of a
 // key is
 //     natural(key) + 2 * #{i : h_i < key} + (key is heavy ? 1 : 0),
-// natural(key) = the leading 64 - nat_shift bits of the key's place in the range the
-// earlier mini-batch's keys spanned (clamped at both ends; for hashed keys simply the key's
-// leading bits),
-// which is monotone in the key; keys share an id only if they share the leading bits
-// and no heavy key lies between them, and a heavy key shares its id with nothing.
+// natural(key) = which of 2^(64 - nat_shift) equal parts of the mini-batch's key range the
+// key lies in (natural_bucket; for hashed keys: the key's leading bits),
+// which is monotone in the key; keys share an id only if they share the part and no
+// heavy key lies between them, and a heavy key shares its id with nothing.
 
 // The heavy keys in LDS, with their spans per value of the top bits, so that a lookup
 // costs one LDS read unless heavy keys share the key's top bits.
 struct HeavyLds {
   u64 keys[kMaxHeavy + 1];
   u32 span[1 << kHeavyTopBits];
-  u64 range_lo;      // see HeavySet
-  u32 range_bits;
+  KeyRange range;
   u32 max_heavy;     // only the max_heavy smallest heavy keys get buckets of their own
 };
 
-// All threads of the block; the caller's next barrier makes the copy visible.
+// All threads of the block; the caller's next barrier makes the copy visible.  H.range is
+// the caller's to fill.
 __device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set, u32 max_heavy) {
   for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += blockDim.x) H.keys[i] = set->keys[i];
   for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += blockDim.x) H.span[i] = set->span[i];
-  if (threadIdx.x == 0) {
-    H.max_heavy = max_heavy;
-    H.range_lo = set->range_lo;
-    H.range_bits = min(set->range_bits, 64u);
-  }
+  if (threadIdx.x == 0) H.max_heavy = max_heavy;
 }
 
 // *heavy tells whether the key is one of the heavy keys (that count: see max_heavy;
 // limiting them keeps the ids of a small dedup below 256, one pass, and the id monotone).
-__device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, int nat_shift, bool* heavy) {
+__device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, bool* heavy) {
   const u32 sp = H.span[(u32)(key >> (64 - kHeavyTopBits))];
   u32 m = sp & 0xFFFFu;
   const u32 end = m + (sp >> 16);
   while (m < end && H.keys[m] < key) ++m;
   *heavy = m < end && m < H.max_heavy && H.keys[m] == key;
   m = min(m, H.max_heavy);
-  const int nat_bits = 64 - nat_shift;                       // 1 .. 15
-  const int shift = (int)H.range_bits > nat_bits ? (int)H.range_bits - nat_bits : 0;
-  const u64 rel = key > H.range_lo ? key - H.range_lo : 0;
-  const u64 last = (1ull << nat_bits) - 1;
-  const u32 natural = (u32)min(rel >> shift, last);
-  return natural + 2 * m + (*heavy ? 1u : 0u);
+  return natural_bucket(key, H.range) + 2 * m + (*heavy ? 1u : 0u);
 }
 
 // ---- status words -------------------------------------------------------------------
@@ -146,12 +178,28 @@ __device__ __forceinline__ void load_row4(const u32* row, u32 lane, u32* w) {
   w[0] = (u32)a; w[1] = (u32)(a >> 32); w[2] = (u32)b; w[3] = (u32)(b >> 32);
 }
 
+// One more round of a wait for another workgroup: sleeps (longer and longer: hundreds of
+// waves polling in a tight loop take memory bandwidth from the workgroup they wait for)
+// and tells whether to go on.  `spins` and `since` are the wait's state, spins = 0 at first.
+__device__ __forceinline__ bool keep_waiting(u32* spins, u64* since) {
+  const u32 s = (*spins)++;
+  if (s == 0) *since = wall_clock64();
+  if (s < 64) {
+    __builtin_amdgcn_s_sleep(8);
+    return true;
+  }
+  const u32 naps = min((s - 64) / 64 + 1, 32u);      // 127 * 64 cycles each
+  for (u32 k = 0; k < naps; ++k) __builtin_amdgcn_s_sleep(127);
+  return wall_clock64() - *since < kWaitTicks;
+}
+
 // Adds to sum[0..3] this lane's digits of rows [first, last) of `rows` (kRadix words
 // per row), waiting for each row to be published.  Returns false if a wait gave up.
 __device__ __forceinline__ bool sum_rows(const u32* rows, u32 first, u32 last, u32 lane, u32 epoch,
                                          u32* sum) {
   for (u32 r0 = first; r0 < last; r0 += kLookChunk) {
     u32 spins = 0;
+    u64 since = 0;
     while (true) {
       u32 w[kLookChunk][4];
 #pragma unroll
@@ -175,8 +223,7 @@ __device__ __forceinline__ bool sum_rows(const u32* rows, u32 first, u32 last, u
           for (int q = 0; q < 4; ++q) sum[q] += status_count(w[k][q]);
         break;
       }
-      if (++spins > kSpinLimit) return false;   // never expected
-      __builtin_amdgcn_s_sleep(8);
+      if (!keep_waiting(&spins, &since)) return false;   // never expected
     }
   }
   return true;
@@ -190,11 +237,11 @@ __device__ __forceinline__ u32 wave_sum_words(const u32* words, u32 first, u32 l
   u32 c = 0;
   for (u32 r = first + lane; r < last; r += kWave) {
     u32 spins = 0;
+    u64 since = 0;
     while (true) {
       const u32 w = __hip_atomic_load(words + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (status_ready(w, epoch)) { c += status_count(w); break; }
-      if (++spins > kSpinLimit) { *ok = false; break; }   // never expected
-      __builtin_amdgcn_s_sleep(8);
+      if (!keep_waiting(&spins, &since)) { *ok = false; break; }   // never expected
     }
   }
 #pragma unroll
@@ -251,6 +298,8 @@ __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* befo
 //   tickets    [kMaxPasses + 2] tile tickets of the passes and of the two unique scans
 //   id16       by_id plans only: receives every key's bucket id (the first pass reads
 //              it, and hands the id's high byte on to the second inside the payload)
+// Every histogram block first works out the range of the keys from the same kRangeSamples
+// evenly spaced keys (so all agree); block 0 leaves it in ctx->range for the later kernels.
 __global__ void __launch_bounds__(kPrepThreads)
 sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict__ ghist,
              u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx,
@@ -287,6 +336,22 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
   // ---- the first hist_blocks blocks: resets and histograms ----
   __shared__ u32 h[kMaxPasses][kRadix];
   __shared__ HeavyLds hv;
+  __shared__ u64 s_lo[kPrepThreads / kWave], s_hi[kPrepThreads / kWave];
+  {
+    u64 lo = ~0ull, hi = 0;
+    const u32 n_samples = min(n, kRangeSamples);
+    for (u32 j = threadIdx.x; j < n_samples; j += kPrepThreads) {
+      const u64 key = keys[n > kRangeSamples ? (u32)(((u64)j * n) / kRangeSamples) : j];
+      lo = min(lo, key);
+      hi = max(hi, key);
+    }
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      lo = min(lo, (u64)__shfl_xor((unsigned long long)lo, d, kWave));
+      hi = max(hi, (u64)__shfl_xor((unsigned long long)hi, d, kWave));
+    }
+    if (lane_id() == 0) { s_lo[threadIdx.x / kWave] = lo; s_hi[threadIdx.x / kWave] = hi; }
+  }
   if (plan.by_id) load_heavy(hv, heavy_set, plan.max_heavy);
   for (u32 sh = blockIdx.x; sh < (u32)kHistShards; sh += hist_blocks)     // the next pull's counters
     for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads)
@@ -304,6 +369,15 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
     if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
   }
   __syncthreads();
+  if (threadIdx.x == 0) {
+    u64 lo = s_lo[0], hi = s_hi[0];
+    for (int w = 1; w < kPrepThreads / kWave; ++w) { lo = min(lo, s_lo[w]); hi = max(hi, s_hi[w]); }
+    if (lo > hi) lo = hi = 0;            // n == 0
+    hv.range = make_range(lo, hi, plan);
+    if (blockIdx.x == 0) ctx->range = hv.range;
+  }
+  __syncthreads();
+  const KeyRange range = hv.range;
   const u32 n_tiles = (n + kSortTile - 1) / kSortTile;
   for (u32 tile = blockIdx.x; tile < n_tiles; tile += hist_blocks) {
     const u32 base = tile * kSortTile;
@@ -314,13 +388,14 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
         const u64 key = keys[i];
         if (plan.by_id) {
           bool heavy;
-          const u32 id = bucket_id(key, hv, plan.nat_shift, &heavy);
+          const u32 id = bucket_id(key, hv, &heavy);
           id16[i] = (uint16_t)id;         // by_id plans have ids below 2^16: two passes
           for (int p = 0; p < plan.n_pass; ++p)
             atomicAdd(&h[p][(id >> (p * kRadixBits)) & (kRadix - 1)], 1u);
         } else {
+          const u64 prefix = sorted_prefix(key, range);
           for (int p = 0; p < plan.n_pass; ++p)
-            atomicAdd(&h[p][key_digit(key, plan.low_shift + p * kRadixBits)], 1u);
+            atomicAdd(&h[p][key_digit(prefix, p * kRadixBits)], 1u);
         }
       }
     }
@@ -336,7 +411,8 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
 // FIRST: the payload is built from the position and bag_of (read in order).
 // IDS: the passes sort by the 16-bit bucket id instead of key bits: the first by its low
 // byte (read from id16; the high byte goes into bits 24..31 of the payload, which limits
-// such dedups to 2^24 occurrences), the second by that high byte.  `ghist` is this pass's global digit histogram; tile_rows
+// such dedups to 2^24 occurrences), the second by that high byte.  Otherwise the digit is
+// bits shift .. shift + 7 of the key's sorted prefix (sorted_prefix).  `ghist` is this pass's global digit histogram; tile_rows
 // [n_tiles][kRadix] and group_rows [n_groups][kRadix] are this pass's status words.
 template <bool FIRST, bool IDS>
 __global__ void __launch_bounds__(kSortThreads)
@@ -367,6 +443,8 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
   const u32 tile_base = tile * kSortTile;
   const u32 tile_n = min((u32)kSortTile, n - tile_base);
   const u32 wave_base = tile_base + wave * kSortWaveSpan;
+  KeyRange range;
+  if (!IDS) range = ctx->range;
 
   u64 key[kSortItems];
   u64 pay[kSortItems];
@@ -388,7 +466,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
       } else if (IDS) {
         digit[r] = (u32)(pay[r] >> 24) & (kRadix - 1);
       } else {
-        digit[r] = key_digit(key[r], shift);
+        digit[r] = key_digit(sorted_prefix(key[r], range), shift);
       }
     }
 #pragma unroll

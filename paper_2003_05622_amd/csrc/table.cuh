@@ -71,7 +71,7 @@ __device__ __forceinline__ bool acc_is_marked(float stored) {
 
 // Called by all threads of one block (exactly 256) once lookup `slot`'s list of frequent
 // keys is complete: orders it into the ring's set and empties the next list.
-__device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot, const u64* uniq, u32 n_unique) {
+__device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
   constexpr u32 kSize = kMaxHeavy + 1;             // a power of two
   __shared__ u64 sorted[kSize];
   const u32 tid = threadIdx.x;
@@ -117,19 +117,15 @@ __device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot, const 
   for (int e = 0; e < 4; ++e) set.span[4 * tid + e] = first[e] | ((first[e + 1] - first[e]) << 16);
   if (tid == 0) {
     set.count = count;
-    // the range of this mini-batch's keys (uniq is ascending)
-    const u64 lo = n_unique ? uniq[0] : 0, hi = n_unique ? uniq[n_unique - 1] : ~0ull;
-    set.range_lo = lo;
-    set.range_bits = hi > lo ? 64 - __clzll((long long)(hi - lo)) : 0;
     ring->raw[(slot + 1) % kHeavyRing].count = 0;
   }
 }
 
-// No mini-batch seen yet: no heavy keys, keys anywhere in 64 bits.
+// No mini-batch seen yet: no heavy keys.
 __global__ void __launch_bounds__(256) init_heavy_set(HeavySet* set) {
   for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += 256) set->keys[i] = ~0ull;
   for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += 256) set->span[i] = 0;
-  if (threadIdx.x == 0) { set->count = 0; set->range_lo = 0; set->range_bits = 64; }
+  if (threadIdx.x == 0) set->count = 0;
 }
 
 // Bits of a wave-wide ballot that belong to this lane's 8-lane group.
@@ -192,9 +188,8 @@ __global__ void __launch_bounds__(64) commit_insert(TableState* st) { commit_ins
 
 // After a lookup that creates nothing (accumulate): the number of keys not found
 // goes to st->absent, the counters are cleared.
-__global__ void __launch_bounds__(256) commit_absent(TableState* st, HeavyRing* ring, u32 slot,
-                                                     const u64* uniq, const u32* n_unique) {
-  if (ring) finalize_heavy(ring, slot, uniq, *n_unique);
+__global__ void __launch_bounds__(256) commit_absent(TableState* st, HeavyRing* ring, u32 slot) {
+  if (ring) finalize_heavy(ring, slot);
   if (threadIdx.x >= kWave) return;
   const u32 lane = lane_id();
   u32 missing = lane < kCountShards ? st->miss_shard[lane] : 0;
