@@ -23,7 +23,7 @@
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller (for example a
  *     torch tensor's data_ptr()); the library never allocates or frees device
- *     memory.  `storage` holds the table for its whole life, `workspace` holds the
+ *     memory (hps_create takes 64 bytes of pinned host memory, hps_destroy frees them).  `storage` holds the table for its whole life, `workspace` holds the
  *     context of the outstanding pull.  Both must be 256-byte aligned.
  *   - Pointers named h_* are host memory.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
@@ -42,8 +42,11 @@
  *     against the calls that share its buffers with HIP events.
  *   - The key dedup has two forms with identical results; the library picks one per call
  *     from the mini-batch's size and the table's history (its third and later dedups use
- *     the keys that earlier lookups found frequent).  The environment variable HPS_DEDUP,
- *     read by hps_create, pins the form: "radix" or "bucket" (tests, comparison runs).
+ *     the keys that earlier lookups found frequent; the lookups report back, into pinned
+ *     host memory that nobody waits for, when the keys did not suit that form, and the next
+ *     dedups then take the other one: hps_stats().n_plain_fallbacks).  The environment
+ *     variable HPS_DEDUP, read by hps_create, pins the form: "radix" or "bucket" (tests,
+ *     comparison runs).
  */
 #ifndef HPS_H_
 #define HPS_H_
@@ -92,6 +95,8 @@ typedef struct {
   uint64_t last_n_unique;   /* unique keys of the last pull                        */
   uint64_t last_n_inserted; /* keys the last pull (or insert) created              */
   uint64_t last_n_absent;   /* distinct keys the last hps_accumulate did not find  */
+  uint64_t n_plain_fallbacks; /* times the dedup went back to its plain form for a while
+                               because the keys did not suit the bucket form          */
   int32_t error;            /* sticky device status (0 or a negative hps_status)   */
   int32_t pull_outstanding; /* 1 between a pull and its push                       */
 } hps_stats_t;

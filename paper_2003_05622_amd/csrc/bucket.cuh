@@ -352,6 +352,7 @@ __device__ __forceinline__ void slow_region(const u64* skeys, const u64* spay, u
                                          i32* inverse, u32* bagperm, u32* seg_off, PullCtx* ctx,
                                          TableState* st) {
   const u32 tid = threadIdx.x;
+  if (tid == 0) atomicAdd(&ctx->n_slow, end - start);
   const u64 *sk, *sp;
   slow_sort_region(skeys, spay, ka, pa, kb, pb, start, end, slow, &sk, &sp);
   // the element before the region is read from the untouched source

@@ -54,11 +54,12 @@ struct KeyRange {
 struct PullCtx {
   u32 n_unique;        // U
   u32 n_long;          // keys the push handles chunk by chunk
-  u32 reserved0;
+  u32 n_slow;          // bucket form: occurrences in regions that did not fit LDS
   u32 n_chunk_items;   // (key, chunk) work items of the push
   u32 n_evidence;      // sorted positions where a run of equal sorted bits mixes keys
   u32 sort_error;      // set if a look-back wait gave up (never expected)
-  u32 pad[2];
+  u32 n_total;         // occurrences of this dedup
+  u32 by_id;           // 1: this dedup took the bucket form
   u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
   KeyRange range;                // written by the dedup's first kernel for the later ones
 };

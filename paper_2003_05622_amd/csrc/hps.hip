@@ -133,6 +133,7 @@ uint32_t tile_group(uint64_t n_tiles) {
 // Largest dedup the bucket path takes: beyond it a heavy key the hint misses could
 // hold more occurrences than a region has room for.
 constexpr uint64_t kBucketPathMaxKeys = 12ull << 20;
+constexpr uint64_t kPlainHold = 32;      // dedups in the plain form after the bucket form disappointed
 static_assert(kChunkSpan + 2 * kNaturalBucket + kBucketPathMaxKeys / kHeavyShare + 64 <= kChunkThreads * kChunkItems,
               "a region must have room for its span, a natural bucket and one heavy key the hint missed");
 
@@ -203,6 +204,16 @@ struct hps_table {
   uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
   int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
   uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
+  // Pinned host word the lookups report into (table.cuh: OftenLists::report).  When a dedup
+  // of the bucket form had to order much of its input the slow way (keys bunched inside
+  // their range, or frequent keys that change from one mini-batch to the next), the
+  // following dedups take the plain form, which copes with both: for kPlainHold dedups, and
+  // twice as long each time in a row the bucket form then disappoints again.
+  unsigned long long* report;
+  uint32_t report_seen;     // serial of the last report acted on
+  uint32_t strikes;
+  uint64_t plain_until;     // dedups numbered below this take the plain form
+  uint64_t n_fallbacks;     // times plain_until was pushed out
 
   // Pull contexts.  `current` is the context of the outstanding pull (-1: none),
   // `prepared` the one whose dedup has been enqueued but not yet pulled (-1: none).
@@ -293,8 +304,22 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(L.tile_rows), (L.evidence - L.tile_rows) / 8, 0);
     // The bucket path needs to know the heavy keys, which it learns from the lookups: the
     // first two dedups of a table take the plain passes, as do very large ones.
+    if (t->dedup_mode == 0) {
+      const unsigned long long r = __atomic_load_n(t->report, __ATOMIC_RELAXED);
+      const uint32_t serial = (uint32_t)r, flags = (uint32_t)(r >> 32);
+      if (serial != t->report_seen) {
+        t->report_seen = serial;
+        if ((flags & kReportBucket) && (flags & kReportSlow)) {
+          t->plain_until = t->serial + ((uint64_t)kPlainHold << (t->strikes < 7 ? t->strikes : 7));
+          ++t->strikes;
+          ++t->n_fallbacks;
+        } else if (flags & kReportBucket) {
+          t->strikes = 0;
+        }
+      }
+    }
     const bool buckets = n <= kBucketPathMaxKeys && t->dedup_mode != 1 &&
-                         (t->dedup_mode == 2 || t->lookup_serial >= 2);
+                         (t->dedup_mode == 2 || (t->lookup_serial >= 2 && t->serial >= t->plain_until));
     const SortPlan plan = buckets ? bucket_plan(n) : sort_plan(n);
     u64* kcur = t->w<u64>(L.keys_a);
     u64* kalt = t->w<u64>(L.keys_b);
@@ -380,6 +405,8 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
   ++t->lookup_serial;
   often.heavy_raw = &t->w<HeavyRing>(t->wl.heavy_raw)->raw[t->lookup_serial % kHeavyRing];
   often.heavy_min = (u32)(n_keys / kHeavyShare > kHeavyMin ? n_keys / kHeavyShare : kHeavyMin);
+  often.report = t->report;
+  often.serial = (u32)t->lookup_serial;
   const unsigned probe_blocks = grid_for(n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0, &ctx->n_unique,
                                                         t->w<u32>(C.rows), nullptr, nullptr, nullptr,
@@ -505,6 +532,17 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->serial = 0;
   t->mean_pooling = false;
   t->lookup_serial = 0;
+  t->report_seen = 0;
+  t->strikes = 0;
+  t->plain_until = 0;
+  t->n_fallbacks = 0;
+  t->report = nullptr;
+  if (hipHostMalloc(reinterpret_cast<void**>(&t->report), 64, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    hps_destroy(t);
+    return HPS_EDEVICE;
+  }
+  *t->report = 0;
   {
     // HPS_DEDUP=radix / bucket pins the dedup to one of its two forms (comparison runs, tests)
     const char* mode = std::getenv("HPS_DEDUP");
@@ -534,6 +572,7 @@ hps_status hps_destroy(hps_table* t) {
     (void)hipEventDestroy(t->cx[k].ready);
     (void)hipEventDestroy(t->cx[k].released);
   }
+  if (t->report) (void)hipHostFree(t->report);     // waits for the device: no lookup still writes to it
   delete t;
   return HPS_OK;
 }
@@ -783,6 +822,7 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->last_n_unique = ctx.n_unique;
   h_out->last_n_inserted = st.inserted;
   h_out->last_n_absent = (uint64_t)st.absent;
+  h_out->n_plain_fallbacks = t->n_fallbacks;
   h_out->error = st.error;
   h_out->pull_outstanding = t->current >= 0 ? 1 : 0;
   return HPS_OK;

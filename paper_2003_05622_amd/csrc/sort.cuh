@@ -365,6 +365,9 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
       ctx->n_chunk_items = 0;
       ctx->n_evidence = 0;
       ctx->sort_error = 0;
+      ctx->n_slow = 0;
+      ctx->n_total = n;
+      ctx->by_id = (u32)plan.by_id;
     }
     if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
   }

@@ -55,7 +55,14 @@ struct OftenLists {
   uint2* chunk_items;   // (unique index, chunk number)
   HeavyRaw* heavy_raw;  // keys with at least heavy_min occurrences are listed for the next dedup
   u32 heavy_min;
+  // Host memory (or null) that receives serial | flags << 32 about the dedup before this
+  // lookup: kReportBucket = it took the bucket form, kReportSlow = and more than 1/8 of
+  // the occurrences lay in regions that had to be ordered through global memory.  The
+  // host looks at it when it chooses the form of a later dedup, without waiting for it.
+  unsigned long long* report;
+  u32 serial;
 };
+constexpr u32 kReportBucket = 1, kReportSlow = 2;
 
 // "Updated since the last dirty dump" is kept in the sign bit of a row's first
 // accumulator element: accumulators are sums of squares, never negative, so the bit
@@ -165,6 +172,9 @@ __global__ void __launch_bounds__(64) set_ctx_empty(PullCtx* ctx, u32* seg_off) 
     ctx->n_chunk_items = 0;
     ctx->n_evidence = 0;
     ctx->sort_error = 0;
+    ctx->n_slow = 0;
+    ctx->n_total = 0;
+    ctx->by_id = 0;
     seg_off[0] = 0;
   }
   if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
@@ -264,6 +274,12 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   __shared__ u32 s_list[MODE == 0 ? kMissLdsCap : 1];
   __shared__ u32 s_med_list[MODE == 0 ? kMedLdsCap : 1];
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
+  if (MODE == 0 && often.report && blockIdx.x == 0 && threadIdx.x == 0) {
+    const PullCtx* c = often.ctx;
+    const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u);
+    __hip_atomic_store(often.report, (unsigned long long)often.serial | ((unsigned long long)flags << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
   if (MODE == 0 && often.ctx->sort_error != 0) {     // the dedup before this lookup failed
     if (threadIdx.x == 0) raise_error(t.st, kErrInternal);
     return;

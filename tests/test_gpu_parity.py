@@ -422,8 +422,10 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
     """The dedup alone (unique keys and inverse ranks, bit-exact) on mid-sized batches whose
     heavy keys change from batch to batch: the bucket form learns heavy keys from earlier
     lookups, so a key that turns hot without warning makes a region too large for LDS and
-    takes the route through global memory; unhashed, consecutive keys put everything into
-    one bucket.  Each case must give the oracle's result whichever form runs."""
+    takes the route through global memory; unhashed, consecutive keys share all their leading
+    bits (the dedup places keys inside the range a sample of them spans), also together with a
+    hashed key far outside that range.  Each case must give the oracle's result whichever
+    form runs."""
     rng = np.random.default_rng(21)
     dim, n_bags = 8, 4096
     gt = hps.HpsTable(1_000_000, dim, 400_000, n_bags, lr=0.05)
@@ -447,10 +449,10 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         (350_000, [7, 8], [0.3, 0.02]),                # new hot keys without warning
         (350_000, [7, 8, 1], [0.1, 0.1, 0.1]),
         (200_000, [7], [0.9]),                         # one key nearly everything
-        (150_000, [], [], True),                       # consecutive integers: one natural bucket ...
+        (150_000, [], [], True),                       # consecutive integers
         (150_000, [], [], True),
-        (200_000, [], [], True),                       # ... until the keys' range is known
-        (200_000, [3], [0.3], True),                   # a hashed hot key far outside that range
+        (200_000, [], [], True),
+        (200_000, [3], [0.3], True),                   # with a hashed hot key far outside their range
         (300_000, [9], [0.001]),                       # back to ordinary
         (300_000, [9], [0.001]),
     ]
@@ -467,6 +469,35 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         assert np.array_equal(host_keys(uniq)[: ou.size], ou), "unique keys"
         assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
         gt.push(torch.zeros((n_bags, dim), device="cuda"))
+
+
+def test_dedup_keys_bunched_inside_their_range(dedup_form):
+    """Raw ids with a long-tailed distribution: nearly all keys lie in a tiny part of the range
+    the keys span, so equal parts of that range are no use as buckets and the bucket form
+    orders most of the batch through global memory.  Results must be the oracle's in every
+    form; left to itself the library must notice (the lookups report it) and go back to the
+    plain form for a while."""
+    rng = np.random.default_rng(33)
+    dim, n_bags, n = 8, 2048, 200_000
+    gt = hps.HpsTable(1_000_000, dim, n, n_bags, lr=0.05)
+    offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+    for step in range(8):
+        keys = np.minimum(rng.pareto(1.0, size=n) * 1000.0, 5e7).astype(np.uint64) + np.uint64(17)
+        print("bunched keys, step", step, flush=True)
+        gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+        ou, oi = oracle.dedup(keys)
+        uniq, inv = gt.last_unique()
+        st = gt.stats()
+        assert st.error == 0 and st.last_n_unique == ou.size
+        assert np.array_equal(host_keys(uniq)[: ou.size], ou), "unique keys"
+        assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+        gt.push(torch.zeros((n_bags, dim), device="cuda"))
+    torch.cuda.synchronize()
+    fallbacks = gt.stats().n_plain_fallbacks
+    if dedup_form == "auto":
+        assert fallbacks >= 1, "the bucket form was never given up"
+    else:
+        assert fallbacks == 0
 
 
 @pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 2047, 2048, 2049, 4096, 4097, 6143, 6144, 6145,
