@@ -23,7 +23,8 @@
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller (for example a
  *     torch tensor's data_ptr()); the library never allocates or frees device
- *     memory (hps_create takes 64 bytes of pinned host memory, hps_destroy frees them).  `storage` holds the table for its whole life, `workspace` holds the
+ *     memory (hps_create takes 64 bytes of pinned host memory, hps_destroy frees
+ *     them).  `storage` holds the table for its whole life, `workspace` holds the
  *     context of the outstanding pull.  Both must be 256-byte aligned.
  *   - Pointers named h_* are host memory.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
@@ -142,7 +143,8 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
  * Keys not in the table are inserted with their initial row before pooling.
  * n_keys <= max_keys and n_examples * n_slots <= max_bags, else HPS_EINVAL.
  * All buffers must stay valid until the work enqueued here has run; d_keys and
- * d_offsets are not needed by the later push. */
+ * d_offsets are not needed by the later push.  HPS_ESTATE while an earlier pull still
+ * waits for its push: one mini-batch at a time is between pull and push. */
 hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
                     const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
                     float* d_pooled, void* stream);
@@ -161,7 +163,8 @@ hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
 /* The table half of a pull for the prepared mini-batch: makes `stream` wait for the
  * prepare, looks up / inserts the unique keys and pools into d_pooled.  The prepared
  * mini-batch becomes the outstanding pull.  hps_pull(...) is hps_prepare followed by
- * hps_pull_prepared on the same stream.  HPS_ESTATE if nothing is prepared. */
+ * hps_pull_prepared on the same stream.  HPS_ESTATE if nothing is prepared, or while an
+ * earlier pull still waits for its push. */
 hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream);
 
 /* Algorithm 1 push_parameters_updates_back_kernel / Algorithm 2's local accumulate.
@@ -225,7 +228,9 @@ hps_status hps_dump_dirty(hps_table* t, uint64_t* d_keys_out, float* d_weights_o
 /* Waits for the stream and fills *h_out (host). */
 hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
 
-/* Clears the sticky device status. */
+/* Clears the sticky device status and abandons the mini-batch between hps_prepare / a
+ * pull and its push, if there is one: while the status was set its kernels did nothing,
+ * so there is nothing valid to push (a later hps_push returns HPS_ESTATE). */
 hps_status hps_clear_error(hps_table* t, void* stream);
 
 /* Stage timing for measurement.  Stages of one step: */

@@ -120,10 +120,7 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   return L;
 }
 
-// How many 8-bit digits to sort for n occurrences: enough that two different keys
-// rarely agree in all sorted bits.  With b sorted bits about n^2 / 2^(b+1) pairs of
-// distinct hashed keys collide; b >= 2*log2(n) - 2 keeps that near one in a few
-// batches, and every collision is repaired anyway (dedup.cuh).
+// Tiles per look-back group: about the square root of the tile count.
 uint32_t tile_group(uint64_t n_tiles) {
   uint32_t g = kMinTileGroup;
   while (g < kMaxTileGroup && (uint64_t)g * g < n_tiles) ++g;
@@ -160,6 +157,10 @@ SortPlan bucket_plan(uint64_t n) {
   return p;
 }
 
+// Plain form.  How many 8-bit digits to sort for n occurrences: enough that two different
+// keys rarely agree in all sorted bits.  With b sorted bits about n^2 / 2^(b+1) pairs of
+// distinct hashed keys collide; b >= 2*log2(n) - 2 keeps that near one in a few
+// batches, and every collision is repaired anyway (dedup.cuh).
 SortPlan sort_plan(uint64_t n) {
   SortPlan p;
   p.by_id = 0;
@@ -526,7 +527,8 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
                 hipEventCreateWithFlags(&t->cx[k].ready, hipEventDisableTiming) == hipSuccess &&
                 hipEventCreateWithFlags(&t->cx[k].released, hipEventDisableTiming) == hipSuccess;
   }
-  if (!events_ok) { (void)hipGetLastError(); delete t; return HPS_EDEVICE; }
+  t->report = nullptr;
+  if (!events_ok) { (void)hipGetLastError(); hps_destroy(t); return HPS_EDEVICE; }
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
   t->serial = 0;
@@ -558,7 +560,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   reset_state<<<1, 64, 0, s>>>(t->view.st);
   for (int k = 0; k < 2; ++k)
     set_ctx_empty<<<1, 64, 0, s>>>(t->ctx(k), t->w<u32>(wl.c[k].seg_off));
-  if (!launch_ok()) { delete t; return HPS_EDEVICE; }
+  if (!launch_ok()) { hps_destroy(t); return HPS_EDEVICE; }
   *out = t;
   return HPS_OK;
 }
@@ -567,10 +569,11 @@ hps_status hps_destroy(hps_table* t) {
   if (!t) return HPS_EINVAL;
   for (int i = 0; i < HPS_N_STAGES; ++i)
     for (hipEvent_t e : t->ev_pool[i]) (void)hipEventDestroy(e);
-  (void)hipEventDestroy(t->scratch_free);
+  // (a table whose creation failed half way holds null handles)
+  if (t->scratch_free) (void)hipEventDestroy(t->scratch_free);
   for (int k = 0; k < 2; ++k) {
-    (void)hipEventDestroy(t->cx[k].ready);
-    (void)hipEventDestroy(t->cx[k].released);
+    if (t->cx[k].ready) (void)hipEventDestroy(t->cx[k].ready);
+    if (t->cx[k].released) (void)hipEventDestroy(t->cx[k].released);
   }
   if (t->report) (void)hipHostFree(t->report);     // waits for the device: no lookup still writes to it
   delete t;
@@ -596,13 +599,18 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 
+static bool mini_batch_ok(const hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
+                          const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots) {
+  if (!t || !d_offsets || (n_keys && !d_keys)) return false;
+  if (n_keys > t->max_keys || (uint64_t)n_examples * n_slots > t->max_bags) return false;
+  return (uintptr_t)d_keys % 8 == 0 && (uintptr_t)d_offsets % 4 == 0;
+}
+
 hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
                        const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots,
                        void* stream) {
-  if (!t || !d_offsets || (n_keys && !d_keys)) return HPS_EINVAL;
+  if (!mini_batch_ok(t, d_keys, n_keys, d_offsets, n_examples, n_slots)) return HPS_EINVAL;
   const uint64_t n_bags = (uint64_t)n_examples * n_slots;
-  if (n_keys > t->max_keys || n_bags > t->max_bags) return HPS_EINVAL;
-  if ((uintptr_t)d_keys % 8 || (uintptr_t)d_offsets % 4) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int c = t->current == 0 ? 1 : 0;        // the context the outstanding pull does not use
   hps_table::Context& cx = t->cx[c];
@@ -628,7 +636,7 @@ hps_status hps_prepare(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
 
 hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
   if (!t) return HPS_EINVAL;
-  if (t->prepared < 0) return HPS_ESTATE;
+  if (t->prepared < 0 || t->current >= 0) return HPS_ESTATE;
   const int c = t->prepared;
   const hps_table::Context& cx = t->cx[c];
   if (cx.n_bags && !d_pooled) return HPS_EINVAL;
@@ -670,6 +678,8 @@ hps_status hps_pull(hps_table* t, const uint64_t* d_keys, uint64_t n_keys,
                     float* d_pooled, void* stream) {
   if ((uint64_t)n_examples * n_slots && !d_pooled) return HPS_EINVAL;
   if ((uintptr_t)d_pooled % 16) return HPS_EINVAL;
+  if (!mini_batch_ok(t, d_keys, n_keys, d_offsets, n_examples, n_slots)) return HPS_EINVAL;
+  if (t->current >= 0) return HPS_ESTATE;
   const hps_status rc = hps_prepare(t, d_keys, n_keys, d_offsets, n_examples, n_slots, stream);
   return rc != HPS_OK ? rc : hps_pull_prepared(t, d_pooled, stream);
 }
@@ -861,6 +871,9 @@ hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count) {
 hps_status hps_clear_error(hps_table* t, void* stream) {
   if (!t) return HPS_EINVAL;
   clear_error<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(t->view.st);
+  // While the status was set the kernels of a pull did nothing: what its context holds
+  // (row numbers above all) may be an earlier mini-batch's, and a push must not use it.
+  t->current = t->prepared = -1;
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 

@@ -253,6 +253,16 @@ def test_edge_cases():
     with pytest.raises(hps.HpsError) as e:
         gt.push(zero_grads)
     assert e.value.status == hps.ESTATE
+    # a second pull while the first still waits for its push
+    k2 = dev_keys(pre[:8])
+    o2 = torch.from_numpy(np.arange(0, 9, dtype=np.int32)).cuda()
+    gt.pull(k2, o2, 2, 4)
+    with pytest.raises(hps.HpsError) as e:
+        gt.pull(k2, o2, 2, 4)
+    assert e.value.status == hps.ESTATE
+    gt.push(torch.zeros((8, cfg.dim), device="cuda"))
+    ot.pull(pre[:8], np.arange(0, 9, dtype=np.int32))
+    ot.push(np.zeros((8, cfg.dim), dtype=np.float32))
     # get: present and absent keys
     probe = np.concatenate([pre[:10], synth.mix64(np.arange(10**9, 10**9 + 10, dtype=np.uint64))])
     w, a, f = gt.get(dev_keys(probe))
