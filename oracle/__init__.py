@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libhps_oracle.so")
 
 OK, EINVAL, EFULL, ERESERVED, ESTATE = 0, -1, -2, -3, -4
 ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
+ROWS_F32, ROWS_BF16 = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -78,6 +79,10 @@ def lib() -> ctypes.CDLL:
         L.hpo_set_pooling.argtypes = [vp, ctypes.c_int]
         L.hpo_accumulate.restype = i32
         L.hpo_accumulate.argtypes = [vp, vp, u64, vp, vp]
+        L.hpo_set_row_format.restype = i32
+        L.hpo_set_row_format.argtypes = [vp, ctypes.c_int]
+        L.hpo_nearest_bf16.restype = f32
+        L.hpo_nearest_bf16.argtypes = [f32]
         _lib = L
     return _lib
 
@@ -105,6 +110,11 @@ def mix(x: int) -> int:
     return int(lib().hpo_mix(ctypes.c_uint64(x & (2**64 - 1))))
 
 
+def nearest_bf16(x: float) -> float:
+    """The bfloat16 value nearest to the float32 x (ties to even), as a float."""
+    return float(lib().hpo_nearest_bf16(ctypes.c_float(x)))
+
+
 def dedup(keys) -> Tuple[np.ndarray, np.ndarray]:
     """Sorted unique keys and inverse[i] = rank of keys[i]."""
     keys = _keys(keys)
@@ -121,10 +131,11 @@ class OracleTable:
 
     def __init__(self, capacity: int, dim: int, *, opt: int = ADAGRAD_ROWWISE, lr: float = 0.05,
                  eps: float = 1e-8, init_acc: float = 0.1, init_range: float = 0.01,
-                 init_seed: int = 0):
+                 init_seed: int = 0, row_format: int = ROWS_F32):
         self._h = lib().hpo_create(capacity, dim, opt, lr, eps, init_acc, init_range, init_seed)
         if not self._h:
             raise OracleError(EINVAL, "create")
+        _check(lib().hpo_set_row_format(self._h, row_format), "set_row_format")
         self.capacity, self.dim = capacity, dim
         self.acc_len = int(lib().hpo_acc_len(self._h))
         self._n = 0

@@ -24,6 +24,9 @@
 // the stored float32 values and rounded to float32 once, when stored.
 // The row initialiser is defined in float32 (two separately rounded
 // operations), so it has exactly one correct bit pattern.
+// Row format bfloat16 (an extension, not from the paper: its rows are float32): a weight
+// is additionally rounded to the nearest bfloat16 value (ties to even) whenever it is
+// stored, and read back as that value; accumulators stay float32.
 //
 // Build: g++ -O2 -ffp-contract=off -shared -fPIC (see oracle/__init__.py).
 
@@ -40,6 +43,21 @@ constexpr uint64_t kReservedKey = ~uint64_t(0);
 
 enum Status { OK = 0, EINVAL = -1, EFULL = -2, ERESERVED = -3, ESTATE = -4 };
 enum OptKind { ADAGRAD_ROWWISE = 0, ADAGRAD_ELEMENTWISE = 1 };
+enum RowFormat { ROWS_F32 = 0, ROWS_BF16 = 1 };
+
+// The nearest bfloat16 value (1 sign, 8 exponent, 7 fraction bits: the upper half of a
+// float32), ties to even, as a float32.
+float nearest_bf16(float x) {
+  if (std::isnan(x)) return x;
+  uint32_t u;
+  std::memcpy(&u, &x, 4);
+  const uint32_t dropped = u & 0xFFFFu;
+  uint32_t kept = u >> 16;
+  if (dropped > 0x8000u || (dropped == 0x8000u && (kept & 1u))) kept += 1;   // carries into the exponent correctly
+  u = kept << 16;
+  std::memcpy(&x, &u, 4);
+  return x;
+}
 
 // SplitMix64 output function (Steele, Lea, Flood: "Fast splittable
 // pseudorandom number generators", 2014) for the state x.
@@ -57,6 +75,9 @@ struct Table {
   float lr, eps, init_acc, init_range;
   uint64_t init_seed;
   uint32_t acc_len;                       // 1 (row-wise) or dim (element-wise)
+  int row_format = ROWS_F32;
+  // what a weight becomes when it is stored
+  float stored(float x) const { return row_format == ROWS_BF16 ? nearest_bf16(x) : x; }
   std::unordered_map<uint64_t, uint64_t> index;   // key -> row number
   std::vector<uint64_t> row_key;
   std::vector<float> w;                   // [rows, dim]
@@ -97,6 +118,7 @@ uint64_t add_row(Table& t, uint64_t key) {
   t.row_key.push_back(key);
   t.w.resize((r + 1) * t.dim);
   init_weights(t, key, &t.w[r * t.dim]);
+  for (uint32_t j = 0; j < t.dim; ++j) t.w[r * t.dim + j] = t.stored(t.w[r * t.dim + j]);
   t.acc.resize((r + 1) * t.acc_len, t.init_acc);
   t.dirty.resize(r + 1, 0);
   return r;
@@ -138,10 +160,27 @@ void* hpo_create(uint64_t capacity, uint32_t dim, int opt, float lr, float eps, 
 
 void hpo_destroy(void* h) { delete static_cast<Table*>(h); }
 
+// How weights are stored: float32 (0, the default) or bfloat16 (1).  Only while the table
+// is empty.
+int hpo_set_row_format(void* h, int format) {
+  Table& t = *static_cast<Table*>(h);
+  if (format != ROWS_F32 && format != ROWS_BF16) return EINVAL;
+  if (t.size() != 0) return ESTATE;
+  t.row_format = format;
+  return OK;
+}
+
+float hpo_nearest_bf16(float x) { return nearest_bf16(x); }
+
 uint64_t hpo_size(void* h) { return static_cast<Table*>(h)->size(); }
 uint32_t hpo_acc_len(void* h) { return static_cast<Table*>(h)->acc_len; }
 
-void hpo_init_row(void* h, uint64_t key, float* out) { init_weights(*static_cast<Table*>(h), key, out); }
+// The row a new key gets, as the table stores it.
+void hpo_init_row(void* h, uint64_t key, float* out) {
+  const Table& t = *static_cast<Table*>(h);
+  init_weights(t, key, out);
+  for (uint32_t j = 0; j < t.dim; ++j) out[j] = t.stored(out[j]);
+}
 
 // Declares that n further keys are resident with untouched (initial) rows
 // without storing them.  Untouched rows are a pure function of the key, so a
@@ -186,7 +225,7 @@ int hpo_insert(void* h, const uint64_t* keys, uint64_t n, const float* weights, 
       if (!weights) continue;
     }
     if (weights) {
-      std::memcpy(&t.w[r * t.dim], weights + i * t.dim, sizeof(float) * t.dim);
+      for (uint32_t j = 0; j < t.dim; ++j) t.w[r * t.dim + j] = t.stored(weights[i * t.dim + j]);
       for (uint32_t j = 0; j < t.acc_len; ++j)
         t.acc[r * t.acc_len + j] = acc ? acc[i * t.acc_len + j] : t.init_acc;
     }
@@ -318,12 +357,12 @@ int hpo_push(void* h, const float* grads) {
       for (uint32_t j = 0; j < t.dim; ++j) ss += g[j] * g[j];
       const double G = (double)a[0] + ss / (double)t.dim;
       const double denom = std::sqrt(G) + eps;
-      for (uint32_t j = 0; j < t.dim; ++j) w[j] = (float)((double)w[j] - lr * g[j] / denom);
+      for (uint32_t j = 0; j < t.dim; ++j) w[j] = t.stored((float)((double)w[j] - lr * g[j] / denom));
       a[0] = (float)G;
     } else {
       for (uint32_t j = 0; j < t.dim; ++j) {
         const double G = (double)a[j] + g[j] * g[j];
-        w[j] = (float)((double)w[j] - lr * g[j] / (std::sqrt(G) + eps));
+        w[j] = t.stored((float)((double)w[j] - lr * g[j] / (std::sqrt(G) + eps)));
         a[j] = (float)G;
       }
     }
@@ -358,7 +397,7 @@ int hpo_accumulate(void* h, const uint64_t* keys, uint64_t n, const float* value
     auto it = t.index.find(uniq[u]);
     if (it == t.index.end()) { ++absent; continue; }
     float* w = &t.w[it->second * t.dim];
-    for (uint32_t j = 0; j < t.dim; ++j) w[j] = (float)((double)w[j] + sum[u * t.dim + j]);
+    for (uint32_t j = 0; j < t.dim; ++j) w[j] = t.stored((float)((double)w[j] + sum[u * t.dim + j]));
     t.dirty[it->second] = 1;
   }
   if (n_absent) *n_absent = absent;

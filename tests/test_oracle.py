@@ -729,3 +729,78 @@ def test_mean_pooling_closed_forms_and_state():
     t.set_pooling(False)                                   # back to sums
     pooled = t.pull(np.array([3, 3], dtype=np.uint64), np.array([0, 2], np.int32))
     assert np.array_equal(pooled[0], (w[0].astype(np.float64) * 2).astype(np.float32))
+
+
+# ---- rows stored as bfloat16 -------------------------------------------------------------
+
+def _torch_bf16(a):
+    """Round float32 values to bfloat16 and back with torch's conversion (nearest, ties to even)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def test_nearest_bf16_ties_and_against_torch():
+    # bfloat16 keeps 8 significant bits: next to 1.0 the values are 1, 1 + 2^-7, 1 + 2^-6, ...
+    assert oracle.nearest_bf16(1.0) == 1.0
+    assert oracle.nearest_bf16(1.0 + 2.0 ** -8) == 1.0                       # tie -> even (fraction 0)
+    assert oracle.nearest_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6       # tie -> even (fraction 2)
+    assert oracle.nearest_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7   # just above the tie
+    assert oracle.nearest_bf16(-(1.0 + 2.0 ** -8)) == -1.0
+    assert oracle.nearest_bf16(0.0) == 0.0 and oracle.nearest_bf16(2.0 ** -130) == 2.0 ** -130   # subnormal kept
+    assert oracle.nearest_bf16(float(np.float32(1.99999988))) == 2.0         # carry into the exponent
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(0, 1, 50_000), rng.uniform(-0.01, 0.01, 50_000),
+                        rng.normal(0, 1, 20_000) * 10.0 ** rng.integers(-30, 30, 20_000)]).astype(np.float32)
+    bits = rng.integers(0, 2 ** 32, 50_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    x = np.concatenate([x, bits[np.isfinite(bits)]])
+    got = np.array([oracle.nearest_bf16(float(v)) for v in x], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), _torch_bf16(x).view(np.uint32))
+
+
+@pytest.mark.parametrize("opt", [oracle.ADAGRAD_ROWWISE, oracle.ADAGRAD_ELEMENTWISE])
+def test_bf16_rows_whole_step_closed_form(opt):
+    """A table that stores weights as bfloat16: every stored weight is a bfloat16 value; a new
+    row is the float32 initial row rounded; pooling sums the rounded rows; a push computes the
+    float32 table's step from the rounded weights and rounds the result.  All of it written out
+    here with numpy float64 and torch's conversion."""
+    rng = np.random.default_rng(12)
+    d, lr, eps, acc0 = 8, 0.05, 1e-8, 0.1
+    tb = OracleTable(64, d, opt=opt, lr=lr, eps=eps, init_acc=acc0, row_format=oracle.ROWS_BF16)
+    tf = OracleTable(64, d, opt=opt, lr=lr, eps=eps, init_acc=acc0)
+    keys = np.array([7, 9, 7, 11, 9, 7], dtype=np.uint64)
+    offsets = np.array([0, 2, 3, 6], dtype=np.int32)
+    uniq = np.array([7, 9, 11], dtype=np.uint64)
+    w0 = _torch_bf16(np.stack([tf.init_row(int(k)) for k in uniq]))          # rounded float32 init rows
+    assert np.array_equal(np.stack([tb.init_row(int(k)) for k in uniq]), w0)
+    pooled = tb.pull(keys, offsets)
+    inv = np.array([0, 1, 0, 2, 1, 0])
+    want = np.stack([w0[inv[a:b]].astype(np.float64).sum(0) for a, b in zip(offsets[:-1], offsets[1:])])
+    assert np.array_equal(pooled, want.astype(np.float32))
+    grads = rng.normal(0, 0.05, size=(3, d)).astype(np.float32)
+    tb.push(grads)
+    bag = np.array([0, 0, 1, 2, 2, 2])
+    g = np.stack([grads[bag[inv == u]].astype(np.float64).sum(0) for u in range(3)])
+    if opt == oracle.ADAGRAD_ROWWISE:
+        G = np.float64(np.float32(acc0)) + (g ** 2).mean(1, keepdims=True)
+    else:
+        G = np.float64(np.float32(acc0)) + g ** 2
+    step = w0.astype(np.float64) - np.float64(np.float32(lr)) * g / (np.sqrt(G) + np.float64(np.float32(eps)))
+    w, a, f = tb.get(uniq)
+    assert f.all()
+    assert np.array_equal(w, _torch_bf16(step.astype(np.float32)))
+    assert np.array_equal(a, G.astype(np.float32))
+    assert not (w.view(np.uint32) & 0xFFFF).any()                            # bfloat16 values only
+    # accumulate and insert store rounded values too; dump -> insert is the identity
+    tb.accumulate(uniq[:2], np.full((2, d), 1e-3, np.float32))
+    w2, _, _ = tb.get(uniq[:2])
+    assert np.array_equal(w2, _torch_bf16((w[:2].astype(np.float64) + np.float64(np.float32(1e-3))).astype(np.float32)))
+    tb.insert(np.array([100], dtype=np.uint64), np.full((1, d), 0.3, np.float32))
+    assert np.array_equal(tb.get(np.array([100], dtype=np.uint64))[0][0], _torch_bf16(np.full(d, 0.3, np.float32)))
+    k, ww, aa = tb.dump()
+    t2 = OracleTable(64, d, opt=opt, lr=lr, eps=eps, init_acc=acc0, row_format=oracle.ROWS_BF16)
+    t2.insert(k, ww, aa)
+    k2, ww2, aa2 = t2.dump()
+    assert np.array_equal(k, k2) and np.array_equal(ww, ww2) and np.array_equal(aa, aa2)
+    with pytest.raises(OracleError):
+        lib_table = OracleTable(4, 2)
+        lib_table.insert(np.array([1], dtype=np.uint64))
+        oracle._check(oracle.lib().hpo_set_row_format(lib_table._h, oracle.ROWS_BF16), "set_row_format")
