@@ -44,14 +44,15 @@ def measured_traffic(workload, stage):
     return None
 
 
-def stage_bytes(n, u, bags, d):
+def stage_bytes(n, u, bags, d, wb=4):
     """Algorithmic HBM bytes of one step, per stage: what the method itself has to move
-    once, with 4-byte indices and each distinct row crossing HBM once per direction."""
+    once, with 4-byte indices and each distinct row crossing HBM once per direction.
+    wb = bytes per stored weight (4, or 2 for bfloat16 rows)."""
     return {
         "dedup": 8 * n + 4 * n + 8 * u,                     # read keys, write inverse, write uniq
         "lookup": 8 * u + 4 * u,                            # one slot key per unique, row id
-        "pool": 4 * d * u + 4 * n + 4 * bags + 4 * d * bags,  # rows, inverse, offsets, pooled
-        "push": 4 * d * bags + 4 * n + 2 * (4 * d + 4) * u,  # grads, grouping, row+acc r/w
+        "pool": wb * d * u + 4 * n + 4 * bags + 4 * d * bags,  # rows, inverse, offsets, pooled
+        "push": 4 * d * bags + 4 * n + 2 * (wb * d + 4) * u,  # grads, grouping, row+acc r/w
     }
 
 
@@ -88,6 +89,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a counter run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
+    ap.add_argument("--rows", choices=("f32", "bf16"), default="f32",
+                    help="how the table stores weights (the arithmetic is float32 either way)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="time budget of the CPU oracle leg (0 disables it)")
     args = ap.parse_args()
@@ -127,7 +130,8 @@ def main():
     uniques = [int(np.unique(b.keys).shape[0]) for b in host_batches]
     table = hps.HpsTable(cfg.capacity, cfg.dim, n_max, cfg.n_bags, lr=cfg.lr, eps=cfg.eps,
                          init_acc=cfg.init_acc, init_range=cfg.init_range,
-                         init_seed=cfg.init_seed)
+                         init_seed=cfg.init_seed,
+                         row_format=hps.ROWS_BF16 if args.rows == "bf16" else hps.ROWS_F32)
     chunk = 1 << 23
     for lo in range(0, cfg.n_prefill, chunk):
         table.insert(dev_keys(synth.prefill_keys(lo, min(lo + chunk, cfg.n_prefill))))
@@ -192,7 +196,7 @@ def main():
     sum_u = sum(uniques[i] for i in idx)
     sum_n = sum(host_batches[i].n_keys for i in idx)
     mean_n, mean_u = sum_n / args.steps, sum_u / args.steps
-    per_stage = stage_bytes(mean_n, mean_u, cfg.n_bags, cfg.dim)
+    per_stage = stage_bytes(mean_n, mean_u, cfg.n_bags, cfg.dim, 2 if args.rows == "bf16" else 4)
     dom_ms = timed[dominant][0] / max(timed[dominant][1], 1)
     achieved = per_stage[dominant] / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     step_bytes = sum(per_stage.values())
@@ -231,7 +235,8 @@ def main():
         import oracle
         ot = oracle.OracleTable(cfg.capacity, cfg.dim, lr=cfg.lr, eps=cfg.eps,
                                 init_acc=cfg.init_acc, init_range=cfg.init_range,
-                                init_seed=cfg.init_seed)
+                                init_seed=cfg.init_seed,
+                                row_format=oracle.ROWS_BF16 if args.rows == "bf16" else oracle.ROWS_F32)
         ot.declare_resident(cfg.n_prefill)
         spent, done_u, done = 0.0, 0, 0
         for b in host_batches:
@@ -264,7 +269,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "schedule": "serial" if args.serial else "dedup of batch i+1 overlaps push of batch i", "table_keys": int(st.size), "capacity": cfg.capacity,
-                   "dim": cfg.dim, "n_examples": cfg.n_examples, "n_slots": cfg.n_slots,
+                   "rows": args.rows, "dim": cfg.dim, "n_examples": cfg.n_examples, "n_slots": cfg.n_slots,
                    "keys_per_step": round(mean_n, 1), "unique_per_step": round(mean_u, 1),
                    "zipf_s": cfg.zipf_s, "fresh_frac": cfg.fresh_frac,
                    "distinct_batches": n_batches},

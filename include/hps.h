@@ -79,12 +79,23 @@ typedef enum {
   HPS_OPT_ADAGRAD_ELEMENTWISE = 1
 } hps_opt_kind;
 
+/* How the table stores weights.  Not from the paper, whose rows are float32 (Section 6:
+ * 30-60 bytes per parameter); bfloat16 rows halve the bytes per row, so a GPU holds more
+ * of the working set.  Every interface stays float32 (pooled rows, gradients, hps_insert /
+ * hps_get / hps_dump buffers), and so do the accumulators and all arithmetic: a weight is
+ * rounded to the nearest bfloat16 (ties to even) when it is stored, nothing else changes. */
+typedef enum {
+  HPS_ROWS_F32 = 0,
+  HPS_ROWS_BF16 = 1
+} hps_row_format;
+
 typedef struct {
   int32_t kind;       /* hps_opt_kind */
   float lr;
   float eps;
   float init_acc;     /* accumulator value of a newly created row                  */
   float init_range;   /* new weights are uniform on [-init_range, init_range)      */
+  int32_t row_format; /* hps_row_format                                            */
   uint64_t init_seed; /* new row = function of (key, init_seed) only               */
 } hps_optimizer;
 

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lib,
     ADAGRAD_ROWWISE,
     ADAGRAD_ELEMENTWISE,
+    ROWS_F32,
+    ROWS_BF16,
     OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM,
     EXPORTS,
     STAGES,

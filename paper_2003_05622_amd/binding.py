@@ -9,6 +9,7 @@ from .build import ensure_built
 
 OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM = 0, -1, -2, -3, -4, -5, -6
 ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
+ROWS_F32, ROWS_BF16 = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
@@ -22,7 +23,7 @@ STAGES = ("sort", "unique", "lookup", "pool", "push")
 class Optimizer(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("lr", ctypes.c_float), ("eps", ctypes.c_float),
                 ("init_acc", ctypes.c_float), ("init_range", ctypes.c_float),
-                ("init_seed", ctypes.c_uint64)]
+                ("row_format", ctypes.c_int32), ("init_seed", ctypes.c_uint64)]
 
 
 class Stats(ctypes.Structure):
@@ -116,7 +117,7 @@ class HpsTable:
     def __init__(self, capacity: int, dim: int, max_keys: int, max_bags: int, *,
                  opt: int = ADAGRAD_ROWWISE, lr: float = 0.05, eps: float = 1e-8,
                  init_acc: float = 0.1, init_range: float = 0.01, init_seed: int = 0,
-                 device: str = "cuda:0"):
+                 row_format: int = ROWS_F32, device: str = "cuda:0"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("paper_2003_05622_amd needs a GPU: there is no CPU path")
@@ -125,7 +126,7 @@ class HpsTable:
         self.capacity, self.dim, self.max_keys, self.max_bags = capacity, dim, max_keys, max_bags
         self.acc_len = dim if opt == ADAGRAD_ELEMENTWISE else 1
         self.device = torch.device(device)
-        self.opt = Optimizer(opt, lr, eps, init_acc, init_range, init_seed)
+        self.opt = Optimizer(opt, lr, eps, init_acc, init_range, row_format, init_seed)
         sb = L.hps_table_bytes(capacity, dim, ctypes.byref(self.opt))
         wb = L.hps_workspace_bytes(max_keys, max_bags, dim)
         if sb == 0 or wb == 0:

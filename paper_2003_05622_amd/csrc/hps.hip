@@ -39,6 +39,7 @@ uint64_t slots_for(uint64_t capacity) {
 
 bool valid_opt(const hps_optimizer* o) {
   return o && (o->kind == HPS_OPT_ADAGRAD_ROWWISE || o->kind == HPS_OPT_ADAGRAD_ELEMENTWISE) &&
+         (o->row_format == HPS_ROWS_F32 || o->row_format == HPS_ROWS_BF16) &&
          o->init_range >= 0.f && o->eps >= 0.f && o->init_acc >= 0.f;
 }
 
@@ -51,11 +52,11 @@ struct StorageLayout {
   size_t keys, w, acc, state, total;
 };
 
-StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len) {
+StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len, int row_format) {
   StorageLayout L;
   size_t o = 0;
   L.keys = o;  o = align_up(o + n_slots * sizeof(uint64_t));
-  L.w = o;     o = align_up(o + n_slots * (size_t)dim * sizeof(float));
+  L.w = o;     o = align_up(o + n_slots * (size_t)dim * (row_format == HPS_ROWS_BF16 ? 2 : sizeof(float)));
   L.acc = o;   o = align_up(o + n_slots * (size_t)acc_len * sizeof(float));
   L.state = o; o = align_up(o + sizeof(TableState));
   L.total = o;
@@ -464,7 +465,7 @@ const char* hps_strerror(hps_status s) {
 size_t hps_table_bytes(uint64_t capacity_keys, uint32_t dim, const hps_optimizer* opt) {
   if (!valid_opt(opt) || !valid_shape(capacity_keys, dim)) return 0;
   const uint32_t acc_len = opt->kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? dim : 1;
-  return storage_layout(slots_for(capacity_keys), dim, acc_len).total;
+  return storage_layout(slots_for(capacity_keys), dim, acc_len, opt->row_format).total;
 }
 
 size_t hps_workspace_bytes(uint64_t max_keys, uint64_t max_bags, uint32_t dim) {
@@ -485,7 +486,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   if (max_keys >= (1ull << 30) || max_bags >= (1ull << 31)) return HPS_EINVAL;
   const uint32_t acc_len = opt->kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? dim : 1;
   const uint64_t n_slots = slots_for(capacity_keys);
-  const StorageLayout sl = storage_layout(n_slots, dim, acc_len);
+  const StorageLayout sl = storage_layout(n_slots, dim, acc_len, opt->row_format);
   const WorkspaceLayout wl = workspace_layout(max_keys, max_bags, dim);
   if (storage_bytes < sl.total || workspace_bytes < wl.total) return HPS_ENOMEM;
   int dev = -1;
@@ -512,6 +513,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->view.init_acc = opt->init_acc;
   t->view.init_range = opt->init_range;
   t->view.init_seed = opt->init_seed;
+  t->view.bf16 = opt->row_format == HPS_ROWS_BF16 ? 1u : 0u;
   t->ws = static_cast<char*>(d_workspace);
   t->wl = wl;
   t->lpr = lanes_per_row(dim);

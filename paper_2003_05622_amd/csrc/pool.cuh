@@ -16,14 +16,12 @@ constexpr int kPoolThreads = 256;
 constexpr int kPoolMaxBlocks = 1024;   // the groups loop over the bags
 constexpr int kPoolInFlight = 8;
 
-template <int LPR, int COLS>
-__global__ void __launch_bounds__(kPoolThreads)
-pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
-          const i32* __restrict__ inverse, const u32* __restrict__ rows,
-          float* __restrict__ pooled, float* __restrict__ inv_len) {
+template <int LPR, int COLS, bool BF16>
+__device__ __forceinline__ void pool_bags_as(const TableView& t, const i32* __restrict__ offsets,
+                                             u32 n_bags, u32 n, const i32* __restrict__ inverse,
+                                             const u32* __restrict__ rows, float* __restrict__ pooled,
+                                             float* __restrict__ inv_len) {
   const u32 sub = threadIdx.x % LPR;
-  if (load_error(t.st) != 0) return;
-  if (blockIdx.x == 0 && threadIdx.x < kWave) commit_insert_wave(t.st);
   const u32 dim4 = t.dim >> 2;
   const u32 n_groups = gridDim.x * (kPoolThreads / LPR);
   for (u32 b = (blockIdx.x * kPoolThreads + threadIdx.x) / LPR; b < n_bags; b += n_groups) {
@@ -38,16 +36,22 @@ pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
       for (int k = 0; k < kPoolInFlight; ++k) r[k] = i0 + k < hi ? (u32)inverse[i0 + k] : 0u;
 #pragma unroll
       for (int k = 0; k < kPoolInFlight; ++k) r[k] = i0 + k < hi ? rows[r[k]] : kNoRow;
-      float4 v[kPoolInFlight][COLS];
+      // the rows as stored (all loads first: nothing between them that needs their data) ...
+      StoredW4<BF16> raw[kPoolInFlight][COLS];
 #pragma unroll
       for (int k = 0; k < kPoolInFlight; ++k) {
-        const float4* row = reinterpret_cast<const float4*>(t.w + (u64)(r[k] == kNoRow ? 0u : r[k]) * t.dim);
 #pragma unroll
         for (int c = 0; c < COLS; ++c) {
           const u32 col = sub + c * LPR;
-          v[k][c] = (r[k] != kNoRow && col < dim4) ? row[col] : make_float4(0.f, 0.f, 0.f, 0.f);
+          raw[k][c] = (r[k] != kNoRow && col < dim4) ? load_stored_w4<BF16>(t, r[k], col) : StoredW4<BF16>();
         }
       }
+      // ... then as float32 (all-zero bits are 0.0 in both formats)
+      float4 v[kPoolInFlight][COLS];
+#pragma unroll
+      for (int k = 0; k < kPoolInFlight; ++k)
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) v[k][c] = raw[k][c].value();
       // one occurrence after the other, as a plain loop would add them
 #pragma unroll
       for (int k = 0; k < kPoolInFlight; ++k) {
@@ -70,6 +74,17 @@ pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
       if (col < dim4) out[col] = acc[c];
     }
   }
+}
+
+template <int LPR, int COLS>
+__global__ void __launch_bounds__(kPoolThreads)
+pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
+          const i32* __restrict__ inverse, const u32* __restrict__ rows,
+          float* __restrict__ pooled, float* __restrict__ inv_len) {
+  if (load_error(t.st) != 0) return;
+  if (blockIdx.x == 0 && threadIdx.x < kWave) commit_insert_wave(t.st);
+  if (t.bf16) pool_bags_as<LPR, COLS, true>(t, offsets, n_bags, n, inverse, rows, pooled, inv_len);
+  else pool_bags_as<LPR, COLS, false>(t, offsets, n_bags, n, inverse, rows, pooled, inv_len);
 }
 
 }  // namespace hps

@@ -60,15 +60,14 @@ template <int LPR, int COLS>
 __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const float4* g, u32 sub,
                                             float lr, float eps, int kind) {
   const u32 dim4 = t.dim >> 2;
-  float4* w = reinterpret_cast<float4*>(t.w + (u64)r * t.dim);
   if (kind == kStepAdd) {
 #pragma unroll
     for (int c = 0; c < COLS; ++c) {
       const u32 col = sub + c * LPR;
       if (col < dim4) {
-        float4 v = w[col];
+        float4 v = load_w4(t, r, col);
         v.x += g[c].x; v.y += g[c].y; v.z += g[c].z; v.w += g[c].w;
-        w[col] = v;
+        store_w4(t, r, col, v);
       }
     }
     if (sub == 0) {
@@ -89,9 +88,9 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
     for (int c = 0; c < COLS; ++c) {
       const u32 col = sub + c * LPR;
       if (col < dim4) {
-        float4 v = w[col];
+        float4 v = load_w4(t, r, col);
         v.x -= scale * g[c].x; v.y -= scale * g[c].y; v.z -= scale * g[c].z; v.w -= scale * g[c].w;
-        w[col] = v;
+        store_w4(t, r, col, v);
       }
     }
     if (sub == 0) *G = acc_marked(Gn);
@@ -101,7 +100,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
     for (int c = 0; c < COLS; ++c) {
       const u32 col = sub + c * LPR;
       if (col < dim4) {
-        float4 a = G[col], v = w[col];
+        float4 a = G[col], v = load_w4(t, r, col);
         a.x = acc_value(a.x) + g[c].x * g[c].x; a.y += g[c].y * g[c].y; a.z += g[c].z * g[c].z; a.w += g[c].w * g[c].w;
         v.x -= lr * g[c].x / (sqrtf(a.x) + eps);
         v.y -= lr * g[c].y / (sqrtf(a.y) + eps);
@@ -109,7 +108,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
         v.w -= lr * g[c].w / (sqrtf(a.w) + eps);
         if (col == 0) a.x = acc_marked(a.x);
         G[col] = a;
-        w[col] = v;
+        store_w4(t, r, col, v);
       }
     }
   }

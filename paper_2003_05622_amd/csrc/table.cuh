@@ -31,7 +31,65 @@ struct TableView {
   float init_acc;
   float init_range;
   u64 init_seed;
+  u32 bf16;         // 1: w holds bfloat16 values (2 bytes each) instead of float32
 };
+
+// ---- weights as stored --------------------------------------------------------------
+// Rows hold float32 or bfloat16 values (the upper half of a float32; stored with
+// round-to-nearest, ties to even); all arithmetic is float32 either way.
+__device__ __forceinline__ float bf16_value(u32 h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ u32 bf16_nearest(float f) {
+  const u32 u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;     // NaN stays NaN
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+// Element j of row `row`.
+__device__ __forceinline__ float load_w(const TableView& t, u64 row, u32 j) {
+  if (t.bf16) return bf16_value(reinterpret_cast<const unsigned short*>(t.w)[row * t.dim + j]);
+  return t.w[row * t.dim + j];
+}
+__device__ __forceinline__ void store_w(const TableView& t, u64 row, u32 j, float v) {
+  if (t.bf16) reinterpret_cast<unsigned short*>(t.w)[row * t.dim + j] = (unsigned short)bf16_nearest(v);
+  else t.w[row * t.dim + j] = v;
+}
+// Elements 4*col4 .. 4*col4+3 of row `row` (dim is a multiple of 4: one 16- or 8-byte access).
+// Loops that keep several loads in flight take the format as a template argument and
+// separate the load from the conversion (a test of t.bf16, or a conversion, between the
+// loads makes the compiler wait for each load before it issues the next).
+template <bool BF16> struct StoredW4;
+template <> struct StoredW4<false> {
+  float4 raw = make_float4(0.f, 0.f, 0.f, 0.f);
+  __device__ __forceinline__ float4 value() const { return raw; }
+};
+template <> struct StoredW4<true> {
+  uint2 raw = make_uint2(0u, 0u);
+  __device__ __forceinline__ float4 value() const {
+    return make_float4(bf16_value(raw.x & 0xFFFFu), bf16_value(raw.x >> 16), bf16_value(raw.y & 0xFFFFu),
+                       bf16_value(raw.y >> 16));
+  }
+};
+template <bool BF16>
+__device__ __forceinline__ StoredW4<BF16> load_stored_w4(const TableView& t, u64 row, u32 col4) {
+  const u64 at = row * (t.dim >> 2) + col4;
+  StoredW4<BF16> s;
+  s.raw = reinterpret_cast<const decltype(s.raw)*>(t.w)[at];
+  return s;
+}
+template <bool BF16>
+__device__ __forceinline__ float4 load_w4_as(const TableView& t, u64 row, u32 col4) {
+  return load_stored_w4<BF16>(t, row, col4).value();
+}
+__device__ __forceinline__ float4 load_w4(const TableView& t, u64 row, u32 col4) {
+  return t.bf16 ? load_w4_as<true>(t, row, col4) : load_w4_as<false>(t, row, col4);
+}
+__device__ __forceinline__ void store_w4(const TableView& t, u64 row, u32 col4, float4 v) {
+  const u64 at = row * (t.dim >> 2) + col4;
+  if (t.bf16)
+    reinterpret_cast<uint2*>(t.w)[at] = make_uint2(bf16_nearest(v.x) | (bf16_nearest(v.y) << 16),
+                                                   bf16_nearest(v.z) | (bf16_nearest(v.w) << 16));
+  else
+    reinterpret_cast<float4*>(t.w)[at] = v;
+}
 
 constexpr int kProbeThreads = 256;
 constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
@@ -345,8 +403,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         }
       }
       if (MODE == 2 && row != kNoRow) {
-        float* wr = t.w + (u64)row * t.dim;
-        for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
+        for (u32 j = sub; j < t.dim; j += 8) store_w(t, row, j, w_in[u * t.dim + j]);
         float* ar = t.acc + (u64)row * t.acc_len;
         for (u32 j = sub; j < t.acc_len; j += 8)
           ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
@@ -354,8 +411,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
       if (MODE == 3) {
         if (sub == 0) found_out[u] = row != kNoRow;
         if (row != kNoRow) {
-          const float* wr = t.w + (u64)row * t.dim;
-          for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = wr[j];
+          for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = load_w(t, row, j);
           const float* ar = t.acc + (u64)row * t.acc_len;
           for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = acc_value(ar[j]);
         }
@@ -446,15 +502,14 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
     if (rows && sub == 0) rows[u] = row;
     if (!created) continue;
     ++made;
-    float* wr = t.w + (u64)row * t.dim;
     float* ar = t.acc + (u64)row * t.acc_len;
     if (w_in) {
-      for (u32 j = sub; j < t.dim; j += 8) wr[j] = w_in[u * t.dim + j];
+      for (u32 j = sub; j < t.dim; j += 8) store_w(t, row, j, w_in[u * t.dim + j]);
       for (u32 j = sub; j < t.acc_len; j += 8)
         ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
     } else {
       const u64 base = mix64(key ^ t.init_seed);
-      for (u32 j = sub; j < t.dim; j += 8) wr[j] = init_weight(base, j, t.init_range);
+      for (u32 j = sub; j < t.dim; j += 8) store_w(t, row, j, init_weight(base, j, t.init_range));
       for (u32 j = sub; j < t.acc_len; j += 8) ar[j] = t.init_acc;
     }
   }
@@ -487,7 +542,7 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
       const u64 o = s_base + before;
       if (o < max_rows) {
         keys_out[o] = key;
-        for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = t.w[s * t.dim + j];
+        for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = load_w(t, s, j);
         for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = acc_value(t.acc[s * t.acc_len + j]);
         if (DIRTY) t.acc[s * t.acc_len] = acc_value(t.acc[s * t.acc_len]);
       }

@@ -32,8 +32,8 @@ def test_strerror():
     assert len(seen) == 7 and all(seen)
 
 
-def _opt(kind=0, rng=0.01, eps=1e-8):
-    return hps.Optimizer(kind, 0.05, eps, 0.1, rng, 0)
+def _opt(kind=0, rng=0.01, eps=1e-8, row_format=0):
+    return hps.Optimizer(kind, 0.05, eps, 0.1, rng, row_format, 0)
 
 
 def test_buffer_sizes():
@@ -49,8 +49,12 @@ def test_buffer_sizes():
     assert L.hps_table_bytes(100, 2048, ctypes.byref(o)) == 0
     assert L.hps_table_bytes(1 << 32, 16, ctypes.byref(o)) == 0       # slot index would overflow
     assert L.hps_table_bytes(100, 16, None) == 0
-    bad = hps.Optimizer(7, 0.05, 1e-8, 0.1, 0.01, 0)
+    bad = hps.Optimizer(7, 0.05, 1e-8, 0.1, 0.01, 0, 0)
     assert L.hps_table_bytes(100, 16, ctypes.byref(bad)) == 0
+    # bfloat16 rows: (1e9 / 0.7) slots x (8 + 32 + 4) bytes ~ 62.9 GB
+    h = _opt(row_format=hps.ROWS_BF16)
+    assert 62.8e9 < L.hps_table_bytes(10**9, 16, ctypes.byref(h)) < 63.0e9
+    assert L.hps_table_bytes(100, 16, ctypes.byref(_opt(row_format=5))) == 0
     assert L.hps_workspace_bytes(1 << 31, 10, 16) == 0
     w1 = L.hps_workspace_bytes(1 << 20, 1 << 18, 16)
     w2 = L.hps_workspace_bytes(1 << 21, 1 << 18, 16)

@@ -69,9 +69,9 @@ def ot_init_acc(ot):
     return ot._init_acc
 
 
-def make_pair(cfg, max_keys, opt=hps.ADAGRAD_ROWWISE):
+def make_pair(cfg, max_keys, opt=hps.ADAGRAD_ROWWISE, row_format=hps.ROWS_F32):
     kw = dict(lr=cfg.lr, eps=cfg.eps, init_acc=cfg.init_acc, init_range=cfg.init_range,
-              init_seed=cfg.init_seed)
+              init_seed=cfg.init_seed, row_format=row_format)
     gt = hps.HpsTable(cfg.capacity, cfg.dim, max_keys, cfg.n_bags, opt=opt, **kw)
     ot = OracleTable(cfg.capacity, cfg.dim, opt=opt, **kw)
     ot._init_acc = cfg.init_acc
@@ -128,6 +128,78 @@ def test_scaled_configs(name, n_prefill, n_examples, n_slots):
     cfg = synth.scaled(synth.CONFIGS[name], n_prefill=n_prefill, n_examples=n_examples,
                        n_slots=n_slots, steps=4)
     run_steps(cfg, steps=4)
+
+
+@pytest.mark.parametrize("opt", [hps.ADAGRAD_ROWWISE, hps.ADAGRAD_ELEMENTWISE])
+@pytest.mark.parametrize("name,n_prefill,n_examples,n_slots", [
+    ("mid", 60_000, 96, 50),               # dim 16: 8-byte accesses per lane
+    ("skewed", 40_000, 128, 32),           # dim 64, hot keys with long segments
+])
+def test_bf16_rows(name, n_prefill, n_examples, n_slots, opt):
+    """Weights stored as bfloat16.  What is exact stays exact: key sets, sizes, unique keys,
+    rows that were only initialised (the float32 initial row rounded to nearest even), and
+    the first pull's pooled rows to the float32 tolerance.  A stored weight is the float32
+    result rounded, and the two sides' float32 results differ in their last bits, so now and
+    then one lands on the other side of a rounding boundary: after the first push nearly all
+    weights are bit-identical and the rest are one bfloat16 step apart (2^-7 relative at
+    most); a step does not depend on the weight it is applied to, so over a few more steps
+    such differences neither heal nor grow beyond a step or two."""
+    cfg = synth.scaled(synth.CONFIGS[name], n_prefill=n_prefill, n_examples=n_examples,
+                       n_slots=n_slots, steps=4)
+    stream = synth.BatchStream(cfg)
+    mean_bag = cfg.bag_mean if cfg.bag_kind == "poisson" else cfg.bag_hi
+    gt, ot = make_pair(cfg, int(cfg.n_bags * mean_bag * 1.5) + 4096, opt, hps.ROWS_BF16)
+    pre = synth.prefill_keys(0, cfg.n_prefill)
+    gt.insert(dev_keys(pre))
+    ot.insert(pre)
+
+    def dumps():
+        k, w, a = gt.dump()
+        k, w, a = host_keys(k), w.cpu().numpy(), a.cpu().numpy()
+        order = np.argsort(k, kind="stable")
+        ok, ow, oa = ot.dump()
+        assert np.array_equal(k[order], ok), "key sets differ"
+        assert not (w.view(np.uint32) & 0xFFFF).any(), "a stored weight is not a bfloat16 value"
+        return ok, w[order], a[order], ow, oa
+
+    _, w, a, ow, oa = dumps()
+    assert np.array_equal(w.view(np.uint32), ow.view(np.uint32)), "initial rows"
+    touched = np.zeros(0, dtype=np.uint64)
+    for step in range(4):
+        b = stream.next()
+        touched = np.union1d(touched, b.keys)
+        pooled = gt.pull(dev_keys(b.keys), torch.from_numpy(b.offsets).cuda(), cfg.n_examples, cfg.n_slots)
+        want = ot.pull(b.keys, b.offsets)
+        uniq, inv = gt.last_unique()
+        ou, oi = ot.last_unique()
+        assert np.array_equal(host_keys(uniq), ou) and np.array_equal(inv.cpu().numpy(), oi)
+        assert gt.stats().last_n_inserted == ot.n_inserted
+        if step == 0:
+            assert_close(pooled.cpu().numpy(), want, "pooled, first pull")
+        gt.push(torch.from_numpy(b.grads).cuda())
+        ot.push(b.grads)
+        k, w, a, ow, oa = dumps()
+        assert_close(a, oa, "accumulators step %d" % step)
+        same = w.view(np.uint32) == ow.view(np.uint32)
+        steps_apart = 1 if step == 0 else 2
+        err = np.abs(w.astype(np.float64) - ow) - steps_apart * 2.0 ** -7 * np.abs(ow) - 1e-30
+        assert err.max() <= 0, "weights more than %d bfloat16 step(s) apart" % steps_apart
+        assert same.mean() > 0.999, "too many weights differ: %g" % (1 - same.mean())
+        rows_untouched = ~np.isin(k, touched)
+        assert same[rows_untouched].all(), "rows that were only initialised must be bit-identical"
+    assert gt.stats().size == ot.size and gt.stats().error == 0
+    # get returns what is stored; dump -> insert into a fresh table is the identity
+    probe = k[:: max(1, k.size // 500)]
+    gw, ga, gf = gt.get(dev_keys(probe))
+    assert gf.all() and np.array_equal(gw.cpu().numpy(), w[:: max(1, k.size // 500)])
+    g2, _ = make_pair(cfg, 1024, opt, hps.ROWS_BF16)
+    kk, ww, aa = gt.dump()
+    g2.insert(kk, ww, aa)
+    k2, w2, a2 = g2.dump()
+    o1, o2 = np.argsort(host_keys(kk), kind="stable"), np.argsort(host_keys(k2), kind="stable")
+    assert np.array_equal(host_keys(kk)[o1], host_keys(k2)[o2])
+    assert torch.equal(ww[torch.from_numpy(o1).cuda()], w2[torch.from_numpy(o2).cuda()])
+    assert torch.equal(aa[torch.from_numpy(o1).cuda()], a2[torch.from_numpy(o2).cuda()])
 
 
 def test_elementwise_adagrad():
