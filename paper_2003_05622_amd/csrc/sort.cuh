@@ -299,7 +299,7 @@ __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* befo
 //   id16       by_id plans only: receives every key's bucket id (the first pass reads
 //              it, and hands the id's high byte on to the second inside the payload)
 // Every histogram block first works out the range of the keys from the same kRangeSamples
-// evenly spaced keys (so all agree); block 0 leaves it in ctx->range for the later kernels.
+// sampled keys (so all agree); block 0 leaves it in ctx->range for the later kernels.
 __global__ void __launch_bounds__(kPrepThreads)
 sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict__ ghist,
              u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx,
@@ -337,11 +337,27 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
   __shared__ u32 h[kMaxPasses][kRadix];
   __shared__ HeavyLds hv;
   __shared__ u64 s_lo[kPrepThreads / kWave], s_hi[kPrepThreads / kWave];
+  // The block's first tile is requested before anything waits for the samples, so that the
+  // two round trips to memory overlap (hist_blocks <= number of tiles: every block has one).
+  constexpr int kPrepItems = kSortTile / kPrepThreads;
+  u64 first_keys[kPrepItems];
+#pragma unroll
+  for (int k = 0; k < kPrepItems; ++k) {
+    const u32 i = blockIdx.x * kSortTile + k * kPrepThreads + threadIdx.x;
+    first_keys[k] = i < n ? keys[i] : 0;
+  }
   {
     u64 lo = ~0ull, hi = 0;
     const u32 n_samples = min(n, kRangeSamples);
+    // kRangeSamples / 8 evenly spaced runs of 8 consecutive keys (a 64-byte line each, the
+    // first and the last included), so that a wave's request is 8 lines and not 64: every
+    // block asks for the same lines, and the caches serve requests, not bytes.
+    const u32 n_lines = n >> 3;
     for (u32 j = threadIdx.x; j < n_samples; j += kPrepThreads) {
-      const u64 key = keys[n > kRangeSamples ? (u32)(((u64)j * n) / kRangeSamples) : j];
+      const u32 at = n > kRangeSamples
+                         ? (u32)(((u64)(j >> 3) * (n_lines - 1)) / (kRangeSamples / 8 - 1)) * 8 + (j & 7)
+                         : j;
+      const u64 key = keys[at];
       lo = min(lo, key);
       hi = max(hi, key);
     }
@@ -382,25 +398,30 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
   __syncthreads();
   const KeyRange range = hv.range;
   const u32 n_tiles = (n + kSortTile - 1) / kSortTile;
-  for (u32 tile = blockIdx.x; tile < n_tiles; tile += hist_blocks) {
+  auto count_key = [&](u32 i, u64 key) {
+    if (plan.by_id) {
+      bool heavy;
+      const u32 id = bucket_id(key, hv, &heavy);
+      id16[i] = (uint16_t)id;         // by_id plans have ids below 2^16: two passes
+      for (int p = 0; p < plan.n_pass; ++p)
+        atomicAdd(&h[p][(id >> (p * kRadixBits)) & (kRadix - 1)], 1u);
+    } else {
+      const u64 prefix = sorted_prefix(key, range);
+      for (int p = 0; p < plan.n_pass; ++p)
+        atomicAdd(&h[p][key_digit(prefix, p * kRadixBits)], 1u);
+    }
+  };
+#pragma unroll
+  for (int k = 0; k < kPrepItems; ++k) {
+    const u32 i = blockIdx.x * kSortTile + k * kPrepThreads + threadIdx.x;
+    if (i < n) count_key(i, first_keys[k]);
+  }
+  for (u32 tile = blockIdx.x + hist_blocks; tile < n_tiles; tile += hist_blocks) {
     const u32 base = tile * kSortTile;
 #pragma unroll 4
-    for (int k = 0; k < kSortTile / kPrepThreads; ++k) {
+    for (int k = 0; k < kPrepItems; ++k) {
       const u32 i = base + k * kPrepThreads + threadIdx.x;
-      if (i < n) {
-        const u64 key = keys[i];
-        if (plan.by_id) {
-          bool heavy;
-          const u32 id = bucket_id(key, hv, &heavy);
-          id16[i] = (uint16_t)id;         // by_id plans have ids below 2^16: two passes
-          for (int p = 0; p < plan.n_pass; ++p)
-            atomicAdd(&h[p][(id >> (p * kRadixBits)) & (kRadix - 1)], 1u);
-        } else {
-          const u64 prefix = sorted_prefix(key, range);
-          for (int p = 0; p < plan.n_pass; ++p)
-            atomicAdd(&h[p][key_digit(prefix, p * kRadixBits)], 1u);
-        }
-      }
+      if (i < n) count_key(i, keys[i]);
     }
   }
   __syncthreads();
