@@ -356,6 +356,10 @@ def test_reserved_key_and_table_full_are_reported():
     st = gt.stats()
     assert st.error == hps.EFULL and st.size == 100
     gt.clear_error()
+    # clearing the status abandons the failed mini-batch: there is nothing valid to push
+    with pytest.raises(hps.HpsError) as e:
+        gt.push(torch.zeros((4, 8), device="cuda"))
+    assert e.value.status == hps.ESTATE
     pooled = gt.pull(dev_keys(np.array([5, 6], dtype=np.uint64)), offs, 2, 2)   # present keys: fine
     assert gt.stats().error == 0
     w, _, f = gt.get(dev_keys(np.array([5, 6], dtype=np.uint64)))
