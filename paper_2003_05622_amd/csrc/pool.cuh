@@ -52,13 +52,19 @@ __device__ __forceinline__ void pool_bags_as(const TableView& t, const i32* __re
       for (int k = 0; k < kPoolInFlight; ++k)
 #pragma unroll
         for (int c = 0; c < COLS; ++c) v[k][c] = raw[k][c].value();
-      // one occurrence after the other, as a plain loop would add them
+      // the (up to) eight rows as a balanced tree, then onto the running sum: a fixed shape,
+      // and a smaller rounding error than adding one row after the other
 #pragma unroll
-      for (int k = 0; k < kPoolInFlight; ++k) {
+      for (int c = 0; c < COLS; ++c) {
 #pragma unroll
-        for (int c = 0; c < COLS; ++c) {
-          acc[c].x += v[k][c].x; acc[c].y += v[k][c].y; acc[c].z += v[k][c].z; acc[c].w += v[k][c].w;
+        for (int w = 1; w < kPoolInFlight; w <<= 1) {
+#pragma unroll
+          for (int k = 0; k + w < kPoolInFlight; k += 2 * w) {
+            v[k][c].x += v[k + w][c].x; v[k][c].y += v[k + w][c].y;
+            v[k][c].z += v[k + w][c].z; v[k][c].w += v[k + w][c].w;
+          }
         }
+        acc[c].x += v[0][c].x; acc[c].y += v[0][c].y; acc[c].z += v[0][c].z; acc[c].w += v[0][c].w;
       }
     }
     if (inv_len) {
