@@ -182,10 +182,9 @@ def test_bf16_rows(name, n_prefill, n_examples, n_slots, opt):
         assert_close(a, oa, "accumulators step %d" % step)
         same = w.view(np.uint32) == ow.view(np.uint32)
         steps_apart = 1 if step == 0 else 2
-        # (on top of the float32 tolerance: where a step nearly cancels a weight, the two float32
-        # results differ by far more than a bfloat16 step of the tiny difference)
-        # (a bfloat16 step of the size the weight had when the difference arose: at least that
-        # of the initial range)
+        # bfloat16 steps of the size the weight had when the difference arose (at least the
+        # initial range), on top of the float32 tolerance: where a step nearly cancels a weight,
+        # the two float32 results differ by far more than a bfloat16 step of what is left
         size = np.maximum(np.abs(ow), cfg.init_range)
         err = np.abs(w.astype(np.float64) - ow) - steps_apart * 2.0 ** -7 * size - (ATOL + RTOL * np.abs(ow))
         assert err.max() <= 0, "weights more than %d bfloat16 step(s) apart" % steps_apart

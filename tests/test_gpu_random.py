@@ -1,8 +1,9 @@
 """Randomised parity on the GPU: seeded random shapes (dim 4..260, 0..300 000 occurrences,
 ragged bags, empty batches), key mixes (hashed Zipf, raw consecutive ids, a handful of
 distinct keys, all distinct, one heavy key, long-tailed raw ids), options (both optimizers,
-sum / mean pooling, float32 / bfloat16 rows, interleaved accumulates) and dedup forms; each
-case is a few pull+push steps checked against the oracle step by step and by a final dump."""
+sum / mean pooling, float32 / bfloat16 rows, interleaved accumulates, the serial and the
+pipelined schedule) and dedup forms; each case is a few pull+push steps checked against the
+oracle step by step and by a final dump."""
 import numpy as np
 import pytest
 import torch
@@ -90,6 +91,10 @@ def run_case(seed, monkeypatch):
         gt.set_pooling(True)
         ot.set_pooling(True)
     steps = int(rng.integers(1, 6))
+    # the default schedule of the benchmark: the dedup of the next mini-batch is enqueued on a
+    # second stream between the current pull and its push
+    pipelined = bool(rng.integers(0, 2))
+    batches = []
     for step in range(steps):
         n = int(rng.integers(0, n_max + 1)) if rng.random() < 0.8 else n_max
         n_bags = int(rng.integers(max(1, n // 32), n_bags_max + 1))
@@ -100,7 +105,26 @@ def run_case(seed, monkeypatch):
         offsets = np.concatenate([[0], cuts, [n]]).astype(np.int32)
         keys = make_keys(rng, n, int(rng.integers(0, 6)), universe) if n else np.zeros(0, np.uint64)
         grads = rng.normal(0, 1e-3, size=(n_bags, dim)).astype(np.float32)
-        pooled = gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+        batches.append((keys, offsets, grads, dev_keys(keys), torch.from_numpy(offsets).cuda()))
+    side = torch.cuda.Stream()
+
+    def prepare(i):
+        keys, offsets, _, dk, do = batches[i]
+        side.wait_stream(torch.cuda.current_stream())      # the inputs were copied on this stream
+        with torch.cuda.stream(side):
+            gt.prepare(dk, do, offsets.size - 1, 1)
+
+    if pipelined:
+        prepare(0)
+    for step in range(steps):
+        keys, offsets, grads, dk, do = batches[step]
+        n, n_bags = keys.size, offsets.size - 1
+        if pipelined:
+            pooled = gt.pull_prepared()
+            if step + 1 < steps:
+                prepare(step + 1)
+        else:
+            pooled = gt.pull(dk, do, n_bags, 1)
         want = ot.pull(keys, offsets)
         st = gt.stats()
         assert st.error == 0
@@ -115,11 +139,12 @@ def run_case(seed, monkeypatch):
             assert err.max(initial=-1) <= 0, "pooled: excess %g" % err.max()
         gt.push(torch.from_numpy(grads).cuda())
         ot.push(grads)
-        if rng.random() < 0.3 and n:
+        if rng.random() < 0.3 and n and not pipelined:     # (not between a prepare and its pull)
             k2 = keys[: max(1, n // 3)]
             v2 = rng.normal(0, 1e-3, size=(k2.size, dim)).astype(np.float32)
             gt.accumulate(dev_keys(k2), torch.from_numpy(v2).cuda())
             ot.accumulate(k2, v2)
+    torch.cuda.synchronize()
     k, w, a = gt.dump()
     k = k.cpu().numpy().view(np.uint64)
     order = np.argsort(k, kind="stable")
