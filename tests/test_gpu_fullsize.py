@@ -143,3 +143,52 @@ def test_skewed_full_size_bucket_path_without_a_hint(monkeypatch):
 def test_large_full_size(monkeypatch):
     monkeypatch.delenv("HPS_DEDUP", raising=False)
     run_full("large", steps=4)
+
+
+def test_dedup_two_million_keys_that_do_not_suit_the_buckets():
+    """The dedup at the mid workload's size (2 M occurrences) on key sets the bucket form is
+    not made for, in the order that is hardest for its hints: hashed keys first (so the table
+    is past its first two dedups), then unhashed consecutive ids, then a key that makes up a
+    third of the batch without having been frequent before (one workgroup orders its 7*10^5
+    pairs through global memory while a thousand others wait for its count), the same again
+    (now announced), long-tailed raw ids (most keys in one part of the range: the library goes
+    back to the plain form), and hashed keys again.  Unique keys and inverse ranks must be the
+    oracle's, bit for bit, every time, and no wait may give up."""
+    import oracle
+    rng = np.random.default_rng(77)
+    n, dim, n_bags = 2_000_000, 8, 4096
+    gt = hps.HpsTable(12_000_000, dim, n, n_bags)
+    offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+    d_off = torch.from_numpy(offsets).cuda()
+    zero = torch.zeros((n_bags, dim), device="cuda")
+
+    def hashed():
+        return synth.mix64(rng.integers(0, 1_500_000, size=n).astype(np.uint64))
+
+    def hot(keys):
+        keys = keys.copy()
+        keys[rng.random(n) < 0.35] = np.uint64(0x123456789ABCDEF)
+        return keys
+
+    cases = [
+        ("hashed", hashed()), ("hashed", hashed()), ("hashed", hashed()),
+        ("raw consecutive ids", np.uint64(1 << 40) + rng.integers(0, 1_500_000, size=n).astype(np.uint64)),
+        ("hashed, one key suddenly a third of the batch", hot(hashed())),
+        ("the same key again", hot(hashed())),
+        ("long-tailed raw ids", np.minimum(rng.pareto(1.0, size=n) * 1000.0, 5e7).astype(np.uint64)),
+        ("long-tailed raw ids", np.minimum(rng.pareto(1.0, size=n) * 1000.0, 5e7).astype(np.uint64)),
+        ("hashed", hashed()),
+    ]
+    for what, keys in cases:
+        t0 = time.time()
+        gt.pull(dev_keys(keys), d_off, n_bags, 1)
+        st = gt.stats()
+        print(what, "pull %.1f ms" % ((time.time() - t0) * 1e3), "unique", st.last_n_unique,
+              "fallbacks", st.n_plain_fallbacks, flush=True)
+        ou, oi = oracle.dedup(keys)
+        assert st.error == 0 and st.last_n_unique == ou.size, what
+        uniq, inv = gt.last_unique()
+        assert np.array_equal(uniq.cpu().numpy().view(np.uint64), ou), what + ": unique keys"
+        assert np.array_equal(inv.cpu().numpy(), oi), what + ": inverse"
+        gt.push(zero)
+    assert gt.stats().n_plain_fallbacks >= 1
