@@ -34,9 +34,10 @@
  *     status word; the kernels of later calls do nothing while it is set, and it
  *     is reported by hps_stats() and cleared by hps_clear_error().
  *   - The key 0xFFFFFFFFFFFFFFFF marks an empty slot and is not a legal key.
- *   - One pull may be outstanding per table (between hps_pull and hps_push); a new
- *     pull replaces it.  In addition one mini-batch may be "prepared" (its key dedup
- *     done ahead of time, see hps_prepare); the workspace holds both contexts.
+ *   - One pull may be outstanding per table (between hps_pull and hps_push); another
+ *     pull before that push is refused (HPS_ESTATE).  In addition one mini-batch may be
+ *     "prepared" (its key dedup done ahead of time, see hps_prepare); the workspace
+ *     holds both contexts.
  *   - Calls that touch the table (insert, pull, pull_prepared, push, get, dump) must
  *     be issued on one stream at a time (or be ordered by the caller).  hps_prepare
  *     does not touch the table and may run on another stream; the library orders it
