@@ -617,3 +617,29 @@ def test_dedup_sizes_around_tile_and_region_borders(n, dedup_form):
             assert np.array_equal(host_keys(uniq), ou), "unique keys"
             assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
             gt.push(torch.zeros((64, dim), device="cuda"))
+
+
+def test_many_dedups_status_words_start_over(dedup_form):
+    """The cross-workgroup status words of the dedup carry the dedup's number modulo 4095, and
+    the library clears them whenever the numbers start over.  4300 small mini-batches of
+    varying size go past that point; the results around it (and every 97th before) must be
+    the oracle's."""
+    rng = np.random.default_rng(4095)
+    dim, n_bags, n_max = 4, 64, 9000
+    gt = hps.HpsTable(300_000, dim, n_max, n_bags)
+    pool = synth.mix64(np.arange(200_000, dtype=np.uint64))
+    zero = torch.zeros((n_bags, dim), device="cuda")
+    for step in range(4300):
+        n = int(rng.integers(1, n_max + 1))
+        keys = pool[rng.integers(0, pool.size, size=n)]
+        offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+        gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+        if step % 97 == 0 or 4085 <= step <= 4105:
+            ou, oi = oracle.dedup(keys)
+            uniq, inv = gt.last_unique()
+            st = gt.stats()
+            assert st.error == 0 and st.last_n_unique == ou.size, "step %d" % step
+            assert np.array_equal(host_keys(uniq), ou), "unique keys, step %d" % step
+            assert np.array_equal(inv.cpu().numpy(), oi), "inverse, step %d" % step
+        gt.push(zero)
+    assert gt.stats().error == 0
