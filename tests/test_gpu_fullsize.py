@@ -192,3 +192,55 @@ def test_dedup_two_million_keys_that_do_not_suit_the_buckets():
         assert np.array_equal(inv.cpu().numpy(), oi), what + ": inverse"
         gt.push(zero)
     assert gt.stats().n_plain_fallbacks >= 1
+
+
+def test_first_pull_creates_three_million_rows():
+    """A pull whose keys are nearly all new, so many that the blocks of the lookup cannot
+    note all their missing keys and the insert falls back to scanning for them: 3 M distinct
+    keys into an empty table.  Unique keys, inverse, the inserted count, pooled rows and a
+    sample of the created rows against the oracle."""
+    rng = np.random.default_rng(5)
+    n, dim, n_bags = 3_000_000, 4, 65536
+    keys = synth.mix64(rng.permutation(4_000_000)[:n].astype(np.uint64) + np.uint64(10**12))
+    offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+    kw = dict(lr=0.05, eps=1e-8, init_acc=0.1, init_range=0.01, init_seed=3)
+    gt = hps.HpsTable(4_000_000, dim, n, n_bags, **kw)
+    ot = OracleTable(4_000_000, dim, **kw)
+    pooled = gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+    want = ot.pull(keys, offsets)
+    st = gt.stats()
+    assert st.error == 0 and st.last_n_unique == n and st.last_n_inserted == n and st.size == n
+    uniq, inv = gt.last_unique()
+    ou, oi = ot.last_unique()
+    assert np.array_equal(uniq.cpu().numpy().view(np.uint64), ou) and np.array_equal(inv.cpu().numpy(), oi)
+    # bags of ~46 rows of both signs: the tolerance is taken relative to the rows' magnitudes
+    err = np.abs(pooled.cpu().numpy().astype(np.float64) - want) - (ATOL + RTOL * 46 * 0.01)
+    assert err.max() <= 0, "pooled: excess %g" % err.max()
+    gt.push(torch.zeros((n_bags, dim), device="cuda"))
+    probe = keys[:: 997]
+    w, a, f = gt.get(dev_keys(probe))
+    ow, oa, of = ot.get(probe)
+    assert f.all() and np.array_equal(w.cpu().numpy(), ow)          # initial rows: bit-exact
+
+
+def test_dedup_thirteen_million_occurrences():
+    """More occurrences than the bucket form takes (1.2 * 10^7): the plain form with six
+    passes at a size no workload has.  Unique keys and inverse ranks against the oracle."""
+    import oracle
+    rng = np.random.default_rng(13)
+    n, dim, n_bags = 13_000_000, 4, 4096
+    keys = synth.mix64(rng.integers(0, 6_000_000, size=n).astype(np.uint64))
+    keys[rng.random(n) < 0.05] = synth.mix64(np.uint64(42))          # and one frequent key
+    offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+    gt = hps.HpsTable(8_000_000, dim, n, n_bags)
+    d_keys, d_off = dev_keys(keys), torch.from_numpy(offsets).cuda()
+    zero = torch.zeros((n_bags, dim), device="cuda")
+    ou, oi = oracle.dedup(keys)
+    for rounds in range(3):       # the third would take the bucket form if the size allowed it
+        gt.pull(d_keys, d_off, n_bags, 1)
+        st = gt.stats()
+        assert st.error == 0 and st.last_n_unique == ou.size
+        uniq, inv = gt.last_unique()
+        assert np.array_equal(uniq.cpu().numpy().view(np.uint64), ou), "unique keys"
+        assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+        gt.push(zero)

@@ -545,6 +545,9 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         (200_000, [3], [0.3], True),                   # with a hashed hot key far outside their range
         (300_000, [9], [0.001]),                       # back to ordinary
         (300_000, [9], [0.001]),
+        (390_000, list(range(100, 2100)), [0.0004] * 2000),   # 2000 keys of ~150 occurrences: more
+        (390_000, list(range(100, 2100)), [0.0004] * 2000),   # frequent keys than the hint can list
+        (390_000, list(range(100, 2100)), [0.0004] * 2000),
     ]
     for case in cases:
         keys = batch(*case)
