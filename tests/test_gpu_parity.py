@@ -646,3 +646,25 @@ def test_many_dedups_status_words_start_over(dedup_form):
             assert np.array_equal(inv.cpu().numpy(), oi), "inverse, step %d" % step
         gt.push(zero)
     assert gt.stats().error == 0
+
+
+def test_dedup_two_clusters_far_apart(dedup_form):
+    """Unhashed ids in two small clusters at opposite ends of the 64-bit range: whatever leading
+    bits (of the key, or of its place in the key range) the passes sort by, the keys of a
+    cluster agree in all of them, so the plain form has to repair nearly everything and the
+    bucket form gets two oversized regions.  Results must still be exact."""
+    rng = np.random.default_rng(8)
+    dim, n_bags, n = 4, 256, 120_000
+    gt = hps.HpsTable(400_000, dim, n, n_bags)
+    offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
+    for step in range(4):
+        low = rng.integers(0, 60_000, size=n).astype(np.uint64)
+        keys = np.where(rng.random(n) < 0.5, low, np.uint64(2**63) + low)
+        gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+        ou, oi = oracle.dedup(keys)
+        uniq, inv = gt.last_unique()
+        st = gt.stats()
+        assert st.error == 0 and st.last_n_unique == ou.size
+        assert np.array_equal(host_keys(uniq), ou), "unique keys"
+        assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
+        gt.push(torch.zeros((n_bags, dim), device="cuda"))
