@@ -42,6 +42,10 @@
  *     be issued on one stream at a time (or be ordered by the caller).  hps_prepare
  *     does not touch the table and may run on another stream; the library orders it
  *     against the calls that share its buffers with HIP events.
+ *   - Do not capture hps_prepare / hps_pull / hps_accumulate into a HIP graph for replay:
+ *     every dedup carries a sequence number, chosen on the host when the call is made,
+ *     that tells its kernels which of the workspace's hand-off words are theirs; a
+ *     replay would reuse the number of the captured call.
  *   - The key dedup has two forms with identical results; the library picks one per call
  *     from the mini-batch's size and the table's history (its third and later dedups use
  *     the keys that earlier lookups found frequent; the lookups report back, into pinned
