@@ -56,6 +56,25 @@ def stage_bytes(n, u, bags, d, wb=4):
     }
 
 
+def host_description():
+    """The box the CPU figure was taken on: core count, CPU model, memory."""
+    model, mem_gib = "unknown", None
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        with open("/proc/meminfo") as f:
+            for line in f:
+                if line.startswith("MemTotal"):
+                    mem_gib = round(int(line.split()[1]) / 2**20, 1)
+                    break
+    except OSError:
+        pass
+    return {"cpus": os.cpu_count(), "cpu_model": model, "mem_gib": mem_gib}
+
+
 STAGE_BITS = {"dedup": 0b00011, "lookup": 0b00100, "pool": 0b01000, "push": 0b10000}
 STAGE_KERNELS = {
     "dedup": "sort_prepare, 1-2 x onesweep_pass (by bucket id), chunk_sort_emit "
@@ -253,7 +272,8 @@ def main():
         cpu = {"value": round(done_u / spent, 1), "unit": "unique keys/s", "cores": 1,
                "kind": "oracle",
                "sample": "%d mini-batch(es) of the '%s' workload, pull+push, single thread, "
-                         "%.1f s" % (done, cfg.name, spent)}
+                         "%.1f s" % (done, cfg.name, spent),
+               "host": host_description()}
 
     out = {
         "metric": "unique keys/sec pull+push (1 MI355X) and achieved HBM GB/s vs peak",
