@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.hpo_set_pooling.argtypes = [vp, ctypes.c_int]
         L.hpo_accumulate.restype = i32
         L.hpo_accumulate.argtypes = [vp, vp, u64, vp, vp]
+        L.hpo_clear.restype = i32
+        L.hpo_clear.argtypes = [vp]
         L.hpo_set_row_format.restype = i32
         L.hpo_set_row_format.argtypes = [vp, ctypes.c_int]
         L.hpo_nearest_bf16.restype = f32
@@ -213,6 +215,10 @@ class OracleTable:
 
     def set_pooling(self, mean: bool) -> None:
         _check(lib().hpo_set_pooling(self._h, 1 if mean else 0), "set_pooling")
+
+    def clear(self) -> None:
+        """Empties the table; settings stay."""
+        _check(lib().hpo_clear(self._h), "clear")
 
     def accumulate(self, keys, values) -> int:
         """Adds the value rows onto the rows of their keys; returns the number of

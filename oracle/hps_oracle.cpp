@@ -160,6 +160,22 @@ void* hpo_create(uint64_t capacity, uint32_t dim, int opt, float lr, float eps, 
 
 void hpo_destroy(void* h) { delete static_cast<Table*>(h); }
 
+// Algorithm 1 builds the HBM table anew for every batch of the outer loop (insert the
+// batch's working parameters, run its mini-batches, hand the updates to the host tier):
+// this empties the table for the next batch.  Settings (optimizer, pooling, row format)
+// stay.
+int hpo_clear(void* h) {
+  Table& t = *static_cast<Table*>(h);
+  if (t.pulled) return ESTATE;
+  t.index.clear();
+  t.row_key.clear();
+  t.w.clear();
+  t.acc.clear();
+  t.dirty.clear();
+  t.implicit_rows = t.implicit_seen = 0;
+  return OK;
+}
+
 // How weights are stored: float32 (0, the default) or bfloat16 (1).  Only while the table
 // is empty.
 int hpo_set_row_format(void* h, int format) {

@@ -804,3 +804,32 @@ def test_bf16_rows_whole_step_closed_form(opt):
         lib_table = OracleTable(4, 2)
         lib_table.insert(np.array([1], dtype=np.uint64))
         oracle._check(oracle.lib().hpo_set_row_format(lib_table._h, oracle.ROWS_BF16), "set_row_format")
+
+
+def test_clear_empties_the_table_and_keeps_the_settings():
+    # Algorithm 1: one table per batch of the outer loop.  After a clear the table behaves
+    # like a new one with the same settings: nothing is found, rows are created from the
+    # initialiser again (whatever they had become), and nothing counts as updated.
+    t = OracleTable(8, 4, opt=oracle.ADAGRAD_ELEMENTWISE, lr=0.5, eps=0.0, init_acc=0.25, init_seed=9)
+    fresh = OracleTable(8, 4, opt=oracle.ADAGRAD_ELEMENTWISE, lr=0.5, eps=0.0, init_acc=0.25, init_seed=9)
+    keys = np.array([5, 6, 7], dtype=np.uint64)
+    offsets = np.array([0, 2, 3], dtype=np.int32)
+    t.set_pooling(True)
+    fresh.set_pooling(True)
+    t.pull(keys, offsets)
+    with pytest.raises(OracleError) as e:
+        t.clear()                                           # not between a pull and its push
+    assert e.value.status == oracle.ESTATE
+    t.push(np.ones((2, 4), dtype=np.float32))
+    assert t.size == 3 and not np.array_equal(t.get(keys)[0][0], t.init_row(5))
+    t.clear()
+    assert t.size == 0 and not t.get(keys)[2].any()
+    assert t.dump()[0].size == 0 and t.dump_dirty()[0].size == 0
+    for table in (t, fresh):                                # same steps on the cleared and on a new table
+        table.insert(np.arange(8, dtype=np.uint64))         # capacity 8 is available again
+        table.pull(keys, offsets)
+        table.push(np.full((2, 4), 0.5, dtype=np.float32))
+    for a, b in zip(t.dump(), fresh.dump()):
+        assert np.array_equal(a, b)
+    for a, b in zip(t.dump_dirty(), fresh.dump_dirty()):
+        assert np.array_equal(a, b)
