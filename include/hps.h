@@ -139,6 +139,13 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
                       void* d_workspace, size_t workspace_bytes, uint64_t max_keys,
                       uint64_t max_bags, void* stream);
 
+/* Algorithm 1 builds the HBM table anew for every batch of its outer loop (insert the
+ * batch's working parameters, run the mini-batches, hand the updates to the host tier):
+ * empties the table for the next batch -- every key, the sticky status and the counters;
+ * optimizer, pooling and row format stay.  Enqueues the clearing of the slot array on
+ * `stream`.  Errors: HPS_ESTATE between hps_prepare / a pull and its push. */
+hps_status hps_clear(hps_table* t, void* stream);
+
 /* Section 4.1 "insert" / Algorithm 1 insert_into_hashtable: bulk load of n keys.
  *   d_weights [n, dim] or NULL, d_acc [n, acc_len] or NULL (acc_len = 1 row-wise,
  *   dim element-wise).

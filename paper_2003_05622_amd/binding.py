@@ -14,7 +14,7 @@ ROWS_F32, ROWS_BF16 = 0, 1
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
            "hps_push", "hps_set_pooling", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
-           "hps_stats", "hps_clear_error",
+           "hps_stats", "hps_clear_error", "hps_clear",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
 STAGES = ("sort", "unique", "lookup", "pool", "push")
@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
         L.hps_clear_error.restype = st
         L.hps_clear_error.argtypes = [vp, vp]
+        L.hps_clear.restype = st
+        L.hps_clear.argtypes = [vp, vp]
         L.hps_set_stage_timing.restype = st
         L.hps_set_stage_timing.argtypes = [vp, u32]
         L.hps_stage_times.restype = st
@@ -248,6 +250,10 @@ class HpsTable:
         cnt = (ctypes.c_uint32 * len(STAGES))()
         _check(lib().hps_stage_times(self._h, ms, cnt), "hps_stage_times")
         return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
+
+    def clear(self) -> None:
+        """Empties the table (settings stay)."""
+        _check(lib().hps_clear(self._h, _stream()), "hps_clear")
 
     def clear_error(self) -> None:
         _check(lib().hps_clear_error(self._h, _stream()), "hps_clear_error")

@@ -582,6 +582,17 @@ hps_status hps_destroy(hps_table* t) {
   return HPS_OK;
 }
 
+hps_status hps_clear(hps_table* t, void* stream) {
+  if (!t) return HPS_EINVAL;
+  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // rows and accumulators need no clearing: a slot's row is written when its key is
+  // claimed, and the marks of updated rows live in the accumulators
+  fill_u64<<<4096, 256, 0, s>>>(t->view.keys, t->n_slots, kEmptyKey);
+  reset_state<<<1, 64, 0, s>>>(t->view.st);
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
 hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_weights,
                       const float* d_acc, void* stream) {
   if (!t || (n && !d_keys) || (d_acc && !d_weights)) return HPS_EINVAL;

@@ -668,3 +668,49 @@ def test_dedup_two_clusters_far_apart(dedup_form):
         assert np.array_equal(host_keys(uniq), ou), "unique keys"
         assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
         gt.push(torch.zeros((n_bags, dim), device="cuda"))
+
+
+def test_clear_and_rebuild_for_the_next_batch():
+    """Algorithm 1's outer loop: per batch the table is filled with that batch's working
+    parameters, its mini-batches are run, the updates are handed over and the table is
+    emptied.  Two such batches; the second starts from the rows the first handed over (for
+    the keys they share) and the table must again hold exactly what the oracle holds."""
+    cfg = synth.scaled(synth.CONFIGS["mid"], n_prefill=30_000, n_examples=64, n_slots=40, steps=6)
+    stream = synth.BatchStream(cfg)
+    gt, ot = make_pair(cfg, 40_000)
+    host = {}                                     # the host tier: key -> (weights, accumulator)
+    for outer in range(2):
+        batches = [stream.next() for _ in range(3)]
+        working = np.unique(np.concatenate([b.keys for b in batches]))
+        known = np.array([k for k in working if int(k) in host], dtype=np.uint64)
+        new = np.setdiff1d(working, known)
+        for table, to_dev in ((gt, True), (ot, False)):
+            if known.size:
+                w = np.stack([host[int(k)][0] for k in known])
+                a = np.stack([host[int(k)][1] for k in known])
+                if to_dev:
+                    table.insert(dev_keys(known), torch.from_numpy(w).cuda(), torch.from_numpy(a).cuda())
+                else:
+                    table.insert(known, w, a)
+            table.insert(dev_keys(new) if to_dev else new)
+        assert gt.stats().size == working.size == ot.size
+        for b in batches:
+            pooled = gt.pull(dev_keys(b.keys), torch.from_numpy(b.offsets).cuda(), cfg.n_examples, cfg.n_slots)
+            want = ot.pull(b.keys, b.offsets)
+            assert gt.stats().last_n_inserted == 0 == ot.n_inserted     # the working set was there
+            assert_close(pooled.cpu().numpy(), want, "pooled")
+            gt.push(torch.from_numpy(b.grads).cuda())
+            ot.push(b.grads)
+        compare_tables(gt, ot, "outer batch %d" % outer, working)
+        k, w, a = ot.dump_dirty()                 # the updates go to the host tier ...
+        gk, gw, ga = gt.dump(dirty=True)
+        assert np.array_equal(np.sort(host_keys(gk)), k)
+        for key, wr, ar in zip(k, w, a):
+            host[int(key)] = (wr.copy(), ar.copy())
+        gt.clear()                                # ... and the table is emptied
+        ot.clear()
+        st = gt.stats()
+        assert st.size == 0 and st.error == 0
+        assert not gt.get(dev_keys(working[:100]))[2].any()
+        kk, _, _ = gt.dump()
+        assert kk.numel() == 0
