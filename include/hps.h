@@ -27,6 +27,10 @@
  *     them).  `storage` holds the table for its whole life, `workspace` holds the
  *     context of the outstanding pull.  Both must be 256-byte aligned.
  *   - Pointers named h_* are host memory.
+ *   - A table belongs to the GPU that is current when hps_create is called (the one its
+ *     storage lives on); make the same device current for every later call on it.  The
+ *     library keeps no state outside its tables: several tables, also on several GPUs
+ *     of one process, do not interfere.  Calls on ONE table are not thread-safe.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *     on it and return without waiting, except where stated.
  *   - Return value: HPS_OK or a negative hps_status.  Errors that only the device
