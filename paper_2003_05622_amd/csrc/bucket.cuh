@@ -352,9 +352,22 @@ __device__ __forceinline__ void slow_region(const u64* skeys, const u64* spay, u
                                          i32* inverse, u32* bagperm, u32* seg_off, PullCtx* ctx,
                                          TableState* st) {
   const u32 tid = threadIdx.x;
-  if (tid == 0) atomicAdd(&ctx->n_slow, end - start);
   const u64 *sk, *sp;
   slow_sort_region(skeys, spay, ka, pa, kb, pb, start, end, slow, &sk, &sp);
+  if (tid == 0) {
+    // For the host's choice of the next dedups' form: how much went this way, and how much
+    // of that because ONE key fills the region (then the sorted region's middle element is
+    // that key: count it) -- a key that turned frequent without warning, which the next
+    // hint will list, and not keys that do not suit the buckets.
+    const u64 mid_key = sk[start + (end - start) / 2];
+    u32 lo = start, hi = end;
+    while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] < mid_key) lo = m + 1; else hi = m; }
+    const u32 first = lo;
+    hi = end;
+    while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] <= mid_key) lo = m + 1; else hi = m; }
+    atomicAdd(&ctx->n_slow, end - start);
+    if ((lo - first) * 2 >= end - start) atomicAdd(&ctx->n_slow_one_key, end - start);
+  }
   // the element before the region is read from the untouched source
   const bool first_is_head = start == 0 || sk[start] != skeys[start - 1];
   u32 heads = 0;

@@ -62,6 +62,8 @@ struct PullCtx {
   u32 by_id;           // 1: this dedup took the bucket form
   u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
   KeyRange range;                // written by the dedup's first kernel for the later ones
+  u32 n_slow_one_key;            // ... of n_slow, in regions that one key fills at least half of
+  u32 pad;
 };
 
 // Keys that make up a large share of a mini-batch (bucket.cuh).  HeavySet: ascending,

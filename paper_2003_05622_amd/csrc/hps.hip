@@ -132,6 +132,7 @@ uint32_t tile_group(uint64_t n_tiles) {
 // hold more occurrences than a region has room for.
 constexpr uint64_t kBucketPathMaxKeys = 12ull << 20;
 constexpr uint64_t kPlainHold = 32;      // dedups in the plain form after the bucket form disappointed
+constexpr uint64_t kHintLag = 3;         // ... after a surprise that the next lists of frequent keys will cover
 static_assert(kChunkSpan + 2 * kNaturalBucket + kBucketPathMaxKeys / kHeavyShare + 64 <= kChunkThreads * kChunkItems,
               "a region must have room for its span, a natural bucket and one heavy key the hint missed");
 
@@ -311,7 +312,11 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       const uint32_t serial = (uint32_t)r, flags = (uint32_t)(r >> 32);
       if (serial != t->report_seen) {
         t->report_seen = serial;
-        if ((flags & kReportBucket) && (flags & kReportSlow)) {
+        if ((flags & kReportBucket) && (flags & kReportSlow) && (flags & kReportOneKey)) {
+          // a few keys turned frequent without warning: plain until the hint has caught up
+          t->plain_until = t->serial + kHintLag;
+          ++t->n_fallbacks;
+        } else if ((flags & kReportBucket) && (flags & kReportSlow)) {
           t->plain_until = t->serial + ((uint64_t)kPlainHold << (t->strikes < 7 ? t->strikes : 7));
           ++t->strikes;
           ++t->n_fallbacks;

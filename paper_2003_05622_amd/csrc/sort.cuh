@@ -112,8 +112,21 @@ __device__ __forceinline__ KeyRange make_range(u64 lo, u64 hi, const SortPlan& p
   r.direct = (r.span >> nat_bits) == 0;
   // span >= 2^nat_bits here, so the quotient is below 2^32 and parts are numbered below 2^nat_bits
   r.mult = r.direct ? 0u : (u32)((1ull << (32 + nat_bits)) / ((r.span >> r.pre) + 1));
-  const u32 sorted_bits = plan.by_id ? 0 : 64 - plan.low_shift;
+  if (plan.by_id) {
+    r.base = 0;
+    return r;
+  }
+  // Plain form: the passes order sorted_bits bits of rel from bit `base` up, so every key with
+  // rel < 2^(base + sorted_bits) is placed exactly, not only those inside the sampled range:
+  // the range that is covered reaches that far, with the sampled range in its middle (a
+  // long-tailed set of raw ids has many keys beyond its largest sample; clamped to one
+  // place they would all have to be put in order afterwards).
+  const u32 sorted_bits = 64 - plan.low_shift;
   r.base = bits > sorted_bits ? bits - sorted_bits : 0;
+  const u64 cover = r.base + sorted_bits >= 64 ? ~0ull : (1ull << (r.base + sorted_bits)) - 1;
+  const u64 spare = (cover - r.span) / 2;
+  r.lo = lo > spare ? lo - spare : 0;
+  r.span = cover;
   return r;
 }
 
@@ -382,6 +395,7 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
       ctx->n_evidence = 0;
       ctx->sort_error = 0;
       ctx->n_slow = 0;
+      ctx->n_slow_one_key = 0;
       ctx->n_total = n;
       ctx->by_id = (u32)plan.by_id;
     }

@@ -115,12 +115,15 @@ struct OftenLists {
   u32 heavy_min;
   // Host memory (or null) that receives serial | flags << 32 about the dedup before this
   // lookup: kReportBucket = it took the bucket form, kReportSlow = and more than 1/8 of
-  // the occurrences lay in regions that had to be ordered through global memory.  The
-  // host looks at it when it chooses the form of a later dedup, without waiting for it.
+  // the occurrences lay in regions that had to be ordered through global memory,
+  // kReportOneKey = most of them in regions that one key fills at least half of (keys
+  // that turned frequent without warning, which the next hint will list; otherwise the
+  // keys do not suit the buckets).  The host looks at it when it chooses the form of a later dedup, without
+  // waiting for it.
   unsigned long long* report;
   u32 serial;
 };
-constexpr u32 kReportBucket = 1, kReportSlow = 2;
+constexpr u32 kReportBucket = 1, kReportSlow = 2, kReportOneKey = 4;
 
 // "Updated since the last dirty dump" is kept in the sign bit of a row's first
 // accumulator element: accumulators are sums of squares, never negative, so the bit
@@ -231,6 +234,7 @@ __global__ void __launch_bounds__(64) set_ctx_empty(PullCtx* ctx, u32* seg_off) 
     ctx->n_evidence = 0;
     ctx->sort_error = 0;
     ctx->n_slow = 0;
+    ctx->n_slow_one_key = 0;
     ctx->n_total = 0;
     ctx->by_id = 0;
     seg_off[0] = 0;
@@ -334,7 +338,8 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
   if (MODE == 0 && often.report && blockIdx.x == 0 && threadIdx.x == 0) {
     const PullCtx* c = often.ctx;
-    const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u);
+    const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u) |
+                      ((u64)c->n_slow_one_key * 2 >= c->n_slow ? kReportOneKey : 0u);
     __hip_atomic_store(often.report, (unsigned long long)often.serial | ((unsigned long long)flags << 32),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
