@@ -54,7 +54,8 @@
  *     from the mini-batch's size and the table's history (its third and later dedups use
  *     the keys that earlier lookups found frequent; the lookups report back, into pinned
  *     host memory that nobody waits for, when the keys did not suit that form, and the next
- *     dedups then take the other one: hps_stats().n_plain_fallbacks).  The environment
+ *     dedups then take the other one, sorting by all 64 key bits if need be:
+ *     hps_stats().n_plain_fallbacks, .n_full_fallbacks).  The environment
  *     variable HPS_DEDUP, read by hps_create, pins the form: "radix" or "bucket" (tests,
  *     comparison runs).
  */
@@ -118,6 +119,8 @@ typedef struct {
   uint64_t last_n_absent;   /* distinct keys the last hps_accumulate did not find  */
   uint64_t n_plain_fallbacks; /* times the dedup went back to its plain form for a while
                                because the keys did not suit the bucket form          */
+  uint64_t n_full_fallbacks;  /* times the dedup's plain form went over to sorting by all
+                               64 key bits for a while (keys in clusters far apart)   */
   int32_t error;            /* sticky device status (0 or a negative hps_status)   */
   int32_t pull_outstanding; /* 1 between a pull and its push                       */
 } hps_stats_t;

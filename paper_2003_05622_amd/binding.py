@@ -31,6 +31,7 @@ class Stats(ctypes.Structure):
                 ("n_slots", ctypes.c_uint64), ("last_n_keys", ctypes.c_uint64),
                 ("last_n_unique", ctypes.c_uint64), ("last_n_inserted", ctypes.c_uint64),
                 ("last_n_absent", ctypes.c_uint64), ("n_plain_fallbacks", ctypes.c_uint64),
+                ("n_full_fallbacks", ctypes.c_uint64),
                 ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
 
 

@@ -20,6 +20,10 @@ constexpr int kErrFull = -2;
 constexpr int kErrReserved = -3;
 constexpr int kErrInternal = -5;   // HPS_EDEVICE: a dedup's cross-workgroup wait gave up (never expected)
 
+// Plain form of the dedup: places where different keys agree in all sorted bits that
+// fix_mixed_runs can note; beyond that one workgroup puts the whole array in order.
+constexpr u32 kMaxEvidence = 1024;
+
 constexpr int kCountShards = 64;   // counters that many blocks add to are spread over this many words
 
 // Lives in the table's storage for the table's whole life.

@@ -27,7 +27,6 @@ namespace hps {
 constexpr int kHeadThreads = 256;
 constexpr int kHeadItems = 8;
 constexpr int kHeadTile = kHeadThreads * kHeadItems;
-constexpr u32 kMaxEvidence = 1024;
 constexpr int kFixThreads = 1024;
 constexpr int kFixWaves = kFixThreads / kWave;
 

@@ -163,7 +163,8 @@ SortPlan bucket_plan(uint64_t n) {
 // keys rarely agree in all sorted bits.  With b sorted bits about n^2 / 2^(b+1) pairs of
 // distinct hashed keys collide; b >= 2*log2(n) - 2 keeps that near one in a few
 // batches, and every collision is repaired anyway (dedup.cuh).
-SortPlan sort_plan(uint64_t n) {
+// all_bits: every bit of the keys is sorted (eight passes), whatever the keys look like.
+SortPlan sort_plan(uint64_t n, bool all_bits) {
   SortPlan p;
   p.by_id = 0;
   p.nat_shift = 0;
@@ -172,7 +173,7 @@ SortPlan sort_plan(uint64_t n) {
   while ((1ull << log2n) < n) ++log2n;
   int want = (2 * log2n - 2 + 7) / 8;
   if (want < 2) want = 2;
-  if (want > kMaxPasses) want = kMaxPasses;
+  if (want > kMaxPasses || all_bits) want = kMaxPasses;
   p.n_pass = want;
   p.low_shift = 64 - 8 * want;
   p.group = tile_group((n + kSortTile - 1) / kSortTile);
@@ -217,6 +218,11 @@ struct hps_table {
   uint32_t strikes;
   uint64_t plain_until;     // dedups numbered below this take the plain form
   uint64_t n_fallbacks;     // times plain_until was pushed out
+  // The same for the plain form itself: after a dedup whose keys agreed in all the bits the
+  // plain form sorts by (table.cuh: kReportMixed), the following ones sort by all 64 bits.
+  uint32_t full_strikes;
+  uint64_t full_until;
+  uint64_t n_full_fallbacks;
 
   // Pull contexts.  `current` is the context of the outstanding pull (-1: none),
   // `prepared` the one whose dedup has been enqueued but not yet pulled (-1: none).
@@ -323,11 +329,19 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
         } else if (flags & kReportBucket) {
           t->strikes = 0;
         }
+        if (flags & kReportMixed) {
+          // the plain form's sorted bits did not tell the keys apart: all 64 bits for a while
+          t->full_until = t->serial + ((uint64_t)kPlainHold << (t->full_strikes < 7 ? t->full_strikes : 7));
+          ++t->full_strikes;
+          ++t->n_full_fallbacks;
+        } else if (!(flags & kReportBucket) && t->serial >= t->full_until) {
+          t->full_strikes = 0;       // the plain form with its usual passes did well
+        }
       }
     }
     const bool buckets = n <= kBucketPathMaxKeys && t->dedup_mode != 1 &&
                          (t->dedup_mode == 2 || (t->lookup_serial >= 2 && t->serial >= t->plain_until));
-    const SortPlan plan = buckets ? bucket_plan(n) : sort_plan(n);
+    const SortPlan plan = buckets ? bucket_plan(n) : sort_plan(n, t->dedup_mode != 2 && t->serial < t->full_until);
     u64* kcur = t->w<u64>(L.keys_a);
     u64* kalt = t->w<u64>(L.keys_b);
     u64* pcur = t->w<u64>(L.idx_a);
@@ -545,6 +559,9 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->strikes = 0;
   t->plain_until = 0;
   t->n_fallbacks = 0;
+  t->full_strikes = 0;
+  t->full_until = 0;
+  t->n_full_fallbacks = 0;
   t->report = nullptr;
   if (hipHostMalloc(reinterpret_cast<void**>(&t->report), 64, hipHostMallocDefault) != hipSuccess) {
     (void)hipGetLastError();
@@ -851,6 +868,7 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->last_n_inserted = st.inserted;
   h_out->last_n_absent = (uint64_t)st.absent;
   h_out->n_plain_fallbacks = t->n_fallbacks;
+  h_out->n_full_fallbacks = t->n_full_fallbacks;
   h_out->error = st.error;
   h_out->pull_outstanding = t->current >= 0 ? 1 : 0;
   return HPS_OK;

@@ -118,12 +118,14 @@ struct OftenLists {
   // the occurrences lay in regions that had to be ordered through global memory,
   // kReportOneKey = most of them in regions that one key fills at least half of (keys
   // that turned frequent without warning, which the next hint will list; otherwise the
-  // keys do not suit the buckets).  The host looks at it when it chooses the form of a later dedup, without
+  // keys do not suit the buckets); kReportMixed = it took the plain form and more places
+  // than fix_mixed_runs can note had different keys agreeing in all sorted bits (keys in
+  // clusters far apart), so that one workgroup had to put the whole array in order.  The host looks at it when it chooses the form of a later dedup, without
   // waiting for it.
   unsigned long long* report;
   u32 serial;
 };
-constexpr u32 kReportBucket = 1, kReportSlow = 2, kReportOneKey = 4;
+constexpr u32 kReportBucket = 1, kReportSlow = 2, kReportOneKey = 4, kReportMixed = 8;
 
 // "Updated since the last dirty dump" is kept in the sign bit of a row's first
 // accumulator element: accumulators are sums of squares, never negative, so the bit
@@ -339,7 +341,8 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   if (MODE == 0 && often.report && blockIdx.x == 0 && threadIdx.x == 0) {
     const PullCtx* c = often.ctx;
     const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u) |
-                      ((u64)c->n_slow_one_key * 2 >= c->n_slow ? kReportOneKey : 0u);
+                      ((u64)c->n_slow_one_key * 2 >= c->n_slow ? kReportOneKey : 0u) |
+                      (!c->by_id && c->n_evidence > kMaxEvidence ? kReportMixed : 0u);
     __hip_atomic_store(often.report, (unsigned long long)often.serial | ((unsigned long long)flags << 32),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }

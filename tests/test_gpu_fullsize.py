@@ -182,12 +182,18 @@ def test_dedup_two_million_keys_that_do_not_suit_the_buckets():
         ("long-tailed raw ids", np.minimum(rng.pareto(1.0, size=n) * 1000.0, 5e7).astype(np.uint64)),
         ("hashed", hashed()),
     ]
+    # two id spaces 2^50 apart, a million ids each: no 40 leading bits tell a space's ids apart
+    # (the plain form repairs everything once, then sorts by all 64 bits)
+    for _ in range(3):
+        low = rng.integers(0, 1_000_000, size=n).astype(np.uint64)
+        cases.append(("two id spaces far apart", np.where(rng.random(n) < 0.5, low, np.uint64(1 << 50) + low)))
+    cases.append(("hashed", hashed()))
     for what, keys in cases:
         t0 = time.time()
         gt.pull(dev_keys(keys), d_off, n_bags, 1)
         st = gt.stats()
         print(what, "pull %.1f ms" % ((time.time() - t0) * 1e3), "unique", st.last_n_unique,
-              "fallbacks", st.n_plain_fallbacks, flush=True)
+              "fallbacks", st.n_plain_fallbacks, st.n_full_fallbacks, flush=True)
         ou, oi = oracle.dedup(keys)
         assert st.error == 0 and st.last_n_unique == ou.size, what
         uniq, inv = gt.last_unique()
@@ -196,7 +202,7 @@ def test_dedup_two_million_keys_that_do_not_suit_the_buckets():
         gt.push(zero)
     # once for the key that turned frequent (a short stay in the plain form: the next hint lists
     # it), once for the long-tailed ids that met the bucket form (a long stay)
-    assert gt.stats().n_plain_fallbacks == 2
+    assert gt.stats().n_plain_fallbacks == 2 and gt.stats().n_full_fallbacks == 1
 
 
 def test_first_pull_creates_three_million_rows():

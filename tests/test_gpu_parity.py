@@ -652,12 +652,13 @@ def test_dedup_two_clusters_far_apart(dedup_form):
     """Unhashed ids in two small clusters at opposite ends of the 64-bit range: whatever leading
     bits (of the key, or of its place in the key range) the passes sort by, the keys of a
     cluster agree in all of them, so the plain form has to repair nearly everything and the
-    bucket form gets two oversized regions.  Results must still be exact."""
+    bucket form gets two oversized regions.  Results must still be exact, and left to itself
+    the library must end up sorting by all 64 bits."""
     rng = np.random.default_rng(8)
     dim, n_bags, n = 4, 256, 120_000
     gt = hps.HpsTable(400_000, dim, n, n_bags)
     offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
-    for step in range(4):
+    for step in range(6):
         low = rng.integers(0, 60_000, size=n).astype(np.uint64)
         keys = np.where(rng.random(n) < 0.5, low, np.uint64(2**63) + low)
         gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
@@ -668,6 +669,11 @@ def test_dedup_two_clusters_far_apart(dedup_form):
         assert np.array_equal(host_keys(uniq), ou), "unique keys"
         assert np.array_equal(inv.cpu().numpy(), oi), "inverse"
         gt.push(torch.zeros((n_bags, dim), device="cuda"))
+    st = gt.stats()
+    if dedup_form == "auto":
+        assert st.n_full_fallbacks >= 1 and st.n_plain_fallbacks >= 1
+    else:
+        assert st.n_full_fallbacks == 0 and st.n_plain_fallbacks == 0
 
 
 def test_clear_and_rebuild_for_the_next_batch():
