@@ -62,11 +62,11 @@ def pooled_slack(ot, keys, offsets, n_bags, dim, mean):
     return ((L / 8 + 4) * 2.0 ** -24 + RTOL) * mag
 
 
-def run_case(seed, monkeypatch):
+def run_case(seed, monkeypatch, sizes=(1, 50, 3000, 70000, 300000)):
     rng = np.random.default_rng(seed)
     dim = int(rng.choice([4, 8, 12, 16, 32, 64, 100, 128, 256, 260]))
     n_bags_max = int(rng.choice([1, 7, 64, 1000, 20000]))
-    n_max = int(rng.choice([1, 50, 3000, 70000, 300000]))
+    n_max = int(rng.choice(sizes))
     if dim >= 128:
         n_max = min(n_max, 70000)
     # bags of thousands of rows are outside the float32 tolerance: mean bag length <= 32
@@ -84,9 +84,10 @@ def run_case(seed, monkeypatch):
               init_seed=int(rng.integers(0, 2**32)))
     print("seed", seed, "dim", dim, "max bags", n_bags_max, "max n", n_max, "opt", opt, "mean", mean,
           "bf16", bf16, "form", form, "universe", universe, flush=True)
-    gt = hps.HpsTable(2_000_000, dim, n_max, n_bags_max,
+    capacity = max(2_000_000, 6 * n_max)
+    gt = hps.HpsTable(capacity, dim, n_max, n_bags_max,
                       row_format=hps.ROWS_BF16 if bf16 else hps.ROWS_F32, **kw)
-    ot = OracleTable(2_000_000, dim, row_format=oracle.ROWS_BF16 if bf16 else oracle.ROWS_F32, **kw)
+    ot = OracleTable(capacity, dim, row_format=oracle.ROWS_BF16 if bf16 else oracle.ROWS_F32, **kw)
     if mean:
         gt.set_pooling(True)
         ot.set_pooling(True)
