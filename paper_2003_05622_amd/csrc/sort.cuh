@@ -17,9 +17,11 @@
 //   Bucket ids (by_id plans; the usual form): one or two passes by a 16-bit id made of the
 //   key's leading bits and its place among the heavy keys (bucket_id below); the rest of
 //   the ordering happens per region inside one workgroup (bucket.cuh).
-//   Key bits (plain plans): the keys' top 8 * n_pass bits.  Mini-batch keys are hashed
+//   Key bits (plain plans): the top 8 * n_pass bits of the key's place in the range the
+//   mini-batch's keys span (for hashed keys: of the key).  Mini-batch keys are hashed
 //   feature ids, so these bits separate almost all distinct keys; the rare runs that
-//   still mix different keys are found and put right afterwards (dedup.cuh).
+//   still mix different keys are found and put right afterwards (dedup.cuh).  With
+//   eight passes every bit is sorted and nothing is left to put right.
 // Either way the dedup's result is exact for any input.
 //
 // Cross-tile counts without a serial chain: tiles are grouped, `group` consecutive
