@@ -110,6 +110,8 @@ def main():
                          "command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     ap.add_argument("--rows", choices=("f32", "bf16"), default="f32",
                     help="how the table stores weights (the arithmetic is float32 either way)")
+    ap.add_argument("--gather-rows", type=int, default=1 << 26,
+                    help="rows of the array the library gather for comparison runs over (0: skip it)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="time budget of the CPU oracle leg (0 disables it)")
     args = ap.parse_args()
@@ -248,6 +250,43 @@ def main():
         serial_ms = (time.perf_counter() - c0) / (serial_steps - 1) * 1e3
     st = table.stats()
 
+    # ---- the rate at which this GPU returns random 64-byte rows ---------------------------
+    # Pooling and push are gathers of rows: at least 3U row accesses (pool reads, push reads
+    # and writes each unique row) and N gradient-row gathers per step.  Their bound is the
+    # random-access rate of the memory system, not its streaming bandwidth.  That rate is
+    # measured here with a kernel that does nothing but read random 64-byte rows of a 4 GiB
+    # array in the pooling kernel's access shape (hps_probe_random_rows), and, for
+    # comparison, with a plain library gather (torch.index_select) over the same array.
+    gather = None
+    if args.gather_rows:
+        big = torch.zeros((args.gather_rows, 16), dtype=torch.float32, device="cuda")
+        sink = torch.empty(262144, dtype=torch.float32, device="cuda")
+        n_acc = 1 << 25
+        hps.probe_random_rows(big, n_acc, sink)
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(3):
+            hps.probe_random_rows(big, n_acc, sink)
+        torch.cuda.synchronize()
+        ceiling = 3 * n_acc / (time.perf_counter() - g0)
+        idx = torch.randint(0, args.gather_rows, (1 << 22,), device="cuda")
+        torch.index_select(big, 0, idx)
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(3):
+            torch.index_select(big, 0, idx)
+        torch.cuda.synchronize()
+        lib_rate = 3 * idx.numel() / (time.perf_counter() - g0)
+        del big, idx, sink
+        pp_ms = stages["pool"]["ms"] + stages["push"]["ms"]
+        path_rate = (3 * mean_u + mean_n) / (pp_ms * 1e-3)
+        gather = {"what": "random 64-byte row accesses per second; pooling + push need at least "
+                          "3U + N of them per step; ceiling = a kernel that only reads random rows "
+                          "of a 4 GiB array (hps_probe_random_rows); library = torch.index_select "
+                          "over the same array",
+                  "path_per_s": round(path_rate, 1), "ceiling_per_s": round(ceiling, 1),
+                  "frac": round(path_rate / ceiling, 3), "library_per_s": round(lib_rate, 1)}
+
     # ---- CPU oracle on a bounded sample of the same workload ------------------------------
     cpu = None
     if args.cpu_seconds > 0:
@@ -304,6 +343,7 @@ def main():
                      "launch_ms": round(dom_ms, 4), "launches_timed": int(timed[dominant][1]),
                      "alg_bytes_per_launch": int(per_stage[dominant])},
         "stages": stages,
+        "random_row_access": gather,
         "serial_ms_per_step": None if serial_ms is None else round(serial_ms, 4),
         "cpu_baseline": cpu,
         "setup_s": round(setup_s, 1),

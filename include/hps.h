@@ -263,6 +263,14 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
  * so there is nothing valid to push (a later hps_push returns HPS_ESTATE). */
 hps_status hps_clear_error(hps_table* t, void* stream);
 
+/* Measurement aid, not part of the path: reads random 64-byte rows of d_rows (n_rows rows
+ * of 64 bytes, device, 16-byte aligned) with the pooling kernel's access shape and grid,
+ * about n_accesses of them (rounded up to a multiple of 8 per lane group: 65536 groups),
+ * and writes one float per lane to d_sink (room for 262144 floats).  A benchmark times it
+ * to learn the rate at which this GPU returns such rows, which bounds pooling and push. */
+hps_status hps_probe_random_rows(const void* d_rows, uint64_t n_rows, uint64_t n_accesses,
+                                 float* d_sink, void* stream);
+
 /* Stage timing for measurement.  Stages of one step: */
 enum {
   HPS_STAGE_SORT = 0,    /* pull: order the key occurrences                        */

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     Optimizer,
     Stats,
     lib,
+    probe_random_rows,
     ADAGRAD_ROWWISE,
     ADAGRAD_ELEMENTWISE,
     ROWS_F32,

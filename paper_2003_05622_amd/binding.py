@@ -14,7 +14,7 @@ ROWS_F32, ROWS_BF16 = 0, 1
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
            "hps_push", "hps_set_pooling", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
-           "hps_stats", "hps_clear_error", "hps_clear",
+           "hps_stats", "hps_clear_error", "hps_clear", "hps_probe_random_rows",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
 STAGES = ("sort", "unique", "lookup", "pool", "push")
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.hps_clear_error.argtypes = [vp, vp]
         L.hps_clear.restype = st
         L.hps_clear.argtypes = [vp, vp]
+        L.hps_probe_random_rows.restype = st
+        L.hps_probe_random_rows.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, vp, vp]
         L.hps_set_stage_timing.restype = st
         L.hps_set_stage_timing.argtypes = [vp, u32]
         L.hps_stage_times.restype = st
@@ -111,6 +113,14 @@ def _stream() -> int:
 
 def _ptr(t) -> Optional[int]:
     return None if t is None else t.data_ptr()
+
+
+def probe_random_rows(rows, n_accesses: int, sink) -> None:
+    """Measurement aid: about n_accesses random reads of the 64-byte rows of `rows` (a float32
+    CUDA tensor of shape [n_rows, 16]); `sink` needs 262144 floats."""
+    assert rows.dim() == 2 and rows.shape[1] == 16 and sink.numel() >= 262144
+    _check(lib().hps_probe_random_rows(_ptr(rows), rows.shape[0], n_accesses, _ptr(sink), _stream()),
+           "hps_probe_random_rows")
 
 
 class HpsTable:

@@ -904,6 +904,19 @@ hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count) {
   return rc;
 }
 
+hps_status hps_probe_random_rows(const void* d_rows, uint64_t n_rows, uint64_t n_accesses,
+                                 float* d_sink, void* stream) {
+  if (!d_rows || !d_sink || n_rows == 0 || (uintptr_t)d_rows % 16) return HPS_EINVAL;
+  const unsigned blocks = kPoolMaxBlocks;
+  const uint64_t groups = (uint64_t)blocks * (kPoolThreads / 4);
+  uint64_t per_group = (n_accesses + groups - 1) / groups;
+  per_group = (per_group + kPoolInFlight - 1) / kPoolInFlight * kPoolInFlight;
+  if (per_group == 0 || per_group > 0xFFFFFFF0ull) return HPS_EINVAL;
+  random_row_probe<<<blocks, kPoolThreads, 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const float4*>(d_rows), n_rows, (u32)per_group, d_sink);
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
 hps_status hps_clear_error(hps_table* t, void* stream) {
   if (!t) return HPS_EINVAL;
   clear_error<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(t->view.st);
