@@ -114,21 +114,6 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
   }
 }
 
-template <int LPR, int COLS>
-__device__ __forceinline__ void add_grad_row(float4* g, const float* grads, u32 bag, u32 dim,
-                                             u32 sub) {
-  const float4* row = reinterpret_cast<const float4*>(grads + (u64)bag * dim);
-  const u32 dim4 = dim >> 2;
-#pragma unroll
-  for (int c = 0; c < COLS; ++c) {
-    const u32 col = sub + c * LPR;
-    if (col < dim4) {
-      const float4 v = row[col];
-      g[c].x += v.x; g[c].y += v.y; g[c].z += v.z; g[c].w += v.w;
-    }
-  }
-}
-
 // Adds the bag gradients of positions lo, lo+stride, ... < hi, kPushInFlight positions
 // in flight at a time; each batch is summed as a balanced tree, then added.
 template <int LPR, int COLS>
@@ -315,8 +300,27 @@ __global__ void __launch_bounds__(kPushThreads) push_long(TableView t, PushArgs 
   float4 g[COLS];
 #pragma unroll
   for (int c = 0; c < COLS; ++c) g[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (u32 c = group; c < n_chunks; c += kGroups)
-    add_grad_row<LPR, COLS>(g, a.partials, seg.y + c, t.dim, sub);
+  // (eight partial rows requested at a time, added in chunk order: a key that fills thousands of
+  // chunks would otherwise wait for every row in turn)
+  for (u32 c0 = group; c0 < n_chunks; c0 += kPushInFlight * kGroups) {
+    float4 v[kPushInFlight][COLS];
+#pragma unroll
+    for (int k = 0; k < kPushInFlight; ++k) {
+      const u32 c = c0 + k * kGroups;
+      const float4* row = reinterpret_cast<const float4*>(a.partials + (u64)(seg.y + (c < n_chunks ? c : c0)) * t.dim);
+#pragma unroll
+      for (int q = 0; q < COLS; ++q) {
+        const u32 col = sub + q * LPR;
+        v[k][q] = (c < n_chunks && col < (t.dim >> 2)) ? row[col] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < kPushInFlight; ++k)
+#pragma unroll
+      for (int q = 0; q < COLS; ++q) {
+        g[q].x += v[k][q].x; g[q].y += v[k][q].y; g[q].z += v[k][q].z; g[q].w += v[k][q].w;
+      }
+  }
   block_tree_sum<LPR, COLS>(g, lds, t.dim >> 2);
   const u32 r = a.rows[seg.x];
   if (group == 0 && r != kNoRow) adagrad_row<LPR, COLS>(t, r, g, sub, a.lr, a.eps, a.kind);
