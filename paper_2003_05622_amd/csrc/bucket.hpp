@@ -1,7 +1,7 @@
 // Key dedup, the short way: two radix passes by bucket id, then every chunk of the
 // array is finished inside one workgroup.
 //
-// After the passes (sort.cuh, by_id mode) the occurrences are ordered by bucket id:
+// After the passes (sort.hpp, by_id mode) the occurrences are ordered by bucket id:
 // buckets of keys that share their leading bits (a few hundred occurrences each, in
 // occurrence order) and, between them, one bucket per heavy key.  chunk_sort_emit
 // cuts the array into regions at bucket borders (about kChunkSpan positions each; a
@@ -13,38 +13,48 @@
 //   bagperm[N]   bag of each occurrence, occurrences grouped by key, bit 31 on group heads
 //   seg_off[U+1] start of each key's group in bagperm
 // The number of unique keys in earlier regions comes from the grouped look-back over
-// status words (sort.cuh).
+// status words (sort.hpp).
 //
 // Which keys are heavy is a hint, taken from an earlier mini-batch (the lookup lists
-// the keys that occurred often, the kernel after it puts them in order; common.cuh).  Hot keys of click
+// the keys that occurred often, the kernel after it puts them in order; common.hpp).  Hot keys of click
 // logs persist from batch to batch, so the hint is nearly always right; when it is
 // not (first batch, a new hot key) some region exceeds the LDS capacity and its
 // workgroup orders it through global memory instead: slower, same result.
 #pragma once
 
-#include "common.cuh"
-#include "sort.cuh"
+#include "common.hpp"
+#include "sort.hpp"
+#include "partition.hpp"
 
 namespace hps {
 
 constexpr int kChunkThreads = 512;
 constexpr int kChunkWaves = kChunkThreads / kWave;
 constexpr int kChunkItems = 8;                                // per thread: regions of up to 4096 elements in LDS
-constexpr u32 kChunkSpan = 2048;                              // positions between nominal cuts
+constexpr u32 kChunkSpan = kRegionSpan;                       // positions between nominal cuts
 constexpr u32 kNaturalBucket = 512;                           // mean size of a leading-bits bucket, at most
 constexpr u32 kHeavyShare = 16384;                            // heavy: more than n / kHeavyShare occurrences
 constexpr u32 kHeavyMin = 64;
-constexpr int kSortBits = 32;
-constexpr u32 kIndexMask = 0xFFFFFFu;   // payload: occurrence index in bits 0..23, bag in 32..63      // key bits a region is ordered by at first (all of them if that fails)
+constexpr int kSortBits = 32;           // key bits a region is ordered by at first (all of them if that fails)
 
 // ---- stable LSD radix sort of 64-bit words inside LDS --------------------------------
-// Sorts words[0, cnt) by bits [first_bit, first_bit + 8 * n_pass).  cnt <= THREADS *
-// ITEMS; the words up to the next multiple of THREADS are overwritten with all-ones.
+// Sorts words[0, cnt) by bits [first_bit, first_bit + 8 * n_pass) (all below bit 48: a word's
+// upper 16 bits must be zero and come back zero).  cnt <= THREADS *
+// ITEMS, and `words` has room for THREADS * ITEMS words: the words from cnt up to the next
+// multiple of THREADS are overwritten with all-ones, and whatever lies behind them may be
+// overwritten with anything.
 // hist: two sets (used by alternate passes) of 256 * 8 16-bit counters, digit-major: the
 // eight waves' counters of a digit are 16 consecutive bytes.  Three barriers per pass.
+//
+// Every thread goes through ITEMS rounds without a branch (ITEMS >= the rounds cnt needs;
+// lds_radix_sort_any picks the instance), so that the LDS operations of a pass are issued
+// back to back instead of each waiting for the one before: a round behind the last one reads
+// whatever is there, adds zero to a counter and writes into the unused tail of `words`
+// (which therefore has to hold THREADS * (ITEMS + 1) words, or THREADS * ITEMS if cnt needs
+// all ITEMS rounds).
 constexpr int kLdsSortHist = 2 * kRadix * 8;      // 16-bit words
 
-template <int THREADS, int ITEMS>
+template <int THREADS, int ITEMS, bool ORDERED>
 __device__ __forceinline__ void lds_radix_sort(u64* words, u32 cnt, int first_bit, int n_pass,
                                                uint16_t* hist) {
   constexpr int WAVES = THREADS / kWave;
@@ -55,31 +65,40 @@ __device__ __forceinline__ void lds_radix_sort(u64* words, u32 cnt, int first_bi
   for (u32 q = cnt + tid; q < padded; q += THREADS) words[q] = ~0ull;
   const u64 lt = lanemask_lt();
   const u32 wave_first = wave * kWave * items;          // a wave owns `items` runs of 64 words
+  // (only used by rounds behind the last: items < ITEMS then)
+  const u32 spare = padded + tid;
   if (n_pass > 0 && tid < (u32)kRadix) reinterpret_cast<uint4*>(hist)[tid] = make_uint4(0, 0, 0, 0);
   __syncthreads();
   for (int pass = 0; pass < n_pass; ++pass) {
     const int bit = first_bit + 8 * pass;
     uint16_t* h = hist + (pass & 1) * (kRadix * WAVES);
     uint4* h4 = reinterpret_cast<uint4*>(h);             // [digit]: waves 0..7, 16 bits each
+    // A word uses its low 48 bits; the element's rank inside (digit, wave) travels in the
+    // upper 16 until the word is stored again.
     u64 wd[ITEMS];
-    u32 rank[ITEMS];
     // This wave's counter of digit d is the 16-bit word h[8 * d + wave]; the atomic works
     // on the 32-bit word it shares with the neighbouring wave's (counts stay below 2^16,
     // so nothing carries over).
     u32* pairs = reinterpret_cast<u32*>(h) + (wave >> 1);
     const int half = (wave & 1) * 16;
 #pragma unroll
+    for (int r = 0; r < ITEMS; ++r) wd[r] = words[wave_first + r * kWave + lane];
+#pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
-      if ((u32)r < items) {
-        wd[r] = words[wave_first + r * kWave + lane];
-        const u32 d = (u32)(wd[r] >> bit) & (kRadix - 1);
-        const u64 same = match_mask(d, true);
+      const bool on = (u32)r < items;
+      const u32 d = (u32)(wd[r] >> bit) & (kRadix - 1);
+      u32 rank;
+      if (ORDERED) {      // (sort.hpp: digit_rank)
+        rank = (atomicAdd(pairs + (WAVES / 2) * d, on ? 1u << half : 0u) >> half) & 0xFFFFu;
+      } else {
+        const u64 same = match_mask(d, on);
         const u32 before = __popcll(same & lt);
         u32 old = 0;
         if (before == 0) old = atomicAdd(pairs + (WAVES / 2) * d, (u32)__popcll(same) << half);
-        old = __shfl(old, __ffsll((unsigned long long)same) - 1, kWave);
-        rank[r] = ((old >> half) & 0xFFFFu) + before;
+        old = __shfl(old, same ? __ffsll((unsigned long long)same) - 1 : 0, kWave);
+        rank = ((old >> half) & 0xFFFFu) + before;
       }
+      wd[r] = (wd[r] & 0xFFFFFFFFFFFFull) | ((u64)rank << 48);
     }
     __syncthreads();
     if (wave == 0) {
@@ -119,12 +138,25 @@ __device__ __forceinline__ void lds_radix_sort(u64* words, u32 cnt, int first_bi
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
-      if ((u32)r < items) {
-        const u32 d = (u32)(wd[r] >> bit) & (kRadix - 1);
-        words[h[WAVES * d + wave] + rank[r]] = wd[r];
-      }
+      const u32 base = h[WAVES * ((u32)(wd[r] >> bit) & (kRadix - 1)) + wave];
+      words[(u32)r < items ? base + (u32)(wd[r] >> 48) : spare] = wd[r] & 0xFFFFFFFFFFFFull;
     }
     __syncthreads();
+  }
+}
+
+// The same for any cnt <= THREADS * MAX_ITEMS, with as few rounds as cnt needs (`words` holds
+// THREADS * MAX_ITEMS words).
+template <int THREADS, int MAX_ITEMS, bool ORDERED>
+__device__ __forceinline__ void lds_radix_sort_any(u64* words, u32 cnt, int first_bit, int n_pass,
+                                                   uint16_t* hist) {
+  static_assert(MAX_ITEMS == 8, "one case per number of rounds");
+  switch ((cnt + THREADS - 1) / THREADS) {
+    case 0: case 1: case 2: lds_radix_sort<THREADS, 2, ORDERED>(words, cnt, first_bit, n_pass, hist); break;
+    case 3: case 4: lds_radix_sort<THREADS, 4, ORDERED>(words, cnt, first_bit, n_pass, hist); break;
+    case 5: lds_radix_sort<THREADS, 5, ORDERED>(words, cnt, first_bit, n_pass, hist); break;
+    case 6: lds_radix_sort<THREADS, 6, ORDERED>(words, cnt, first_bit, n_pass, hist); break;
+    default: lds_radix_sort<THREADS, 8, ORDERED>(words, cnt, first_bit, n_pass, hist); break;
   }
 }
 
@@ -203,57 +235,6 @@ __device__ void slow_sort_region(const u64* skeys, const u64* spay, u64* ka, u64
   *pres = pc;
 }
 
-// ---- regions ---------------------------------------------------------------------------
-// A region may start where the bucket id changes, or anywhere inside a heavy key's
-// bucket.  border(p0) = the first such position >= p0, n if there is none; region c is
-// [border(c * kChunkSpan), border((c + 1) * kChunkSpan)), border(0) = 0.  Both borders
-// are looked for at once, half the block each, kBorderWindow positions per round.
-constexpr u32 kBorderWindow = kChunkThreads;     // positions per border per round
-
-__device__ __forceinline__ bool is_border(const u64* __restrict__ skeys, u32 p, u32 p0,
-                                          const HeavyLds& hv) {
-  bool heavy, heavy_prev;
-  const u32 id = bucket_id(skeys[p], hv, &heavy);
-  const u32 id_prev = bucket_id(skeys[p - 1], hv, &heavy_prev);
-  return id != id_prev || (p == p0 && heavy);
-}
-
-// s_border[0] / [1] (LDS) must hold ~0u for a border still to be found, else its value.
-__device__ void find_borders(const u64* __restrict__ skeys, u32 n, u32 p0_lo, u32 p0_hi,
-                             const HeavyLds& hv, u32* s_border) {
-  const u32 half = threadIdx.x / (kChunkThreads / 2);          // which border this thread serves
-  const u32 t = threadIdx.x % (kChunkThreads / 2);
-  const u32 p0 = half ? p0_hi : p0_lo;
-  for (u32 round = 0;; ++round) {
-    const bool open = s_border[half] == ~0u;
-    __syncthreads();
-    if (open) {
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        const u32 p = p0 + round * kBorderWindow + k * (kChunkThreads / 2) + t;
-        if (p < n && is_border(skeys, p, p0, hv)) atomicMin(&s_border[half], p);
-      }
-    }
-    __syncthreads();
-    bool done = true;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const u32 q0 = h ? p0_hi : p0_lo;
-      if (s_border[h] == ~0u) {
-        if ((u64)q0 + (u64)(round + 1) * kBorderWindow >= n) {
-          __syncthreads();                 // every thread has read the ~0u
-          if (threadIdx.x == 0) s_border[h] = n;
-          __syncthreads();
-        } else {
-          done = false;
-        }
-      }
-    }
-    if (done) break;
-  }
-  __syncthreads();
-}
-
 template <int ITEMS>
 struct ChunkLds {
   union {
@@ -262,14 +243,12 @@ struct ChunkLds {
     SlowLds slow;
   };
   uint16_t hist[kLdsSortHist];
-  HeavyLds hv;
   u32 scratch[kChunkWaves + 1];
-  u32 s_chunk, s_earlier, s_flag;
-  u32 s_border[2];
+  u32 s_chunk, s_earlier;
   unsigned long long s_or;
 };
 
-// Cross-region head counts (grouped status words, sort.cuh).  A region publishes its
+// Cross-region head counts (grouped status words, sort.hpp).  A region publishes its
 // number of group heads as soon as it knows it; the last region of a group then also
 // publishes the group's total.  Wave 0 only; the other waves go on.
 __device__ __forceinline__ void publish_heads(u32 chunk, u32 heads, u32 group, u32 epoch,
@@ -305,42 +284,6 @@ __device__ __forceinline__ u32 heads_before(u32* s_earlier, u32 chunk, u32 group
   }
   __syncthreads();
   return *s_earlier;
-}
-
-// Number of distinct keys among the thread block's keys (key[r] valid for r < items and
-// r * THREADS + tid < cnt), counted with a hash set of `slots` 64-bit words in LDS.
-// Contains barriers; `table` is free again afterwards.
-template <int ITEMS>
-__device__ __forceinline__ u32 count_distinct(const u64* key, u32 items, u32 cnt, u64* table,
-                                              u32* scratch) {
-  constexpr int kChunkItems = ITEMS;
-  constexpr u32 kCountSlots = kChunkThreads * ITEMS;
-  const u32 tid = threadIdx.x;
-#pragma unroll
-  for (int r = 0; r < kChunkItems; ++r) table[r * kChunkThreads + tid] = ~0ull;
-  __syncthreads();
-  u32 fresh = 0;
-#pragma unroll
-  for (int r = 0; r < kChunkItems; ++r) {
-    const u32 p = r * kChunkThreads + tid;
-    if ((u32)r < items && p < cnt && key[r] != ~0ull) {
-      const u64 k = key[r];
-      // the keys of a region share their leading bits: hash the low half
-      u32 slot = (u32)(((u64)((u32)k * 0x9E3779B1u) * kCountSlots) >> 32);
-      for (u32 step = 0; step < kCountSlots; ++step) {
-        unsigned long long* cell = reinterpret_cast<unsigned long long*>(table + slot);
-        u64 seen = *reinterpret_cast<volatile u64*>(cell);
-        if (seen == ~0ull) seen = atomicCAS(cell, ~0ull, (unsigned long long)k);
-        if (seen == ~0ull) { ++fresh; break; }
-        if (seen == k) break;
-        slot = slot + 1 == kCountSlots ? 0 : slot + 1;
-      }
-    }
-  }
-  u32 total;
-  (void)block_excl_sum<kChunkThreads>(fresh, scratch, &total);
-  __syncthreads();
-  return total;
 }
 
 // A whole region the slow way: ordered in global memory, then walked.  Kept out of line
@@ -393,73 +336,46 @@ __device__ __forceinline__ void slow_region(const u64* skeys, const u64* spay, u
         seg_off[r] = j;
         if (key == kEmptyKey) raise_error(st, kErrReserved);
       }
-      inverse[(u32)pay & kIndexMask] = (i32)r;
-      bagperm[j] = min((u32)(pay >> 32), n_bags - 1) | (head ? 0x80000000u : 0u);
+      inverse[(u32)pay] = (i32)r;
+      bagperm[j] = min((u32)(pay >> 32), n_bags ? n_bags - 1 : 0u) | (head ? 0x80000000u : 0u);
     }
     rank += tile_heads;
   }
 }
 
-// Two keys of the region agreed in the bits [lo, hb) it was ordered by without being
-// equal: order by the bits below lo first, then (stable) by the bits above, so that all
-// 64 bits count.  Rare; out of line.
-template <int ITEMS>
-__device__ __forceinline__ void resort_all_bits(u64* words, uint16_t* hist, const u64* skeys, u32 start,
-                                             u32 cnt, int lo, u64 bit_mask, int top_pass) {
-  const u32 tid = threadIdx.x;
-  const u32 items = (cnt + kChunkThreads - 1) / kChunkThreads;
-#pragma unroll
-  for (int r = 0; r < ITEMS; ++r) {
-    const u32 p = r * kChunkThreads + tid;
-    if ((u32)r < items && p < cnt) words[p] = ((skeys[start + p] & ((1ull << lo) - 1)) << 16) | p;
-  }
-  __syncthreads();
-  lds_radix_sort<kChunkThreads, ITEMS>(words, cnt, 16, (lo + 7) / 8, hist);
-#pragma unroll
-  for (int r = 0; r < ITEMS; ++r) {
-    const u32 q = r * kChunkThreads + tid;
-    if ((u32)r < items && q < cnt) {
-      const u32 p = (u32)words[q] & 0xFFFFu;
-      words[q] = (((skeys[start + p] >> lo) & bit_mask) << 16) | p;
-    }
-  }
-  __syncthreads();
-  lds_radix_sort<kChunkThreads, ITEMS>(words, cnt, 16, top_pass, hist);
-}
-
 // skeys/spay: the pairs ordered by bucket id (payload = occurrence index | bag << 32),
-// read only; ka/pa and kb/pb: scratch of the same shape (only touched the slow way).
-template <int ITEMS>
+// read only; ka/pa and kb/pb: scratch of the same shape (only touched the slow way);
+// borders[0 .. n_regions]: the regions (region_borders).
+//
+// After the LDS sort a thread owns the sorted positions tid, tid + 512, ... of its region
+// (conflict-free LDS reads, coalesced writes); the rank of a position's key is the number
+// of group heads before it, counted with wave ballots per round of 512 positions and one
+// 64-entry scan over (round, wave).
+template <int ITEMS, bool ORDERED>
 __global__ void __launch_bounds__(kChunkThreads, 4)
-chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
-                u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
-                u32 max_heavy,
-                const HeavySet* __restrict__ heavy_set, u32* __restrict__ head_rows,
-                u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
-                u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
-                u32* __restrict__ bagperm, u32* __restrict__ seg_off, PullCtx* __restrict__ ctx,
-                TableState* __restrict__ st) {
-  constexpr int kChunkItems = ITEMS;
+region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
+                 u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
+                 const u32* __restrict__ borders, u32* __restrict__ head_rows,
+                 u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
+                 u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
+                 u32* __restrict__ bagperm, u32* __restrict__ seg_off, PullCtx* __restrict__ ctx,
+                 TableState* __restrict__ st) {
+  static_assert(ITEMS == kChunkWaves, "the (round, wave) head counts are scanned by one wave");
   constexpr u32 kChunkCap = kChunkThreads * ITEMS;
-  constexpr u32 kCountMax = kChunkCap * 3 / 4;      // beyond this the table of the distinct count is too full
   __shared__ ChunkLds<ITEMS> L;
-  const u32 tid = threadIdx.x;
-  if (tid == 0) L.s_chunk = atomicAdd(ticket, 1u);
-  load_heavy(L.hv, heavy_set, max_heavy);
-  if (tid == 0) L.hv.range = ctx->range;
+  const u32 tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
+  const u64 lt = lanemask_lt();
+  if (tid == 0) {
+    L.s_chunk = atomicAdd(ticket, 1u);
+    L.s_or = 0;
+  }
   __syncthreads();
   const u32 chunk = L.s_chunk;
   const u32 n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
   const bool last = chunk + 1 == n_chunks;
-  if (tid == 0) {
-    L.s_border[0] = chunk == 0 ? 0u : ~0u;
-    L.s_border[1] = last ? n : ~0u;
-    L.s_or = 0;
-  }
-  __syncthreads();
-  find_borders(skeys, n, chunk * kChunkSpan, (chunk + 1) * kChunkSpan, L.hv, L.s_border);
-  const u32 start = L.s_border[0], end = L.s_border[1];
+  const u32 start = borders[chunk], end = borders[chunk + 1];
   const u32 cnt = end - start;       // start <= end: both borders come from the same rule
+  const u32 bag_max = n_bags ? n_bags - 1 : 0;
 
   if (cnt > kChunkCap) {
     slow_region(skeys, spay, ka, pa, kb, pb, n, start, end, chunk, last, L.slow, L.scratch, &L.s_earlier,
@@ -469,20 +385,22 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
 
   // ---- the usual way: order the region in LDS ----
   const u32 items = (cnt + kChunkThreads - 1) / kChunkThreads;
-  const u64 key0 = cnt ? skeys[start] : 0;
-  u64 key[kChunkItems], pay[kChunkItems];
+  // loads behind the region's end repeat its last key (an empty region reads a key it does not use)
+  const u32 last_p = cnt ? start + cnt - 1 : min(start, n - 1);
+  const u64 key0 = skeys[min(start, last_p)];
+  u64 key[ITEMS];
   {
     // which key bits vary inside the region
     u64 diff = 0;
 #pragma unroll
-    for (int r = 0; r < kChunkItems; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
       const u32 p = r * kChunkThreads + tid;
-      key[r] = ((u32)r < items && p < cnt) ? skeys[start + p] : key0;
+      key[r] = skeys[min(start + p, last_p)];
       diff |= key[r] ^ key0;
     }
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) diff |= __shfl_xor(diff, d, kWave);
-    if ((tid & (kWave - 1)) == 0 && diff) atomicOr(&L.s_or, (unsigned long long)diff);
+    if (lane == 0 && diff) atomicOr(&L.s_or, (unsigned long long)diff);
   }
   __syncthreads();
   const u64 vary = L.s_or;
@@ -491,14 +409,13 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
   const int n_bits = hb - lo;
   const u64 bit_mask = (1ull << n_bits) - 1;                  // bits above hb are dropped: all equal
   const int top_pass = (n_bits + 7) / 8;
-  // The number of group heads is published before the sort, so that no later region has
-  // to wait for this one's sort: it is the number of distinct keys, less one if the
-  // region starts inside a heavy key's bucket whose earlier part belongs to the region before.
-  const bool first_continues = cnt && start > 0 && skeys[start - 1] == key0;
+  // the key before the region: a region that starts inside a heavy key's bucket continues
+  // that key's group
+  const u64 key_before = start > 0 ? skeys[start - 1] : 0;
   if (hb == 0) {
     // One key only (part of a heavy key's bucket, typically), or nothing: the region is
     // in order as it stands, its pairs are read in place.
-    const u32 n_heads = cnt && !first_continues ? 1u : 0u;
+    const u32 n_heads = cnt && !(start > 0 && key_before == key0) ? 1u : 0u;
     publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
     const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
     if (last && tid == 0) { ctx->n_unique = earlier + n_heads; seg_off[earlier + n_heads] = n; }
@@ -509,116 +426,139 @@ chunk_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64
       if (key0 == kEmptyKey) raise_error(st, kErrReserved);
     }
 #pragma unroll
-    for (int r = 0; r < kChunkItems; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
       const u32 p = r * kChunkThreads + tid;
       if ((u32)r < items && p < cnt) {
         const u64 pay = spay[start + p];
-        bagperm[start + p] = min((u32)(pay >> 32), n_bags - 1) | (p == 0 && n_heads ? 0x80000000u : 0u);
-        inverse[(u32)pay & kIndexMask] = (i32)rank;
+        bagperm[start + p] = min((u32)(pay >> 32), bag_max) | (p == 0 && n_heads ? 0x80000000u : 0u);
+        inverse[(u32)pay] = (i32)rank;
       }
     }
     return;
   }
-  const bool early = cnt <= kCountMax;
-  u32 n_heads = 0;
-  if (early) {
-    const u32 distinct = count_distinct<ITEMS>(key, items, cnt, L.words, L.scratch);
-    n_heads = distinct - (first_continues ? 1u : 0u);
-    publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
-  }
 
-  u64 prev_key = 0;
-  const u32 j0 = tid * items;          // this thread's run of sorted positions
-  bool mixed = false;
-  for (int attempt = 0; attempt < 2; ++attempt) {
-    if (attempt == 0) {
+  // The sorted words stay in LDS to the end: sorted position j holds the place (inside the
+  // region) of its pair in the low 16 bits.  Stage 0 orders by the bits [lo, hb).  If two
+  // different keys then agree in all of those bits (rare), stage 1 orders by the bits below lo
+  // and stage 2, stable, by [lo, hb) again, so that all 64 bits count.  One sort loop serves
+  // all stages.  Afterwards the rounds are taken four at a time, so that few gathered keys
+  // and payloads are in registers at once.
+  u32 head_bits = 0;       // bit k: the key at sorted position k * 512 + tid differs from the key before it
+  const u32 last_j = cnt - 1;          // (cnt > 0 here) loads behind the region's end repeat its last pair
 #pragma unroll
-      for (int r = 0; r < kChunkItems; ++r) {
-        const u32 p = r * kChunkThreads + tid;
-        key[r] = (((key[r] >> lo) & bit_mask) << 16) | p;     // from here on: the word
+  for (int r = 0; r < ITEMS; ++r) {
+    const u32 q = r * kChunkThreads + tid;
+    if (q < cnt) L.words[q] = (((key[r] >> lo) & bit_mask) << 16) | q;
+  }
+  for (int stage = 0; stage < 3; ++stage) {
+    if (stage == 1) {
+#pragma unroll 1
+      for (int r = 0; r < ITEMS; ++r) {
+        const u32 q = r * kChunkThreads + tid;
+        if (q < cnt) L.words[q] = ((skeys[start + q] & ((1ull << lo) - 1)) << 16) | q;
       }
-      __syncthreads();       // the words replace the table of the distinct count
-#pragma unroll
-      for (int r = 0; r < kChunkItems; ++r) {
-        const u32 p = r * kChunkThreads + tid;
-        if ((u32)r < items && p < cnt) L.words[p] = key[r];
+    } else if (stage == 2) {
+#pragma unroll 1
+      for (int r = 0; r < ITEMS; ++r) {
+        const u32 q = r * kChunkThreads + tid;
+        if (q < cnt) {
+          const u32 place = (u32)L.words[q] & 0xFFFFu;
+          L.words[q] = (((skeys[start + place] >> lo) & bit_mask) << 16) | place;
+        }
       }
-      __syncthreads();
-      lds_radix_sort<kChunkThreads, kChunkItems>(L.words, cnt, 16, top_pass, L.hist);
-    } else {
-      resort_all_bits<ITEMS>(L.words, L.hist, skeys, start, cnt, lo, bit_mask, top_pass);
     }
-    // sorted position j0 + k -> its pair
-    u64 prev_word = ~0ull;
-    if (j0 > 0 && j0 < cnt) {
-      prev_word = L.words[j0 - 1];
-      prev_key = skeys[start + ((u32)prev_word & 0xFFFFu)];
-    } else if (j0 == 0 && start > 0 && cnt) {
-      prev_key = skeys[start - 1];
-    }
+    __syncthreads();
+    lds_radix_sort_any<kChunkThreads, ITEMS, ORDERED>(L.words, cnt, 16, stage == 1 ? (lo + 7) / 8 : top_pass, L.hist);
+    if (stage == 1) continue;
     bool bad = false;
+    head_bits = 0;
 #pragma unroll
-    for (int k = 0; k < kChunkItems; ++k) {
-      const u32 j = j0 + k;
-      if ((u32)k < items && j < cnt) {
-        const u64 w = L.words[j];
-        const u32 p = (u32)w & 0xFFFFu;
-        key[k] = skeys[start + p];
-        pay[k] = spay[start + p];
-        const u64 pk = k ? key[k - 1] : prev_key;
-        const u64 pw = k ? L.words[j - 1] : prev_word;
-        if (j > 0 && (pw >> 16) == (w >> 16) && pk != key[k]) bad = true;
+    for (int k0 = 0; k0 < ITEMS; k0 += 4) {
+      if ((u32)k0 >= items) break;       // block-uniform
+      u64 word[4], skey[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) word[q] = L.words[min((k0 + q) * kChunkThreads + tid, last_j)];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) skey[q] = skeys[start + ((u32)word[q] & 0xFFFFu)];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const u32 j = (k0 + q) * kChunkThreads + tid;
+        // the pair at the sorted position before: the neighbouring lane's, or (lane 0) looked up
+        u64 prev_key = __shfl_up(skey[q], 1, kWave);
+        u64 prev_word = __shfl_up(word[q], 1, kWave);
+        if (lane == 0) {
+          if (j == 0) {
+            prev_word = ~0ull;
+            prev_key = key_before;
+          } else if (j < cnt) {
+            prev_word = L.words[j - 1];
+            prev_key = skeys[start + ((u32)prev_word & 0xFFFFu)];
+          }
+        }
+        if (j < cnt) {
+          const bool differs = skey[q] != prev_key;
+          if (start + j == 0 || differs) head_bits |= 1u << (k0 + q);
+          if (j > 0 && differs && (prev_word >> 16) == (word[q] >> 16)) bad = true;
+        }
       }
     }
-    mixed = __syncthreads_or(bad && lo > 0 && attempt == 0);
-    if (!mixed) break;
+    if (!__syncthreads_or(bad && lo > 0 && stage == 0)) break;
   }
 
-  bool head[kChunkItems];
-  u32 heads = 0;
+  // heads before each of this thread's positions: per round a wave ballot, and one scan over
+  // the (round, wave) counts in the order of the positions
+  u32 my_count = 0;       // lane k of wave w: heads in round k of wave w
 #pragma unroll
-  for (int k = 0; k < kChunkItems; ++k) {
-    const u32 j = j0 + k;
-    head[k] = false;
-    if ((u32)k < items && j < cnt) {
-      const u64 pk = k ? key[k - 1] : prev_key;
-      head[k] = (start + j == 0) || key[k] != pk;
-      heads += head[k] ? 1u : 0u;
-    }
+  for (int k = 0; k < ITEMS; ++k) {
+    const u64 m = __ballot((head_bits >> k) & 1u);
+    if (lane == (u32)k) my_count = (u32)__popcll(m);
   }
-  // the bags, back in sorted order (does not need the ranks: before the wait below)
-  __syncthreads();        // every thread has read its words: L.out may overwrite them
-#pragma unroll
-  for (int k = 0; k < kChunkItems; ++k) {
-    const u32 j = j0 + k;
-    // clamped: whatever the offsets said, the push must stay inside the gradient buffer
-    if ((u32)k < items && j < cnt)
-      L.out[j] = min((u32)(pay[k] >> 32), n_bags - 1) | (head[k] ? 0x80000000u : 0u);
+  u32* counts = reinterpret_cast<u32*>(L.hist);      // [round][wave], then their exclusive prefix
+  if (lane < (u32)ITEMS) counts[lane * kChunkWaves + wave] = my_count;
+  __syncthreads();
+  if (wave == 0) {
+    const u32 c = counts[lane];
+    const u32 incl = wave_incl_sum(c);
+    counts[lane] = incl - c;
+    if (lane == kWave - 1) L.scratch[0] = incl;
   }
   __syncthreads();
+  const u32 total = L.scratch[0];
+  publish_heads(chunk, total, group, epoch, head_rows, head_groups, ctx);
+
+  // the pairs' payloads; the bags go out in sorted order (before the wait below)
+  u32 idx[ITEMS];
+  {
+    u64 pay[ITEMS];
 #pragma unroll
-  for (int r = 0; r < kChunkItems; ++r) {
-    const u32 p = r * kChunkThreads + tid;
-    if ((u32)r < items && p < cnt) bagperm[start + p] = L.out[p];
+    for (int k = 0; k < ITEMS; ++k)
+      pay[k] = spay[start + ((u32)L.words[min(k * kChunkThreads + tid, last_j)] & 0xFFFFu)];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+      const u32 j = k * kChunkThreads + tid;
+      idx[k] = (u32)pay[k];
+      // clamped: whatever the offsets said, the push must stay inside the gradient buffer
+      if (j < cnt)
+        bagperm[start + j] = min((u32)(pay[k] >> 32), bag_max) | (((head_bits >> k) & 1u) ? 0x80000000u : 0u);
+    }
   }
-  u32 total;
-  const u32 before = block_excl_sum<kChunkThreads>(heads, L.scratch, &total);
-  if (early && total != n_heads && tid == 0) ctx->sort_error = 1;     // never expected
-  if (!early) publish_heads(chunk, total, group, epoch, head_rows, head_groups, ctx);
   const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
   if (last && tid == 0) { ctx->n_unique = earlier + total; seg_off[earlier + total] = n; }
-  u32 rank = earlier + before;         // heads before this thread's first position
 #pragma unroll
-  for (int k = 0; k < kChunkItems; ++k) {
-    const u32 j = j0 + k;
-    if ((u32)k < items && j < cnt) {
-      if (head[k]) {
-        uniq[rank] = key[k];
+  for (int k = 0; k < ITEMS; ++k) {
+    const u32 j = k * kChunkThreads + tid;
+    const bool head = (head_bits >> k) & 1u;
+    const u64 m = __ballot(head);
+    if (j < cnt) {
+      // rank of this pair's key: heads at or before its position, less one
+      const u32 rank = earlier + counts[k * kChunkWaves + wave] + (u32)__popcll(m & lt) + (head ? 1u : 0u) - 1u;
+      if (head) {
+        const u64 key_j = skeys[start + ((u32)L.words[j] & 0xFFFFu)];
+        uniq[rank] = key_j;
         seg_off[rank] = start + j;
-        if (key[k] == kEmptyKey) raise_error(st, kErrReserved);
-        ++rank;
+        if (key_j == kEmptyKey) raise_error(st, kErrReserved);
       }
-      inverse[(u32)pay[k] & kIndexMask] = (i32)(rank - 1);
+      inverse[idx[k]] = (i32)rank;
     }
   }
 }

@@ -38,13 +38,13 @@ struct TableState {
   u32 miss_shard[kCountShards];
   u32 made_shard[kCountShards];
   u32 miss_overflow;            // the list of missing keys did not fit: scan instead
-  u32 pad2;
+  u32 probe_bad;                // result word of probe_lane_order (written once, at creation)
 };
 
 // Where a mini-batch's keys lie, estimated from a sample of them (sort_prepare).  The
 // dedup orders keys by rel = clamp(key - lo, 0, span) instead of by the key itself, which
 // is the same order, but raw ids that all share their leading bits spread over the
-// buckets / digits like hashed keys do (sort.cuh: range_rel, natural_bucket).
+// buckets / digits like hashed keys do (sort.hpp: range_rel, natural_bucket).
 struct KeyRange {
   u64 lo;
   u64 span;      // largest rel
@@ -70,7 +70,7 @@ struct PullCtx {
   u32 pad;
 };
 
-// Keys that make up a large share of a mini-batch (bucket.cuh).  HeavySet: ascending,
+// Keys that make up a large share of a mini-batch (bucket.hpp).  HeavySet: ascending,
 // padded with all-ones.  HeavyRaw: the keys the last lookup saw often, in arrival
 // order; only a hint, readers cope with any content.
 constexpr int kMaxHeavy = 1023;

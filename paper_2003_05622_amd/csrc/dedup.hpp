@@ -1,5 +1,5 @@
 // Key dedup, part 2, plain form (a table's first dedups and very large ones; the usual
-// form is in bucket.cuh): from the occurrences sorted by the top bits of their keys
+// form is in bucket.hpp): from the occurrences sorted by the top bits of their keys
 // (skeys[j], spay[j]; payload = occurrence index | bag << 32) to
 //   uniq[U]      ascending unique keys
 //   inverse[N]   rank of each occurrence's key among them
@@ -19,8 +19,8 @@
 //                   evidence (REDO instance).
 #pragma once
 
-#include "common.cuh"
-#include "sort.cuh"
+#include "common.hpp"
+#include "sort.hpp"
 
 namespace hps {
 
@@ -166,7 +166,7 @@ fix_mixed_runs(u64* __restrict__ skeys, u64* __restrict__ sidx, u64* __restrict_
 
 // Heads of the key groups, their ranks, and every output of the dedup.
 //   head_rows [n_tiles] and head_groups [n_groups]: status words of the tiles' and
-//   tile groups' head counts (see sort.cuh), ticket: tile tickets
+//   tile groups' head counts (see sort.hpp), ticket: tile tickets
 //   bagperm[j] = bag of the occurrence at sorted position j, bit 31 set on group heads
 // REDO = false: the first instance; counts evidence.  REDO = true: the instance after
 // fix_mixed_runs; returns at once unless there was evidence.
@@ -210,7 +210,7 @@ unique_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u32 n,
     const u64 pay = lds_pay[threadIdx.x * kHeadItems + k];
     idx[k] = (u32)pay;
     // clamped: whatever the offsets said, the push must stay inside the gradient buffer
-    bag[k] = min((u32)(pay >> 32), n_bags - 1);
+    bag[k] = min((u32)(pay >> 32), n_bags ? n_bags - 1 : 0u);
   }
 #pragma unroll
   for (int k = 0; k < kHeadItems; ++k) {

@@ -6,19 +6,21 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
 
-#include "common.cuh"
-#include "bucket.cuh"
-#include "dedup.cuh"
-#include "pool.cuh"
-#include "push.cuh"
-#include "sort.cuh"
-#include "table.cuh"
+#include "common.hpp"
+#include "bucket.hpp"
+#include "dedup.hpp"
+#include "partition.hpp"
+#include "pool.hpp"
+#include "push.hpp"
+#include "sort.hpp"
+#include "table.hpp"
 
 using namespace hps;
 
@@ -70,8 +72,9 @@ struct ContextLayout {
 };
 
 struct WorkspaceLayout {
-  size_t keys_a, keys_b, keys_c, idx_a, idx_b, idx_c, id16, heavy_raw, ghist, tickets, tile_rows, group_rows, head_rows,
-      head_groups, evidence, bag_of, miss_list, med_list, long_list, chunk_items, partials, total;
+  size_t keys_a, keys_b, keys_c, idx_a, idx_b, idx_c, id16, dig, part_hist, part_tot, borders, heavy_raw, ghist,
+      tickets, tile_rows, group_rows, head_rows, head_groups, evidence, bag_of, miss_list, med_list, long_list,
+      chunk_items, partials, total;
   ContextLayout c[2];
   uint64_t med_cap, max_long, max_items, sort_tiles, head_tiles, shard_cap;
 };
@@ -92,7 +95,11 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
   L.idx_b = o;       o = align_up(o + n1 * 8);
   L.idx_c = o;       o = align_up(o + n1 * 8);
   L.id16 = o;        o = align_up(o + n1 * 2);    // bucket id of every occurrence
-  // from here to `evidence`: cleared at creation, never again (see sort.cuh)
+  L.dig = o;         o = align_up(o + n1 + 4);    // the ids' high bytes, ordered by the low bytes
+  L.part_hist = o;   o = align_up(o + (size_t)kRadix * L.sort_tiles * 4);   // [digit][tile] counts of a pass
+  L.part_tot = o;    o = align_up(o + kRadix * 4);
+  L.borders = o;     o = align_up(o + (n1 / kRegionSpan + 3) * 4);
+  // from here to `evidence`: cleared at creation, never again (see sort.hpp)
   L.ghist = o;       o = align_up(o + 2 * (size_t)kHistWords * 4);
   L.tickets = o;     o = align_up(o + (kMaxPasses + 2) * 4);
   L.tile_rows = o;   o = align_up(o + (size_t)kMaxPasses * L.sort_tiles * kRadix * 4);
@@ -162,7 +169,7 @@ SortPlan bucket_plan(uint64_t n) {
 // Plain form.  How many 8-bit digits to sort for n occurrences: enough that two different
 // keys rarely agree in all sorted bits.  With b sorted bits about n^2 / 2^(b+1) pairs of
 // distinct hashed keys collide; b >= 2*log2(n) - 2 keeps that near one in a few
-// batches, and every collision is repaired anyway (dedup.cuh).
+// batches, and every collision is repaired anyway (dedup.hpp).
 // all_bits: every bit of the keys is sorted (eight passes), whatever the keys look like.
 SortPlan sort_plan(uint64_t n, bool all_bits) {
   SortPlan p;
@@ -207,8 +214,10 @@ struct hps_table {
   bool mean_pooling;        // bags are averaged instead of summed (hps_set_pooling)
   uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
   int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
+  bool ordered_rank;   // the GPU's LDS atomics serve a wave's lanes in lane order (sort.hpp: digit_rank)
   uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
-  // Pinned host word the lookups report into (table.cuh: OftenLists::report).  When a dedup
+  uint64_t plain_serial;   // ... of them in the plain form
+  // Pinned host word the lookups report into (table.hpp: OftenLists::report).  When a dedup
   // of the bucket form had to order much of its input the slow way (keys bunched inside
   // their range, or frequent keys that change from one mini-batch to the next), the
   // following dedups take the plain form, which copes with both: for kPlainHold dedups, and
@@ -219,7 +228,7 @@ struct hps_table {
   uint64_t plain_until;     // dedups numbered below this take the plain form
   uint64_t n_fallbacks;     // times plain_until was pushed out
   // The same for the plain form itself: after a dedup whose keys agreed in all the bits the
-  // plain form sorts by (table.cuh: kReportMixed), the following ones sort by all 64 bits.
+  // plain form sorts by (table.hpp: kReportMixed), the following ones sort by all 64 bits.
   uint32_t full_strikes;
   uint64_t full_until;
   uint64_t n_full_fallbacks;
@@ -346,53 +355,85 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
     u64* kalt = t->w<u64>(L.keys_b);
     u64* pcur = t->w<u64>(L.idx_a);
     u64* palt = t->w<u64>(L.idx_b);
-    u32* ghist = t->w<u32>(L.ghist) + (t->serial & 1) * kHistWords;
-    u32* ghist_next = t->w<u32>(L.ghist) + ((t->serial + 1) & 1) * kHistWords;
     u32* tickets = t->w<u32>(L.tickets);
-    // the most recent list of frequent keys that is certainly complete (common.cuh)
-    const HeavySet* heavy =
-        &t->w<HeavyRing>(L.heavy_raw)->set[(t->lookup_serial + kHeavyRing - 1) % kHeavyRing];
     const unsigned n_tiles = (n + kSortTile - 1) / kSortTile;
-    const unsigned hist_blocks = n_tiles < 768 ? n_tiles : 768;
     const unsigned bag_blocks = grid_for(d_offsets ? n_bags : n, kPrepThreads, 256);
-    sort_prepare<<<hist_blocks + bag_blocks, kPrepThreads, 0, s>>>(
-        d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, n_bags,
-        t->w<i32>(L.bag_of), heavy, t->w<uint16_t>(L.id16), hist_blocks);
-    for (int p = 0; p < plan.n_pass; ++p) {
-      u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
-      u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
-      const int shift = p * kRadixBits;     // within the key's sorted prefix
-#define HPS_PASS(FIRST, IDS, KIN, PIN, KOUT, POUT)                                              \
-  onesweep_pass<FIRST, IDS><<<n_tiles, kSortThreads, 0, s>>>(                                  \
-      KIN, PIN, t->w<i32>(L.bag_of), KOUT, POUT, n, shift, ghist + p * kRadix, tile_rows,      \
-      group_rows, plan.group, tickets + p, epoch, ctx, t->w<uint16_t>(L.id16))
-      if (p == 0) {
-        if (buckets) HPS_PASS(true, true, d_keys, nullptr, kcur, pcur);
-        else HPS_PASS(true, false, d_keys, nullptr, kcur, pcur);
-      } else {
-        if (buckets) HPS_PASS(false, true, kcur, pcur, kalt, palt);
-        else HPS_PASS(false, false, kcur, pcur, kalt, palt);
+    if (buckets) {
+      // the most recent list of frequent keys that is certainly complete (common.hpp)
+      const HeavySet* heavy =
+          &t->w<HeavyRing>(L.heavy_raw)->set[(t->lookup_serial + kHeavyRing - 1) % kHeavyRing];
+      const unsigned count_blocks = n_tiles < 1024 ? n_tiles : 1024;
+      const unsigned n_regions = (n + kRegionSpan - 1) / kRegionSpan;
+      const u32 region_group = tile_group(n_regions);
+      u32* hist = t->w<u32>(L.part_hist);
+      u32* tot = t->w<u32>(L.part_tot);
+      uint8_t* dig = plan.n_pass == 2 ? t->w<uint8_t>(L.dig) : nullptr;
+      bucket_count<<<count_blocks + bag_blocks, kPrepThreads, 0, s>>>(
+          d_keys, n, plan, tickets, ctx, d_offsets, n_bags, t->w<i32>(L.bag_of), heavy,
+          t->w<uint16_t>(L.id16), hist, n_tiles, count_blocks);
+      // (the first scan also clears the status words of region_sort_emit: one per region and
+      // one per group of regions, laid out back to back)
+      scan_tiles<<<kRadix, kPartThreads, 0, s>>>(hist, n_tiles, tot, t->w<u32>(L.head_rows),
+                                                 (u32)((L.evidence - L.head_rows) / 4));
+#define HPS_SCATTER(FIRST, ...)                                                          \
+  do {                                                                                  \
+    if (t->ordered_rank) scatter_pass<FIRST, true><<<n_tiles, kPartThreads, 0, s>>>(__VA_ARGS__);  \
+    else scatter_pass<FIRST, false><<<n_tiles, kPartThreads, 0, s>>>(__VA_ARGS__);      \
+  } while (0)
+      HPS_SCATTER(true, d_keys, nullptr, t->w<i32>(L.bag_of), t->w<uint16_t>(L.id16), nullptr, kcur, pcur,
+                  dig, n, hist, n_tiles, tot);
+      if (plan.n_pass == 2) {
+        digit_count<<<n_tiles, kPartThreads, 0, s>>>(dig, n, hist, n_tiles);
+        scan_tiles<<<kRadix, kPartThreads, 0, s>>>(hist, n_tiles, tot, nullptr, 0);
+        HPS_SCATTER(false, kcur, pcur, nullptr, nullptr, dig, kalt, palt, nullptr, n, hist, n_tiles, tot);
         u64* tk = kcur; kcur = kalt; kalt = tk;
         tk = pcur; pcur = palt; palt = tk;
       }
-#undef HPS_PASS
-    }
-    stage_mark(t, HPS_STAGE_SORT, s);
-    // a1: unique keys, ranks, grouping
-    stage_mark(t, HPS_STAGE_UNIQUE, s);
-    if (buckets) {
-      const unsigned n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
-#define HPS_CHUNKS(ITEMS)                                                                          \
-  chunk_sort_emit<ITEMS><<<n_chunks, kChunkThreads, 0, s>>>(                                       \
-      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n,                            \
-      plan.max_heavy, heavy,                                                                        \
-      t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), tile_group(n_chunks), tickets + kMaxPasses, \
-      epoch, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm),                 \
-      t->w<u32>(C.seg_off), ctx, t->view.st)
-      HPS_CHUNKS(kChunkItems);
-#undef HPS_CHUNKS
+      stage_mark(t, HPS_STAGE_SORT, s);
+      // a1: unique keys, ranks, grouping
+      stage_mark(t, HPS_STAGE_UNIQUE, s);
+      u32* borders = t->w<u32>(L.borders);
+      region_borders<<<(n_regions + 1 + kPartWaves - 1) / kPartWaves, kPartThreads, 0, s>>>(
+          kcur, n, n_regions, plan.max_heavy, heavy, ctx, borders);
+#undef HPS_SCATTER
+#define HPS_EMIT(ORDERED)                                                                          \
+  region_sort_emit<kChunkItems, ORDERED><<<n_regions, kChunkThreads, 0, s>>>(                      \
+      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, borders,                 \
+      t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), region_group, tickets + kMaxPasses, 1u,    \
+      n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), \
+      ctx, t->view.st)
+      if (t->ordered_rank) HPS_EMIT(true);
+      else HPS_EMIT(false);
+#undef HPS_EMIT
     } else {
-      // the second unique_emit only acts after a repair
+      // two sets of digit histograms: a plain dedup counts into one and clears the other for
+      // the next plain dedup
+      ++t->plain_serial;
+      u32* ghist = t->w<u32>(L.ghist) + (t->plain_serial & 1) * kHistWords;
+      u32* ghist_next = t->w<u32>(L.ghist) + ((t->plain_serial + 1) & 1) * kHistWords;
+      const unsigned hist_blocks = n_tiles < 768 ? n_tiles : 768;
+      sort_prepare<<<hist_blocks + bag_blocks, kPrepThreads, 0, s>>>(
+          d_keys, n, plan, ghist, ghist_next, tickets, ctx, d_offsets, n_bags, t->w<i32>(L.bag_of),
+          hist_blocks);
+      for (int p = 0; p < plan.n_pass; ++p) {
+        u32* tile_rows = t->w<u32>(L.tile_rows) + (size_t)p * L.sort_tiles * kRadix;
+        u32* group_rows = t->w<u32>(L.group_rows) + (size_t)p * (L.sort_tiles / kMinTileGroup + 1) * kRadix;
+        const int shift = p * kRadixBits;     // within the key's sorted prefix
+        if (p == 0) {
+          onesweep_pass<true><<<n_tiles, kSortThreads, 0, s>>>(
+              d_keys, nullptr, t->w<i32>(L.bag_of), kcur, pcur, n, shift, ghist + p * kRadix, tile_rows,
+              group_rows, plan.group, tickets + p, epoch, ctx);
+        } else {
+          onesweep_pass<false><<<n_tiles, kSortThreads, 0, s>>>(
+              kcur, pcur, t->w<i32>(L.bag_of), kalt, palt, n, shift, ghist + p * kRadix, tile_rows,
+              group_rows, plan.group, tickets + p, epoch, ctx);
+          u64* tk = kcur; kcur = kalt; kalt = tk;
+          tk = pcur; pcur = palt; palt = tk;
+        }
+      }
+      stage_mark(t, HPS_STAGE_SORT, s);
+      // a1: unique keys, ranks, grouping; the second unique_emit only acts after a repair
+      stage_mark(t, HPS_STAGE_UNIQUE, s);
       const unsigned head_tiles = (n + kHeadTile - 1) / kHeadTile;
       const u32 head_group = tile_group(head_tiles);
       u32* evidence = t->w<u32>(L.evidence);
@@ -453,6 +494,37 @@ static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, P
   a.kind = kind;
   a.ring = nullptr;
   a.ring_slot = 0;
+}
+
+// Whether the GPU's LDS atomics serve the lanes of one instruction in ascending lane order
+// (sort.hpp: digit_rank), measured once per device: 0 not yet, 1 yes, 2 no.  uses the table's (not yet
+// initialised) state block for the result; waits for the stream.  HPS_RANK=ballot / ordered overrides
+// the measurement (comparison runs, tests).
+static int g_lane_order[64];
+
+static bool lane_order_holds(TableState* st, hipStream_t s) {
+  static_assert(offsetof(TableState, miss_overflow) % 8 == 0 &&
+                    offsetof(TableState, probe_bad) == offsetof(TableState, miss_overflow) + 4,
+                "the two words are cleared as one");
+  u32* word = &st->probe_bad;
+  const char* force = std::getenv("HPS_RANK");
+  if (force && std::strcmp(force, "ballot") == 0) return false;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return false; }
+  int state = __atomic_load_n(&g_lane_order[dev], __ATOMIC_ACQUIRE);
+  if (state == 0) {
+    u32 bad = 1;
+    fill_u64<<<1, 64, 0, s>>>(reinterpret_cast<u64*>(&st->miss_overflow), 1, 0);
+    probe_lane_order<<<256, kSortThreads, 0, s>>>(64, word);
+    if (hipMemcpyAsync(&bad, word, sizeof(bad), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+      (void)hipGetLastError();
+      return false;
+    }
+    state = bad == 0 ? 1 : 2;
+    __atomic_store_n(&g_lane_order[dev], state, __ATOMIC_RELEASE);
+  }
+  return state == 1;
 }
 
 #define HPS_DISPATCH_LPR(lpr, CALL)            \
@@ -553,6 +625,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->timing_mask = 0;
   for (int i = 0; i < HPS_N_STAGES; ++i) t->ev_used[i] = 0;
   t->serial = 0;
+  t->plain_serial = 0;
   t->mean_pooling = false;
   t->lookup_serial = 0;
   t->report_seen = 0;
@@ -576,6 +649,7 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
+  t->ordered_rank = lane_order_holds(t->view.st, s);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);
   // look-back status words and digit histograms start at zero
   fill_u64<<<1024, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.bag_of - wl.ghist) / 8, 0);

@@ -7,8 +7,8 @@
 // then their rows.  Block 0 also books the rows the preceding insert created.
 #pragma once
 
-#include "common.cuh"
-#include "table.cuh"
+#include "common.hpp"
+#include "table.hpp"
 
 namespace hps {
 

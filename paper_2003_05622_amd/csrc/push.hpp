@@ -5,7 +5,7 @@
 // sorted position j.  The gradient of a sum-pooled bag reaches every occurrence
 // unchanged, so the gradient of key u is the sum of grads[bagperm[j]] over its
 // positions.  Keys are handled by how often they occur; the pull's lookup already
-// sorted the frequent ones into work lists (table.cuh, OftenLists):
+// sorted the frequent ones into work lists (table.hpp, OftenLists):
 //
 //   push_main   one launch, blocks take one of three roles:
 //                 short   a group of LPR lanes per key with at most kShortSeg
@@ -19,8 +19,8 @@
 // Every sum has a fixed shape, so results do not depend on scheduling.
 #pragma once
 
-#include "common.cuh"
-#include "table.cuh"
+#include "common.hpp"
+#include "table.hpp"
 
 namespace hps {
 
@@ -269,7 +269,7 @@ __global__ void __launch_bounds__(kPushThreads) push_main(TableView t, PushArgs 
   if (load_error(t.st) != 0) return;
   const u32 b = blockIdx.x;
   if (a.ring && b == gridDim.x - 1) {
-    // Not part of the push: the list of frequent keys the pull's lookup left (common.cuh) is
+    // Not part of the push: the list of frequent keys the pull's lookup left (common.hpp) is
     // put in order here, where it costs nothing -- the next dedup that reads it starts after
     // this push, and the push takes several times longer than this block.
     finalize_heavy(a.ring, a.ring_slot);

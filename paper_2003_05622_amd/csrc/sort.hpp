@@ -16,11 +16,11 @@
 // What the passes sort by comes in two forms.
 //   Bucket ids (by_id plans; the usual form): one or two passes by a 16-bit id made of the
 //   key's leading bits and its place among the heavy keys (bucket_id below); the rest of
-//   the ordering happens per region inside one workgroup (bucket.cuh).
+//   the ordering happens per region inside one workgroup (bucket.hpp).
 //   Key bits (plain plans): the top 8 * n_pass bits of the key's place in the range the
 //   mini-batch's keys span (for hashed keys: of the key).  Mini-batch keys are hashed
 //   feature ids, so these bits separate almost all distinct keys; the rare runs that
-//   still mix different keys are found and put right afterwards (dedup.cuh).  With
+//   still mix different keys are found and put right afterwards (dedup.hpp).  With
 //   eight passes every bit is sorted and nothing is left to put right.
 // Either way the dedup's result is exact for any input.
 //
@@ -36,7 +36,7 @@
 // the words each time the epoch wraps.
 #pragma once
 
-#include "common.cuh"
+#include "common.hpp"
 
 namespace hps {
 
@@ -58,7 +58,7 @@ constexpr int kHistWords = kHistShards * kMaxPasses * kRadix;   // one pull's hi
 
 // A wait for another workgroup's status word gives up after this long (100 MHz ticks: one
 // minute).  Nothing legitimate comes near: the slowest producer is a workgroup that sorts
-// one oversized bucket through global memory (bucket.cuh), seconds at the very worst.
+// one oversized bucket through global memory (bucket.hpp), seconds at the very worst.
 constexpr u64 kWaitTicks = 6000000000ull;
 constexpr u32 kRangeSamples = 2048;    // keys sampled for the key range (sort_prepare)
 constexpr u32 kEpochMod = 4095;        // epochs run 1..4095
@@ -134,7 +134,7 @@ __device__ __forceinline__ KeyRange make_range(u64 lo, u64 hi, const SortPlan& p
 
 // ---- bucket ids ---------------------------------------------------------------------
 // Keys that make up a large share of a mini-batch ("heavy" keys; found from a sample,
-// bucket.cuh) get buckets of their own, so that every other bucket stays small enough
+// bucket.hpp) get buckets of their own, so that every other bucket stays small enough
 // to be sorted inside one workgroup.  With the heavy keys h_0 < h_1 < ... the id of a
 // key is
 //     natural(key) + 2 * #{i : h_i < key} + (key is heavy ? 1 : 0),
@@ -278,17 +278,58 @@ __device__ __forceinline__ u64 match_mask(u32 d, bool valid) {
 
 // Rank of this lane's element among the wave's elements with the same digit, counted
 // over all calls so far: `counter` (LDS) holds the digit's running count for this wave.
-// The first lane of each group adds the group's size with ONE returning atomic and hands
-// the old value to the others by a shuffle, so consecutive calls do not wait for each
-// other (LDS executes a wave's operations in order; nothing has to come back before the
-// next call's atomic is issued).
+//
+// ORDERED = false: the lanes with the same digit are found with wave ballots; the first of
+// them adds the group's size with ONE returning atomic and hands the old value to the
+// others by a shuffle, so consecutive calls do not wait for each other (LDS executes a
+// wave's operations in order; nothing has to come back before the next call's atomic is
+// issued).  About fifty vector instructions per call.
+// ORDERED = true: every lane adds one with its own returning atomic and takes the old value
+// as its rank.  That is only the rank in lane order if the LDS serves the lanes of one
+// instruction that hit the same address in ascending lane order -- which the instruction
+// set manual does not promise, so the library measures it (probe_lane_order below, once per
+// GPU when the first table is created there) and uses this form only where it holds.
+template <bool ORDERED>
 __device__ __forceinline__ u32 digit_rank(u32* counter, u32 d, bool valid, u64 lt) {
+  if (ORDERED) return valid ? atomicAdd(counter, 1u) : 0u;
   const u64 same = match_mask(d, valid);
   const u32 before = __popcll(same & lt);
   u32 old = 0;
   if (valid && before == 0) old = atomicAdd(counter, (u32)__popcll(same));
   old = __shfl(old, same ? __ffsll((unsigned long long)same) - 1 : 0, kWave);
   return old + before;
+}
+
+// Counts, over `rounds` rounds of pseudo-random digits per wave (uniform digits, few distinct
+// digits, one digit only, one frequent digit, all distinct; all lanes or a random part of
+// them active), the lanes whose ORDERED rank differs from the ballot rank; adds the count to
+// *n_bad.  Two atomics per round, the second on top of the first's counts.
+__global__ void __launch_bounds__(kSortThreads)
+probe_lane_order(u32 rounds, u32* __restrict__ n_bad) {
+  __shared__ u32 cnt[kSortThreads / kWave][kRadix];
+  const u32 wave = threadIdx.x / kWave, lane = lane_id();
+  const u64 lt = lanemask_lt();
+  u32 bad = 0;
+  for (u32 r = 0; r < rounds; ++r) {
+    for (u32 d = lane; d < (u32)kRadix; d += kWave) cnt[wave][d] = 0;
+    const u64 h = mix64(((u64)blockIdx.x << 40) ^ ((u64)wave << 32) ^ ((u64)r << 8) ^ lane);
+    const u64 hw = mix64(((u64)blockIdx.x << 40) ^ ((u64)wave << 32) ^ r ^ 0xABCDEFull);   // the same in all lanes
+    const u32 mode = (u32)(hw % 6);
+    u32 d;
+    if (mode == 0) d = (u32)h & 255u;
+    else if (mode == 1) d = (u32)h & 3u;
+    else if (mode == 2) d = 7u;
+    else if (mode == 3) d = ((u32)h & 255u) < 200u ? 42u : (u32)(h >> 8) & 255u;
+    else if (mode == 4) d = lane;
+    else d = lane / 2;
+    const bool active = mode == 0 ? ((h >> 20) & 3) != 0 : true;
+    const u64 same = match_mask(d, active);
+    const u32 expect = __popcll(same & lt);
+    const u32 first = digit_rank<true>(&cnt[wave][d], d, active, lt);
+    const u32 second = digit_rank<true>(&cnt[wave][d], d, active, lt);
+    if (active && (first != expect || second != expect + (u32)__popcll(same))) ++bad;
+  }
+  if (bad) atomicAdd(n_bad, bad);
 }
 
 // Number of lanes of the wave (among `valid` ones) whose digit equals this lane's,
@@ -305,52 +346,96 @@ __device__ __forceinline__ void match_digit(u32 d, bool valid, u64 lt, u32* befo
   *count = __popcll(same);
 }
 
-// Histograms of every pass's digit over all keys (the first hist_blocks blocks, which
-// also reset what the passes need) and bag_of[i] (the other blocks, at least one: a wave
-// takes 64 bags at a time; bags of more than 8 occurrences are filled by the whole wave).
+// Resets of the pull context, shared by the first kernel of either dedup form.
+__device__ __forceinline__ void reset_ctx(PullCtx* ctx, u32 n, u32 by_id) {
+  if (threadIdx.x == 0) {
+    ctx->n_unique = 0;
+    ctx->n_long = 0;
+    ctx->n_chunk_items = 0;
+    ctx->n_evidence = 0;
+    ctx->sort_error = 0;
+    ctx->n_slow = 0;
+    ctx->n_slow_one_key = 0;
+    ctx->n_total = n;
+    ctx->by_id = by_id;
+  }
+  if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
+}
+
+// bag_of[i] = bag of occurrence i, by the blocks of a launch that are given this role:
+// `block` of `n_blocks`, kPrepThreads threads each.  A wave takes 64 bags at a time; bags of
+// more than 8 occurrences are filled by the whole wave.  offsets == nullptr: bag_of[i] = i.
+__device__ __forceinline__ void expand_bags(const i32* __restrict__ offsets, u32 n_bags, u32 n,
+                                            i32* __restrict__ bag_of, u32 block, u32 n_blocks) {
+  if (offsets == nullptr) {
+    for (u32 i = block * kPrepThreads + threadIdx.x; i < n; i += n_blocks * kPrepThreads)
+      bag_of[i] = (i32)i;
+    return;
+  }
+  const u32 wave_global = (block * kPrepThreads + threadIdx.x) / kWave;
+  const u32 n_waves = n_blocks * (kPrepThreads / kWave);
+  for (u32 b0 = wave_global * kWave; b0 < n_bags; b0 += n_waves * kWave) {
+    const u32 b = b0 + lane_id();
+    i32 lo = 0, hi = 0;
+    if (b < n_bags) { lo = offsets[b]; hi = offsets[b + 1]; }
+    lo = max(lo, 0);
+    hi = min(hi, (i32)n);          // never write outside bag_of, whatever the offsets say
+    const bool big = hi - lo > 8;
+    if (!big) for (i32 i = lo; i < hi; ++i) bag_of[i] = (i32)b;
+    u64 todo = __ballot(big);
+    while (todo) {
+      const int src = __ffsll((unsigned long long)todo) - 1;
+      todo &= todo - 1;
+      const i32 blo = __shfl(lo, src, kWave), bhi = __shfl(hi, src, kWave);
+      for (i32 i = blo + (i32)lane_id(); i < bhi; i += kWave) bag_of[i] = (i32)(b0 + src);
+    }
+  }
+}
+
+// Smallest and largest of kRangeSamples sampled keys, to every thread of the block (kPrepThreads
+// threads; contains barriers; s_lo / s_hi: kPrepThreads / kWave words of LDS each).  The samples
+// are kRangeSamples / 8 evenly spaced runs of 8 consecutive keys (a 64-byte line each, the first
+// and the last included), so that a wave's request is 8 lines and not 64: every block asks for
+// the same lines, and the caches serve requests, not bytes.
+__device__ __forceinline__ void sample_key_range(const u64* __restrict__ keys, u32 n, u64* s_lo,
+                                                 u64* s_hi) {
+  u64 lo = ~0ull, hi = 0;
+  const u32 n_samples = min(n, kRangeSamples);
+  const u32 n_lines = n >> 3;
+  for (u32 j = threadIdx.x; j < n_samples; j += kPrepThreads) {
+    const u32 at = n > kRangeSamples
+                       ? (u32)(((u64)(j >> 3) * (n_lines - 1)) / (kRangeSamples / 8 - 1)) * 8 + (j & 7)
+                       : j;
+    const u64 key = keys[at];
+    lo = min(lo, key);
+    hi = max(hi, key);
+  }
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    lo = min(lo, (u64)__shfl_xor((unsigned long long)lo, d, kWave));
+    hi = max(hi, (u64)__shfl_xor((unsigned long long)hi, d, kWave));
+  }
+  if (lane_id() == 0) { s_lo[threadIdx.x / kWave] = lo; s_hi[threadIdx.x / kWave] = hi; }
+}
+
+// First kernel of a plain-form dedup: histograms of every pass's digit over all keys (the
+// first hist_blocks blocks, which also reset what the passes need) and bag_of[i] (the other
+// blocks, at least one).
 //   ghist      [kHistShards][kMaxPasses][kRadix] of this pull (zero on entry), ghist_next the
 //              buffer the next pull will use (cleared here)
 //   tickets    [kMaxPasses + 2] tile tickets of the passes and of the two unique scans
-//   id16       by_id plans only: receives every key's bucket id (the first pass reads
-//              it, and hands the id's high byte on to the second inside the payload)
 // Every histogram block first works out the range of the keys from the same kRangeSamples
 // sampled keys (so all agree); block 0 leaves it in ctx->range for the later kernels.
 __global__ void __launch_bounds__(kPrepThreads)
 sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict__ ghist,
              u32* __restrict__ ghist_next, u32* __restrict__ tickets, PullCtx* __restrict__ ctx,
-             const i32* __restrict__ offsets, u32 n_bags, i32* __restrict__ bag_of,
-             const HeavySet* __restrict__ heavy_set, uint16_t* __restrict__ id16, u32 hist_blocks) {
+             const i32* __restrict__ offsets, u32 n_bags, i32* __restrict__ bag_of, u32 hist_blocks) {
   if (blockIdx.x >= hist_blocks) {
-    // ---- the blocks behind the first hist_blocks write bag_of ----
-    const u32 block = blockIdx.x - hist_blocks, n_blocks = gridDim.x - hist_blocks;
-    if (offsets == nullptr) {     // every occurrence is its own bag
-      for (u32 i = block * kPrepThreads + threadIdx.x; i < n; i += n_blocks * kPrepThreads)
-        bag_of[i] = (i32)i;
-      return;
-    }
-    const u32 wave_global = (block * kPrepThreads + threadIdx.x) / kWave;
-    const u32 n_waves = n_blocks * (kPrepThreads / kWave);
-    for (u32 b0 = wave_global * kWave; b0 < n_bags; b0 += n_waves * kWave) {
-      const u32 b = b0 + lane_id();
-      i32 lo = 0, hi = 0;
-      if (b < n_bags) { lo = offsets[b]; hi = offsets[b + 1]; }
-      lo = max(lo, 0);
-      hi = min(hi, (i32)n);          // never write outside bag_of, whatever the offsets say
-      const bool big = hi - lo > 8;
-      if (!big) for (i32 i = lo; i < hi; ++i) bag_of[i] = (i32)b;
-      u64 todo = __ballot(big);
-      while (todo) {
-        const int src = __ffsll((unsigned long long)todo) - 1;
-        todo &= todo - 1;
-        const i32 blo = __shfl(lo, src, kWave), bhi = __shfl(hi, src, kWave);
-        for (i32 i = blo + (i32)lane_id(); i < bhi; i += kWave) bag_of[i] = (i32)(b0 + src);
-      }
-    }
+    expand_bags(offsets, n_bags, n, bag_of, blockIdx.x - hist_blocks, gridDim.x - hist_blocks);
     return;
   }
-  // ---- the first hist_blocks blocks: resets and histograms ----
   __shared__ u32 h[kMaxPasses][kRadix];
-  __shared__ HeavyLds hv;
+  __shared__ KeyRange s_range;
   __shared__ u64 s_lo[kPrepThreads / kWave], s_hi[kPrepThreads / kWave];
   // The block's first tile is requested before anything waits for the samples, so that the
   // two round trips to memory overlap (hist_blocks <= number of tiles: every block has one).
@@ -361,83 +446,42 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
     const u32 i = blockIdx.x * kSortTile + k * kPrepThreads + threadIdx.x;
     first_keys[k] = i < n ? keys[i] : 0;
   }
-  {
-    u64 lo = ~0ull, hi = 0;
-    const u32 n_samples = min(n, kRangeSamples);
-    // kRangeSamples / 8 evenly spaced runs of 8 consecutive keys (a 64-byte line each, the
-    // first and the last included), so that a wave's request is 8 lines and not 64: every
-    // block asks for the same lines, and the caches serve requests, not bytes.
-    const u32 n_lines = n >> 3;
-    for (u32 j = threadIdx.x; j < n_samples; j += kPrepThreads) {
-      const u32 at = n > kRangeSamples
-                         ? (u32)(((u64)(j >> 3) * (n_lines - 1)) / (kRangeSamples / 8 - 1)) * 8 + (j & 7)
-                         : j;
-      const u64 key = keys[at];
-      lo = min(lo, key);
-      hi = max(hi, key);
-    }
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      lo = min(lo, (u64)__shfl_xor((unsigned long long)lo, d, kWave));
-      hi = max(hi, (u64)__shfl_xor((unsigned long long)hi, d, kWave));
-    }
-    if (lane_id() == 0) { s_lo[threadIdx.x / kWave] = lo; s_hi[threadIdx.x / kWave] = hi; }
-  }
-  if (plan.by_id) load_heavy(hv, heavy_set, plan.max_heavy);
+  sample_key_range(keys, n, s_lo, s_hi);
   for (u32 sh = blockIdx.x; sh < (u32)kHistShards; sh += hist_blocks)     // the next pull's counters
     for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads)
       ghist_next[sh * kMaxPasses * kRadix + i] = 0;
   for (int i = threadIdx.x; i < kMaxPasses * kRadix; i += kPrepThreads) (&h[0][0])[i] = 0;
   if (blockIdx.x == 0) {
     if (threadIdx.x < kMaxPasses + 2) tickets[threadIdx.x] = 0;
-    if (threadIdx.x == 0) {
-      ctx->n_unique = 0;
-      ctx->n_long = 0;
-      ctx->n_chunk_items = 0;
-      ctx->n_evidence = 0;
-      ctx->sort_error = 0;
-      ctx->n_slow = 0;
-      ctx->n_slow_one_key = 0;
-      ctx->n_total = n;
-      ctx->by_id = (u32)plan.by_id;
-    }
-    if (threadIdx.x < kCountShards) ctx->med_count[threadIdx.x] = 0;
+    reset_ctx(ctx, n, 0u);
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     u64 lo = s_lo[0], hi = s_hi[0];
     for (int w = 1; w < kPrepThreads / kWave; ++w) { lo = min(lo, s_lo[w]); hi = max(hi, s_hi[w]); }
     if (lo > hi) lo = hi = 0;            // n == 0
-    hv.range = make_range(lo, hi, plan);
-    if (blockIdx.x == 0) ctx->range = hv.range;
+    s_range = make_range(lo, hi, plan);
+    if (blockIdx.x == 0) ctx->range = s_range;
   }
   __syncthreads();
-  const KeyRange range = hv.range;
+  const KeyRange range = s_range;
   const u32 n_tiles = (n + kSortTile - 1) / kSortTile;
-  auto count_key = [&](u32 i, u64 key) {
-    if (plan.by_id) {
-      bool heavy;
-      const u32 id = bucket_id(key, hv, &heavy);
-      id16[i] = (uint16_t)id;         // by_id plans have ids below 2^16: two passes
-      for (int p = 0; p < plan.n_pass; ++p)
-        atomicAdd(&h[p][(id >> (p * kRadixBits)) & (kRadix - 1)], 1u);
-    } else {
-      const u64 prefix = sorted_prefix(key, range);
-      for (int p = 0; p < plan.n_pass; ++p)
-        atomicAdd(&h[p][key_digit(prefix, p * kRadixBits)], 1u);
-    }
+  auto count_key = [&](u64 key) {
+    const u64 prefix = sorted_prefix(key, range);
+    for (int p = 0; p < plan.n_pass; ++p)
+      atomicAdd(&h[p][key_digit(prefix, p * kRadixBits)], 1u);
   };
 #pragma unroll
   for (int k = 0; k < kPrepItems; ++k) {
     const u32 i = blockIdx.x * kSortTile + k * kPrepThreads + threadIdx.x;
-    if (i < n) count_key(i, first_keys[k]);
+    if (i < n) count_key(first_keys[k]);
   }
   for (u32 tile = blockIdx.x + hist_blocks; tile < n_tiles; tile += hist_blocks) {
     const u32 base = tile * kSortTile;
 #pragma unroll 4
     for (int k = 0; k < kPrepItems; ++k) {
       const u32 i = base + k * kPrepThreads + threadIdx.x;
-      if (i < n) count_key(i, keys[i]);
+      if (i < n) count_key(keys[i]);
     }
   }
   __syncthreads();
@@ -449,19 +493,17 @@ sort_prepare(const u64* __restrict__ keys, u32 n, SortPlan plan, u32* __restrict
 
 // One stable radix pass over (key, payload) pairs; payload = index | bag << 32.
 // FIRST: the payload is built from the position and bag_of (read in order).
-// IDS: the passes sort by the 16-bit bucket id instead of key bits: the first by its low
-// byte (read from id16; the high byte goes into bits 24..31 of the payload, which limits
-// such dedups to 2^24 occurrences), the second by that high byte.  Otherwise the digit is
-// bits shift .. shift + 7 of the key's sorted prefix (sorted_prefix).  `ghist` is this pass's global digit histogram; tile_rows
-// [n_tiles][kRadix] and group_rows [n_groups][kRadix] are this pass's status words.
-template <bool FIRST, bool IDS>
+// The digit is bits shift .. shift + 7 of the key's sorted prefix (sorted_prefix).  `ghist`
+// is this pass's global digit histogram; tile_rows [n_tiles][kRadix] and group_rows
+// [n_groups][kRadix] are this pass's status words.
+template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads)
 onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
               const i32* __restrict__ bag_of, u64* __restrict__ keys_out,
               u64* __restrict__ pay_out, u32 n, int shift,
               const u32* __restrict__ ghist, u32* __restrict__ tile_rows,
               u32* __restrict__ group_rows, u32 group, u32* __restrict__ ticket, u32 epoch,
-              PullCtx* __restrict__ ctx, const uint16_t* __restrict__ id16) {
+              PullCtx* __restrict__ ctx) {
   __shared__ u32 tile_hist[kRadix];              // digit counts of the tile
   __shared__ u32 earlier[kRadix];                // same-digit elements in earlier tiles
   __shared__ u32 wave_cnt[kSortWaves][kRadix];   // per-wave digit counts, then wave offsets
@@ -483,8 +525,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
   const u32 tile_base = tile * kSortTile;
   const u32 tile_n = min((u32)kSortTile, n - tile_base);
   const u32 wave_base = tile_base + wave * kSortWaveSpan;
-  KeyRange range;
-  if (!IDS) range = ctx->range;
+  const KeyRange range = ctx->range;
 
   u64 key[kSortItems];
   u64 pay[kSortItems];
@@ -499,15 +540,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
         pay[r] = (i < n) ? ((u64)i | ((u64)(u32)bag_of[i] << 32)) : 0ull;
       else
         pay[r] = (i < n) ? pay_in[i] : 0ull;
-      if (IDS && FIRST) {
-        const u32 id = (i < n) ? id16[i] : 0u;
-        digit[r] = id & (kRadix - 1);
-        pay[r] |= (u64)(id >> kRadixBits) << 24;
-      } else if (IDS) {
-        digit[r] = (u32)(pay[r] >> 24) & (kRadix - 1);
-      } else {
-        digit[r] = key_digit(sorted_prefix(key[r], range), shift);
-      }
+      digit[r] = key_digit(sorted_prefix(key[r], range), shift);
     }
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
@@ -542,7 +575,7 @@ onesweep_pass(const u64* __restrict__ keys_in, const u64* __restrict__ pay_in,
 #pragma unroll
     for (int r = 0; r < kSortItems; ++r) {
       const u32 i = wave_base + r * kWave + lane;
-      rank[r] = digit_rank(&wave_cnt[wave][digit[r]], digit[r], i < n, lt);
+      rank[r] = digit_rank<false>(&wave_cnt[wave][digit[r]], digit[r], i < n, lt);
     }
   }
   __syncthreads();

@@ -15,7 +15,7 @@
 // table size.
 #pragma once
 
-#include "common.cuh"
+#include "common.hpp"
 
 namespace hps {
 
@@ -101,7 +101,7 @@ constexpr u32 kShortSeg = 16;            // occurrences handled serially by one 
 constexpr u32 kMedSeg = 512;             // occurrences handled by one wave
 constexpr u32 kChunk = 1024;             // occurrences per queued chunk of a longer key
 
-// What the pull leaves for the push about keys that occur often (push.cuh): keys with
+// What the pull leaves for the push about keys that occur often (push.hpp): keys with
 // kShortSeg < occurrences <= kMedSeg go to a sharded list (shard b % 64 for block b,
 // med_cap entries per shard), keys with more are cut into chunks of kChunk positions.
 struct OftenLists {
