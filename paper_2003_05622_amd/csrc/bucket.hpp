@@ -239,147 +239,97 @@ template <int ITEMS>
 struct ChunkLds {
   union {
     u64 words[kChunkThreads * ITEMS];
-    u32 out[kChunkThreads * ITEMS];
     SlowLds slow;
   };
   uint16_t hist[kLdsSortHist];
   u32 scratch[kChunkWaves + 1];
-  u32 s_chunk, s_earlier;
   unsigned long long s_or;
 };
 
-// Cross-region head counts (grouped status words, sort.hpp).  A region publishes its
-// number of group heads as soon as it knows it; the last region of a group then also
-// publishes the group's total.  Wave 0 only; the other waves go on.
-__device__ __forceinline__ void publish_heads(u32 chunk, u32 heads, u32 group, u32 epoch,
-                                              u32* head_rows, u32* head_groups, PullCtx* ctx) {
-  if (threadIdx.x >= kWave) return;
-  const u32 lane = threadIdx.x;
-  if (lane == 0)
-    __hip_atomic_store(head_rows + chunk, status_word(epoch, heads), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-  if (chunk % group == group - 1) {
-    bool ok = true;
-    const u32 g = chunk / group;
-    const u32 earlier = wave_sum_words(head_rows, g * group, chunk, lane, epoch, &ok);
-    if (lane == 0)
-      __hip_atomic_store(head_groups + g, status_word(epoch, earlier + heads), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-    if (!ok) ctx->sort_error = 1;
-  }
-}
+// ---- what region_sort leaves for region_emit --------------------------------------------
+// kind[c]   how region c was ordered:
+constexpr u32 kRegionSorted = 0;     // in LDS: order[] describes its sorted positions
+constexpr u32 kRegionOneKey = 1;     // it holds one key (or nothing): in order as it stands
+constexpr u32 kRegionSlowSrc = 2;    // the slow way; the ordered pairs are in the source arrays
+constexpr u32 kRegionSlowA = 3;      //   ... in the first scratch pair (ka, pa)
+constexpr u32 kRegionSlowB = 4;      //   ... in the second scratch pair (kb, pb)
+// heads[c]  number of group heads (first occurrences of a key in sorted order) in region c;
+//           group_heads[c / kRegionGroup] their sum over a group of regions
+// order[start + j] (kRegionSorted) for sorted position j of the region:
+//           place inside the region of the pair that belongs there (bits 0..11), number of
+//           heads at or before j (bits 12..24; 0: j continues the last key of the region
+//           before), bit 31: j is a head
+constexpr u32 kRegionGroup = 64;
+constexpr u32 kOrderPlaceMask = 0xFFFu;
+constexpr int kOrderHeadsShift = 12;
+constexpr u32 kOrderHeadsMask = 0x1FFFu;
+constexpr u32 kOrderHeadBit = 0x80000000u;
+static_assert(kChunkThreads * kChunkItems <= (int)kOrderPlaceMask + 1, "a place fits 12 bits");
 
-// The number of heads in earlier regions, to all threads (contains a barrier).
-__device__ __forceinline__ u32 heads_before(u32* s_earlier, u32 chunk, u32 group, u32 epoch,
-                                            const u32* head_rows, const u32* head_groups,
-                                            PullCtx* ctx) {
-  if (threadIdx.x < kWave) {
-    const u32 lane = threadIdx.x;
-    bool ok = true;
-    const u32 g = chunk / group;
-    u32 earlier = wave_sum_words(head_rows, g * group, chunk, lane, epoch, &ok);
-    earlier += wave_sum_words(head_groups, 0, g, lane, epoch, &ok);
-    if (!ok) ctx->sort_error = 1;
-    if (lane == 0) *s_earlier = earlier;
-  }
-  __syncthreads();
-  return *s_earlier;
-}
+static_assert(kRegionGroup == (u32)kWave, "region_emit adds up a group's regions one per lane");
 
-// A whole region the slow way: ordered in global memory, then walked.  Kept out of line
-// so that its registers do not weigh on the usual path.
-__device__ __forceinline__ void slow_region(const u64* skeys, const u64* spay, u64* ka, u64* pa, u64* kb,
-                                         u64* pb, u32 n, u32 start, u32 end, u32 chunk, bool last,
-                                         SlowLds& slow, u32* scratch, u32* s_earlier, u32* head_rows,
-                                         u32* head_groups, u32 group, u32 epoch, u32 n_bags, u64* uniq,
-                                         i32* inverse, u32* bagperm, u32* seg_off, PullCtx* ctx,
-                                         TableState* st) {
-  const u32 tid = threadIdx.x;
-  const u64 *sk, *sp;
-  slow_sort_region(skeys, spay, ka, pa, kb, pb, start, end, slow, &sk, &sp);
-  if (tid == 0) {
-    // For the host's choice of the next dedups' form: how much went this way, and how much
-    // of that because ONE key fills the region (then the sorted region's middle element is
-    // that key: count it) -- a key that turned frequent without warning, which the next
-    // hint will list, and not keys that do not suit the buckets.
-    const u64 mid_key = sk[start + (end - start) / 2];
-    u32 lo = start, hi = end;
-    while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] < mid_key) lo = m + 1; else hi = m; }
-    const u32 first = lo;
-    hi = end;
-    while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] <= mid_key) lo = m + 1; else hi = m; }
-    atomicAdd(&ctx->n_slow, end - start);
-    if ((lo - first) * 2 >= end - start) atomicAdd(&ctx->n_slow_one_key, end - start);
-  }
-  // the element before the region is read from the untouched source
-  const bool first_is_head = start == 0 || sk[start] != skeys[start - 1];
-  u32 heads = 0;
-  for (u32 j = start + tid; j < end; j += kChunkThreads)
-    heads += (j == start ? first_is_head : sk[j] != sk[j - 1]) ? 1u : 0u;
-  u32 total;
-  (void)block_excl_sum<kChunkThreads>(heads, scratch, &total);
-  publish_heads(chunk, total, group, epoch, head_rows, head_groups, ctx);
-  u32 rank = heads_before(s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
-  if (last && tid == 0) { ctx->n_unique = rank + total; seg_off[rank + total] = n; }
-  for (u32 base = start; base < end; base += kChunkThreads) {
-    const u32 j = base + tid;
-    const bool valid = j < end;
-    const u64 key = valid ? sk[j] : 0;
-    const bool head = valid && (j == start ? first_is_head : key != sk[j - 1]);
-    u32 tile_heads;
-    const u32 before = block_excl_sum<kChunkThreads>(head ? 1u : 0u, scratch, &tile_heads);
-    if (valid) {
-      const u32 r = rank + before + (head ? 1u : 0u) - 1;   // rank of this occurrence's key
-      const u64 pay = sp[j];
-      if (head) {
-        uniq[r] = key;
-        seg_off[r] = j;
-        if (key == kEmptyKey) raise_error(st, kErrReserved);
-      }
-      inverse[(u32)pay] = (i32)r;
-      bagperm[j] = min((u32)(pay >> 32), n_bags ? n_bags - 1 : 0u) | (head ? 0x80000000u : 0u);
-    }
-    rank += tile_heads;
-  }
+// Called by ONE thread of the region's workgroup.
+__device__ __forceinline__ void publish_region(u32 chunk, u32 kind, u32 heads, u32* region_kind,
+                                               u32* region_heads, u32* group_heads) {
+  region_kind[chunk] = kind;
+  region_heads[chunk] = heads;
+  if (heads) atomicAdd(group_heads + chunk / kRegionGroup, heads);
 }
 
 // skeys/spay: the pairs ordered by bucket id (payload = occurrence index | bag << 32),
 // read only; ka/pa and kb/pb: scratch of the same shape (only touched the slow way);
-// borders[0 .. n_regions]: the regions (region_borders).
+// borders[0 .. n_regions]: the regions (region_borders).  One region per workgroup; no
+// workgroup waits for another.  group_heads must be zero on entry.
 //
 // After the LDS sort a thread owns the sorted positions tid, tid + 512, ... of its region
-// (conflict-free LDS reads, coalesced writes); the rank of a position's key is the number
-// of group heads before it, counted with wave ballots per round of 512 positions and one
-// 64-entry scan over (round, wave).
+// (conflict-free LDS reads, coalesced writes); the number of heads up to a position comes
+// from wave ballots per round of 512 positions and one 64-entry scan over (round, wave).
 template <int ITEMS, bool ORDERED>
 __global__ void __launch_bounds__(kChunkThreads, 4)
-region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
-                 u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
-                 const u32* __restrict__ borders, u32* __restrict__ head_rows,
-                 u32* __restrict__ head_groups, u32 group, u32* __restrict__ ticket, u32 epoch,
-                 u32 n_bags, u64* __restrict__ uniq, i32* __restrict__ inverse,
-                 u32* __restrict__ bagperm, u32* __restrict__ seg_off, PullCtx* __restrict__ ctx,
-                 TableState* __restrict__ st) {
+region_sort(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __restrict__ ka,
+            u64* __restrict__ pa, u64* __restrict__ kb, u64* __restrict__ pb, u32 n,
+            const u32* __restrict__ borders, u32* __restrict__ region_kind,
+            u32* __restrict__ region_heads, u32* __restrict__ group_heads,
+            u32* __restrict__ order, PullCtx* __restrict__ ctx) {
   static_assert(ITEMS == kChunkWaves, "the (round, wave) head counts are scanned by one wave");
   constexpr u32 kChunkCap = kChunkThreads * ITEMS;
   __shared__ ChunkLds<ITEMS> L;
   const u32 tid = threadIdx.x, wave = tid / kWave, lane = tid & (kWave - 1);
   const u64 lt = lanemask_lt();
-  if (tid == 0) {
-    L.s_chunk = atomicAdd(ticket, 1u);
-    L.s_or = 0;
-  }
-  __syncthreads();
-  const u32 chunk = L.s_chunk;
-  const u32 n_chunks = (n + kChunkSpan - 1) / kChunkSpan;
-  const bool last = chunk + 1 == n_chunks;
+  const u32 chunk = blockIdx.x;
+  if (tid == 0) L.s_or = 0;
   const u32 start = borders[chunk], end = borders[chunk + 1];
   const u32 cnt = end - start;       // start <= end: both borders come from the same rule
-  const u32 bag_max = n_bags ? n_bags - 1 : 0;
+  __syncthreads();
 
   if (cnt > kChunkCap) {
-    slow_region(skeys, spay, ka, pa, kb, pb, n, start, end, chunk, last, L.slow, L.scratch, &L.s_earlier,
-                head_rows, head_groups, group, epoch, n_bags, uniq, inverse, bagperm, seg_off, ctx, st);
+    // ---- the slow way: ordered through global memory, described by where the result is ----
+    const u64 *sk, *sp;
+    slow_sort_region(skeys, spay, ka, pa, kb, pb, start, end, L.slow, &sk, &sp);
+    if (tid == 0) {
+      // For the host's choice of the next dedups' form: how much went this way, and how much
+      // of that because ONE key fills the region (then the sorted region's middle element is
+      // that key: count it) -- a key that turned frequent without warning, which the next
+      // hint will list, and not keys that do not suit the buckets.
+      const u64 mid_key = sk[start + (end - start) / 2];
+      u32 lo = start, hi = end;
+      while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] < mid_key) lo = m + 1; else hi = m; }
+      const u32 first = lo;
+      hi = end;
+      while (lo < hi) { const u32 m = lo + (hi - lo) / 2; if (sk[m] <= mid_key) lo = m + 1; else hi = m; }
+      atomicAdd(&ctx->n_slow, end - start);
+      if ((lo - first) * 2 >= end - start) atomicAdd(&ctx->n_slow_one_key, end - start);
+    }
+    // the element before the region is read from the untouched source
+    const bool first_is_head = start == 0 || sk[start] != skeys[start - 1];
+    u32 heads = 0;
+    for (u32 j = start + tid; j < end; j += kChunkThreads)
+      heads += (j == start ? first_is_head : sk[j] != sk[j - 1]) ? 1u : 0u;
+    u32 total;
+    (void)block_excl_sum<kChunkThreads>(heads, L.scratch, &total);
+    if (tid == 0)
+      publish_region(chunk, sk == skeys ? kRegionSlowSrc : sk == ka ? kRegionSlowA : kRegionSlowB, total,
+                     region_kind, region_heads, group_heads);
     return;
   }
 
@@ -414,26 +364,10 @@ region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u6
   const u64 key_before = start > 0 ? skeys[start - 1] : 0;
   if (hb == 0) {
     // One key only (part of a heavy key's bucket, typically), or nothing: the region is
-    // in order as it stands, its pairs are read in place.
-    const u32 n_heads = cnt && !(start > 0 && key_before == key0) ? 1u : 0u;
-    publish_heads(chunk, n_heads, group, epoch, head_rows, head_groups, ctx);
-    const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
-    if (last && tid == 0) { ctx->n_unique = earlier + n_heads; seg_off[earlier + n_heads] = n; }
-    const u32 rank = earlier + n_heads - 1;      // of the key (cnt > 0: earlier + n_heads >= 1)
-    if (n_heads && tid == 0) {
-      uniq[rank] = key0;
-      seg_off[rank] = start;
-      if (key0 == kEmptyKey) raise_error(st, kErrReserved);
-    }
-#pragma unroll
-    for (int r = 0; r < ITEMS; ++r) {
-      const u32 p = r * kChunkThreads + tid;
-      if ((u32)r < items && p < cnt) {
-        const u64 pay = spay[start + p];
-        bagperm[start + p] = min((u32)(pay >> 32), bag_max) | (p == 0 && n_heads ? 0x80000000u : 0u);
-        inverse[(u32)pay] = (i32)rank;
-      }
-    }
+    // in order as it stands.
+    if (tid == 0)
+      publish_region(chunk, kRegionOneKey, cnt && !(start > 0 && key_before == key0) ? 1u : 0u, region_kind,
+                     region_heads, group_heads);
     return;
   }
 
@@ -442,14 +376,14 @@ region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u6
   // different keys then agree in all of those bits (rare), stage 1 orders by the bits below lo
   // and stage 2, stable, by [lo, hb) again, so that all 64 bits count.  One sort loop serves
   // all stages.  Afterwards the rounds are taken four at a time, so that few gathered keys
-  // and payloads are in registers at once.
-  u32 head_bits = 0;       // bit k: the key at sorted position k * 512 + tid differs from the key before it
-  const u32 last_j = cnt - 1;          // (cnt > 0 here) loads behind the region's end repeat its last pair
+  // are in registers at once.
 #pragma unroll
   for (int r = 0; r < ITEMS; ++r) {
     const u32 q = r * kChunkThreads + tid;
     if (q < cnt) L.words[q] = (((key[r] >> lo) & bit_mask) << 16) | q;
   }
+  u32 head_bits = 0;       // bit k: the key at sorted position k * 512 + tid differs from the key before it
+  const u32 last_j = cnt - 1;          // (cnt > 0 here) loads behind the region's end repeat its last pair
   for (int stage = 0; stage < 3; ++stage) {
     if (stage == 1) {
 #pragma unroll 1
@@ -505,7 +439,7 @@ region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u6
     if (!__syncthreads_or(bad && lo > 0 && stage == 0)) break;
   }
 
-  // heads before each of this thread's positions: per round a wave ballot, and one scan over
+  // heads up to each of this thread's positions: per round a wave ballot, and one scan over
   // the (round, wave) counts in the order of the positions
   u32 my_count = 0;       // lane k of wave w: heads in round k of wave w
 #pragma unroll
@@ -520,46 +454,119 @@ region_sort_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, u6
     const u32 c = counts[lane];
     const u32 incl = wave_incl_sum(c);
     counts[lane] = incl - c;
-    if (lane == kWave - 1) L.scratch[0] = incl;
+    if (lane == kWave - 1) publish_region(chunk, kRegionSorted, incl, region_kind, region_heads, group_heads);
   }
   __syncthreads();
-  const u32 total = L.scratch[0];
-  publish_heads(chunk, total, group, epoch, head_rows, head_groups, ctx);
-
-  // the pairs' payloads; the bags go out in sorted order (before the wait below)
-  u32 idx[ITEMS];
-  {
-    u64 pay[ITEMS];
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k)
-      pay[k] = spay[start + ((u32)L.words[min(k * kChunkThreads + tid, last_j)] & 0xFFFFu)];
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-      const u32 j = k * kChunkThreads + tid;
-      idx[k] = (u32)pay[k];
-      // clamped: whatever the offsets said, the push must stay inside the gradient buffer
-      if (j < cnt)
-        bagperm[start + j] = min((u32)(pay[k] >> 32), bag_max) | (((head_bits >> k) & 1u) ? 0x80000000u : 0u);
-    }
-  }
-  const u32 earlier = heads_before(&L.s_earlier, chunk, group, epoch, head_rows, head_groups, ctx);
-  if (last && tid == 0) { ctx->n_unique = earlier + total; seg_off[earlier + total] = n; }
 #pragma unroll
   for (int k = 0; k < ITEMS; ++k) {
     const u32 j = k * kChunkThreads + tid;
     const bool head = (head_bits >> k) & 1u;
     const u64 m = __ballot(head);
     if (j < cnt) {
-      // rank of this pair's key: heads at or before its position, less one
-      const u32 rank = earlier + counts[k * kChunkWaves + wave] + (u32)__popcll(m & lt) + (head ? 1u : 0u) - 1u;
-      if (head) {
-        const u64 key_j = skeys[start + ((u32)L.words[j] & 0xFFFFu)];
-        uniq[rank] = key_j;
-        seg_off[rank] = start + j;
-        if (key_j == kEmptyKey) raise_error(st, kErrReserved);
-      }
-      inverse[idx[k]] = (i32)rank;
+      const u32 upto = counts[k * kChunkWaves + wave] + (u32)__popcll(m & lt) + (head ? 1u : 0u);
+      order[start + j] = ((u32)L.words[j] & kOrderPlaceMask) | (upto << kOrderHeadsShift) | (head ? kOrderHeadBit : 0u);
     }
+  }
+}
+
+// The dedup's outputs for region blockIdx.x from what region_sort left.  The number of heads
+// in earlier regions -- the rank of the region's first new key -- is the sum of the earlier
+// groups' totals and of the earlier regions of the own group.
+__global__ void __launch_bounds__(kChunkThreads)
+region_emit(const u64* __restrict__ skeys, const u64* __restrict__ spay, const u64* __restrict__ ka,
+            const u64* __restrict__ pa, const u64* __restrict__ kb, const u64* __restrict__ pb, u32 n,
+            const u32* __restrict__ borders, const u32* __restrict__ region_kind,
+            const u32* __restrict__ region_heads, const u32* __restrict__ group_heads,
+            const u32* __restrict__ order, u32 n_bags, u64* __restrict__ uniq,
+            i32* __restrict__ inverse, u32* __restrict__ bagperm, u32* __restrict__ seg_off,
+            PullCtx* __restrict__ ctx, TableState* __restrict__ st) {
+  __shared__ u32 scratch[kChunkWaves + 1];
+  __shared__ u32 s_earlier;
+  const u32 tid = threadIdx.x;
+  const u32 chunk = blockIdx.x, n_chunks = gridDim.x;
+  const u32 start = borders[chunk], end = borders[chunk + 1];
+  const u32 cnt = end - start;
+  const u32 kind = region_kind[chunk];
+  const u32 bag_max = n_bags ? n_bags - 1 : 0;
+  if (tid < kWave) {
+    const u32 g = chunk / kRegionGroup;
+    u32 c = 0;
+    for (u32 i = tid; i < g; i += kWave) c += group_heads[i];
+    const u32 r = g * kRegionGroup + tid;          // kRegionGroup == kWave: one region per lane
+    if (r < chunk) c += region_heads[r];
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) c += __shfl_xor(c, d, kWave);
+    if (tid == 0) s_earlier = c;
+  }
+  __syncthreads();
+  const u32 earlier = s_earlier;
+  if (chunk + 1 == n_chunks && tid == 0) {
+    const u32 total = earlier + region_heads[chunk];
+    ctx->n_unique = total;
+    seg_off[total] = n;
+  }
+  if (cnt == 0) return;
+
+  if (kind == kRegionSorted) {
+    for (u32 j = tid; j < cnt; j += kChunkThreads) {
+      const u32 o = order[start + j];
+      const u32 at = start + (o & kOrderPlaceMask);
+      const u64 pay = spay[at];
+      const bool head = (o & kOrderHeadBit) != 0;
+      // rank of this pair's key: heads at or before its position, less one
+      const u32 rank = earlier + ((o >> kOrderHeadsShift) & kOrderHeadsMask) - 1u;
+      // clamped: whatever the offsets said, the push must stay inside the gradient buffer
+      bagperm[start + j] = min((u32)(pay >> 32), bag_max) | (head ? kOrderHeadBit : 0u);
+      inverse[(u32)pay] = (i32)rank;
+      if (head) {
+        const u64 key = skeys[at];
+        uniq[rank] = key;
+        seg_off[rank] = start + j;
+        if (key == kEmptyKey) raise_error(st, kErrReserved);
+      }
+    }
+    return;
+  }
+  if (kind == kRegionOneKey) {
+    const u64 key0 = skeys[start];
+    const bool is_head = !(start > 0 && skeys[start - 1] == key0);
+    const u32 rank = earlier + (is_head ? 1u : 0u) - 1u;      // (earlier >= 1 if it is not a head)
+    if (is_head && tid == 0) {
+      uniq[rank] = key0;
+      seg_off[rank] = start;
+      if (key0 == kEmptyKey) raise_error(st, kErrReserved);
+    }
+    for (u32 j = tid; j < cnt; j += kChunkThreads) {
+      const u64 pay = spay[start + j];
+      bagperm[start + j] = min((u32)(pay >> 32), bag_max) | (j == 0 && is_head ? kOrderHeadBit : 0u);
+      inverse[(u32)pay] = (i32)rank;
+    }
+    return;
+  }
+  // ordered the slow way: walk the ordered pairs, a block-wide count of heads per round
+  const u64* sk = kind == kRegionSlowSrc ? skeys : kind == kRegionSlowA ? ka : kb;
+  const u64* sp = kind == kRegionSlowSrc ? spay : kind == kRegionSlowA ? pa : pb;
+  const bool first_is_head = start == 0 || sk[start] != skeys[start - 1];
+  u32 rank = earlier;
+  for (u32 base = start; base < end; base += kChunkThreads) {
+    const u32 j = base + tid;
+    const bool valid = j < end;
+    const u64 key = valid ? sk[j] : 0;
+    const bool head = valid && (j == start ? first_is_head : key != sk[j - 1]);
+    u32 tile_heads;
+    const u32 before = block_excl_sum<kChunkThreads>(head ? 1u : 0u, scratch, &tile_heads);
+    if (valid) {
+      const u32 r = rank + before + (head ? 1u : 0u) - 1;   // rank of this occurrence's key
+      const u64 pay = sp[j];
+      if (head) {
+        uniq[r] = key;
+        seg_off[r] = j;
+        if (key == kEmptyKey) raise_error(st, kErrReserved);
+      }
+      inverse[(u32)pay] = (i32)r;
+      bagperm[j] = min((u32)(pay >> 32), bag_max) | (head ? kOrderHeadBit : 0u);
+    }
+    rank += tile_heads;
   }
 }
 

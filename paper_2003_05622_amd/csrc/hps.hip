@@ -364,7 +364,6 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
           &t->w<HeavyRing>(L.heavy_raw)->set[(t->lookup_serial + kHeavyRing - 1) % kHeavyRing];
       const unsigned count_blocks = n_tiles < 1024 ? n_tiles : 1024;
       const unsigned n_regions = (n + kRegionSpan - 1) / kRegionSpan;
-      const u32 region_group = tile_group(n_regions);
       u32* hist = t->w<u32>(L.part_hist);
       u32* tot = t->w<u32>(L.part_tot);
       uint8_t* dig = plan.n_pass == 2 ? t->w<uint8_t>(L.dig) : nullptr;
@@ -396,15 +395,24 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
       region_borders<<<(n_regions + 1 + kPartWaves - 1) / kPartWaves, kPartThreads, 0, s>>>(
           kcur, n, n_regions, plan.max_heavy, heavy, ctx, borders);
 #undef HPS_SCATTER
-#define HPS_EMIT(ORDERED)                                                                          \
-  region_sort_emit<kChunkItems, ORDERED><<<n_regions, kChunkThreads, 0, s>>>(                      \
-      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, borders,                 \
-      t->w<u32>(L.head_rows), t->w<u32>(L.head_groups), region_group, tickets + kMaxPasses, 1u,    \
-      n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse), t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), \
-      ctx, t->view.st)
-      if (t->ordered_rank) HPS_EMIT(true);
-      else HPS_EMIT(false);
-#undef HPS_EMIT
+      // region_sort's notes for region_emit: heads per region and per group of regions (the
+      // status words the first scan cleared), how each region was ordered, and the order itself
+      // (in bag_of, which the first scatter has finished with)
+      u32* region_heads = t->w<u32>(L.head_rows);
+      u32* region_kind = t->w<u32>(L.head_rows) + L.head_tiles;
+      u32* group_heads = t->w<u32>(L.head_groups);
+      u32* order = t->w<u32>(L.bag_of);
+#define HPS_REGIONS(ORDERED)                                                                       \
+  region_sort<kChunkItems, ORDERED><<<n_regions, kChunkThreads, 0, s>>>(                           \
+      kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, borders, region_kind,    \
+      region_heads, group_heads, order, ctx)
+      if (t->ordered_rank) HPS_REGIONS(true);
+      else HPS_REGIONS(false);
+#undef HPS_REGIONS
+      region_emit<<<n_regions, kChunkThreads, 0, s>>>(
+          kcur, pcur, kalt, palt, t->w<u64>(L.keys_c), t->w<u64>(L.idx_c), n, borders, region_kind,
+          region_heads, group_heads, order, n_bags, t->w<u64>(C.uniq), t->w<i32>(C.inverse),
+          t->w<u32>(C.bagperm), t->w<u32>(C.seg_off), ctx, t->view.st);
     } else {
       // two sets of digit histograms: a plain dedup counts into one and clears the other for
       // the next plain dedup
