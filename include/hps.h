@@ -226,6 +226,21 @@ hps_status hps_set_pooling(hps_table* t, int mean);
 hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_values,
                           void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace of their own (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the same
+ * operation as hps_accumulate, with the call's scratch data (the sorted pairs, the unique keys,
+ * their rows, the work lists) in a device array that is part of the library's code object
+ * instead of the table's workspace -- 10 MiB per GPU the library runs on, held until the
+ * process ends.  The call allocates nothing, on the device or through the HIP runtime.
+ *   n <= HPS_STATIC_MAX_KEYS, else HPS_EINVAL; other arguments and results as hps_accumulate.
+ * All tables of a GPU share that GPU's array, and a call leaves its contents behind: the call
+ * clears what it needs cleared, but two calls that overlap on one GPU (different streams or
+ * threads, also on different tables) race.  Issue it on the stream of the table's other calls.
+ * Its key dedup always takes the plain form over all 64 key bits, whatever the table's history. */
+#define HPS_STATIC_MAX_KEYS 65536u
+hps_status hps_accumulate_static(hps_table* t, const uint64_t* d_keys, uint64_t n,
+                                 const float* d_values, void* stream);
+
 /* Section 3 "union of the referenced parameters": copies the outstanding pull's
  * ascending unique keys (d_uniq_out, room for n_keys) and per-occurrence ranks
  * (d_inverse_out [n_keys] int32, uniq[inverse[i]] == keys[i]); either may be NULL.

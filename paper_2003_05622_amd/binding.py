@@ -13,7 +13,7 @@ ROWS_F32, ROWS_BF16 = 0, 1
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
-           "hps_push", "hps_set_pooling", "hps_accumulate", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
+           "hps_push", "hps_set_pooling", "hps_accumulate", "hps_accumulate_static", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
            "hps_stats", "hps_clear_error", "hps_clear", "hps_probe_random_rows",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.hps_set_pooling.argtypes = [vp, ctypes.c_int]
         L.hps_accumulate.restype = st
         L.hps_accumulate.argtypes = [vp, vp, u64, vp, vp]
+        L.hps_accumulate_static.restype = st
+        L.hps_accumulate_static.argtypes = [vp, vp, u64, vp, vp]
         L.hps_stats.restype = st
         L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
         L.hps_clear_error.restype = st
@@ -231,6 +233,14 @@ class HpsTable:
             raise ValueError("values must be [n, dim]")
         _check(lib().hps_accumulate(self._h, _ptr(keys), n, _ptr(values), _stream()),
                "hps_accumulate")
+
+    def accumulate_static(self, keys, values) -> None:
+        """accumulate() with the library's static device array as scratch (no allocation)."""
+        n = keys.numel()
+        if n and tuple(values.shape) != (n, self.dim):
+            raise ValueError("values must be [n, dim]")
+        _check(lib().hps_accumulate_static(self._h, _ptr(keys), n, _ptr(values), _stream()),
+               "hps_accumulate_static")
 
     def dump(self, max_rows: Optional[int] = None, dirty: bool = False):
         """All rows, or with dirty=True the rows updated since the last dirty dump."""

@@ -203,6 +203,19 @@ bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
 }  // namespace
 
+// ---- the one entry point that allocates nothing (hps_accumulate_static) ------------------
+// Its workspace: a file-scope device array, one copy per GPU, held until the process ends.
+// Room for the workspace of HPS_STATIC_MAX_KEYS pairs with rows of up to 1024 floats.
+constexpr size_t kStaticScratchBytes = 10u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  char* ptr;                // this device's address of `scratch` (hipGetSymbolAddress), null until first used
+  bool ring_ready;          // its lists of frequent keys have been initialised
+  uint64_t lookup_serial;   // lookups run on it so far (they take turns on its three lists)
+};
+static StaticScratch g_static[kMaxDevices];
+
 struct hps_table {
   uint64_t capacity, n_slots, max_keys, max_bags;
   uint32_t dim, acc_len;
@@ -836,16 +849,10 @@ hps_status hps_set_pooling(hps_table* t, int mean) {
   return HPS_OK;
 }
 
-hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_values,
-                          void* stream) {
-  if (!t || (n && (!d_keys || !d_values))) return HPS_EINVAL;
-  if (n > t->max_keys || (uintptr_t)d_keys % 8 || (uintptr_t)d_values % 16) return HPS_EINVAL;
-  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// The kernels of an accumulate on context 0 of whatever workspace the table currently points to.
+static hps_status accumulate_launches(hps_table* t, const uint64_t* d_keys, uint64_t n,
+                                      const float* d_values, hipStream_t s) {
   const int c = 0;
-  hps_table::Context& cx = t->cx[c];
-  if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
-  if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
   // every (key, value row) pair is a bag of its own: the dedup groups the pairs by key,
   // the push kernels sum each group's value rows and add the sum onto the row
   launch_dedup(t, c, d_keys, (u32)n, nullptr, (u32)n, s);
@@ -861,12 +868,81 @@ hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, cons
   } else {
     commit_absent<<<1, 256, 0, s>>>(t->view.st, nullptr, 0);
   }
-  if (!launch_ok()) return HPS_EDEVICE;
+  return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, const float* d_values,
+                          void* stream) {
+  if (!t || (n && (!d_keys || !d_values))) return HPS_EINVAL;
+  if (n > t->max_keys || (uintptr_t)d_keys % 8 || (uintptr_t)d_values % 16) return HPS_EINVAL;
+  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hps_table::Context& cx = t->cx[0];
+  if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
+  if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
+  const hps_status rc = accumulate_launches(t, d_keys, n, d_values, s);
+  if (rc != HPS_OK) return rc;
   if (hipEventRecord(cx.released, s) != hipSuccess || hipEventRecord(t->scratch_free, s) != hipSuccess)
     return HPS_EDEVICE;
   cx.released_set = true;
   t->scratch_set = true;
   return HPS_OK;
+}
+
+hps_status hps_accumulate_static(hps_table* t, const uint64_t* d_keys, uint64_t n,
+                                 const float* d_values, void* stream) {
+  if (!t || (n && (!d_keys || !d_values))) return HPS_EINVAL;
+  if (n > HPS_STATIC_MAX_KEYS || (uintptr_t)d_keys % 8 || (uintptr_t)d_values % 16) return HPS_EINVAL;
+  if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
+  const WorkspaceLayout wl = workspace_layout(HPS_STATIC_MAX_KEYS, HPS_STATIC_MAX_KEYS, t->dim);
+  if (wl.total > kStaticScratchBytes) return HPS_EINVAL;       // rows too wide for the static array
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return HPS_EDEVICE; }
+  StaticScratch& ss = g_static[dev];
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!ss.ptr) {
+    // this device's copy of the array: the name itself is no device address on the host
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return HPS_EDEVICE; }
+    ss.ptr = static_cast<char*>(p);
+    ss.ring_ready = false;
+  }
+  // The table works on the static array for the length of this call: its own workspace, and
+  // what the host keeps about it, stay as they are.
+  struct Saved {
+    char* ws; WorkspaceLayout wl; uint64_t serial, plain_serial, lookup_serial, full_until;
+    int dedup_mode; unsigned long long* report; uint32_t timing_mask;
+  } keep = {t->ws, t->wl, t->serial, t->plain_serial, t->lookup_serial, t->full_until,
+            t->dedup_mode, t->report, t->timing_mask};
+  t->ws = ss.ptr;
+  t->wl = wl;
+  t->serial = t->plain_serial = 0;            // the status words are cleared below: any epoch will do
+  t->lookup_serial = ss.lookup_serial;
+  t->dedup_mode = 1;                           // plain passes ...
+  t->full_until = ~0ull;                       // ... over all 64 key bits: exact whatever the keys, no history needed
+  t->report = nullptr;
+  t->timing_mask = 0;
+  // what must start at zero: digit histograms, tickets, status words; once per device: the lists of frequent keys
+  fill_u64<<<256, 256, 0, s>>>(t->w<u64>(wl.ghist), (wl.heavy_raw - wl.ghist) / 8, 0);
+  if (!ss.ring_ready) {
+    fill_u64<<<64, 256, 0, s>>>(t->w<u64>(wl.heavy_raw), (wl.bag_of - wl.heavy_raw) / 8, 0);
+    for (u32 k = 0; k < kHeavyRing; ++k)
+      init_heavy_set<<<1, 256, 0, s>>>(&t->w<HeavyRing>(wl.heavy_raw)->set[k]);
+    ss.ring_ready = true;
+  }
+  set_ctx_empty<<<1, 64, 0, s>>>(t->ctx(0), t->w<u32>(wl.c[0].seg_off));
+  const hps_status rc = accumulate_launches(t, d_keys, n, d_values, s);
+  ss.lookup_serial = t->lookup_serial;
+  t->ws = keep.ws;
+  t->wl = keep.wl;
+  t->serial = keep.serial;
+  t->plain_serial = keep.plain_serial;
+  t->lookup_serial = keep.lookup_serial;
+  t->full_until = keep.full_until;
+  t->dedup_mode = keep.dedup_mode;
+  t->report = keep.report;
+  t->timing_mask = keep.timing_mask;
+  return rc;
 }
 
 hps_status hps_last_unique(hps_table* t, uint64_t* d_uniq_out, int32_t* d_inverse_out,
