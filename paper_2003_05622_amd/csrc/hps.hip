@@ -490,7 +490,7 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
   often.heavy_min = (u32)(n_keys / kHeavyShare > kHeavyMin ? n_keys / kHeavyShare : kHeavyMin);
   often.report = t->report;
   often.serial = (u32)t->lookup_serial;
-  const unsigned probe_blocks = grid_for(n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+  const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0, &ctx->n_unique,
                                                         t->w<u32>(C.rows), nullptr, nullptr, nullptr,
                                                         nullptr, nullptr, t->w<u32>(t->wl.miss_list),
@@ -715,12 +715,13 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
   if (!t || (n && !d_keys) || (d_acc && !d_weights)) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+  const unsigned lookup_blocks = grid_for(n, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
   if (n) {
     if (d_weights)
-      lookup_keys<2><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
+      lookup_keys<2><<<lookup_blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
                                                       d_acc, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     else
-      lookup_keys<1><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
+      lookup_keys<1><<<lookup_blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
                                                       nullptr, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
                                                     d_acc, nullptr, 0);
@@ -968,7 +969,7 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
   if (!t || (n && (!d_keys || !d_weights_out || !d_acc_out || !d_found_out))) return HPS_EINVAL;
   if (n == 0) return HPS_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const unsigned blocks = grid_for(n, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
+  const unsigned blocks = grid_for(n, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
                                                   nullptr, d_weights_out, d_acc_out, d_found_out,
                                                   nullptr, 0, OftenLists());

@@ -92,8 +92,13 @@ __device__ __forceinline__ void store_w4(const TableView& t, u64 row, u32 col4, 
 }
 
 constexpr int kProbeThreads = 256;
-constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // 8-lane groups per block
+constexpr int kProbeGroups = kProbeThreads / kSlotsPerLine;   // insert: 8-lane groups per block
 constexpr int kProbeInFlight = 8;                             // keys a group probes at a time
+// Lookups take four lanes per key, each reading two of the line's eight slots with one
+// 16-byte load: a wave's load instruction then asks for sixteen lines instead of eight, and
+// the rate at which lines come back follows the lines asked for per instruction.
+constexpr int kLookupLanes = 4;
+constexpr int kLookupGroups = kProbeThreads / kLookupLanes;
 constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
 constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
@@ -292,6 +297,30 @@ __device__ __forceinline__ u32 probe_find(const TableView& t, u64 key, u32 sub, 
   return kNoRow;
 }
 
+// The same for a group of kLookupLanes lanes: lane `sub` holds slots 2 * sub and 2 * sub + 1 of
+// the line in `pair`.
+__device__ __forceinline__ u32 group4_bits(u64 ballot) {
+  return (u32)(ballot >> (lane_id() & ~3u)) & 0xFu;
+}
+__device__ __forceinline__ ulonglong2 load_slot_pair(const TableView& t, u64 line, u32 sub) {
+  return reinterpret_cast<const ulonglong2*>(t.keys)[line * (kSlotsPerLine / 2) + sub];
+}
+__device__ __forceinline__ u32 probe_find4(const TableView& t, u64 key, u32 sub, u64& line,
+                                           ulonglong2& pair) {
+  for (u64 step = 0; step < t.n_lines; ++step) {
+    // bit s: lane s's first slot, bit 4 + s: its second
+    const u32 hit = group4_bits(__ballot(pair.x == key)) | (group4_bits(__ballot(pair.y == key)) << 4);
+    if (hit) {
+      const u32 b = __ffs(hit) - 1;
+      return (u32)(line * kSlotsPerLine + 2 * (b & 3u) + (b >> 2));
+    }
+    if (group4_bits(__ballot(pair.x == kEmptyKey || pair.y == kEmptyKey))) return kNoRow;
+    line = line + 1 == t.n_lines ? 0 : line + 1;
+    pair = load_slot_pair(t, line, sub);
+  }
+  return kNoRow;
+}
+
 // Finds the key or claims a free slot for it.  *created tells which.
 __device__ __forceinline__ u32 probe_find_or_claim(const TableView& t, u64 key, u32 sub, u64 line,
                                                    u64 slot_key, bool* created) {
@@ -353,12 +382,13 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
   if (load_error(t.st) != 0) return;
   if (threadIdx.x == 0) { s_missing = 0; s_med = 0; }
   __syncthreads();
-  const u32 sub = threadIdx.x & 7;
-  const u64 group = (u64)blockIdx.x * kProbeGroups + (threadIdx.x >> 3);
-  const u64 n_groups = (u64)gridDim.x * kProbeGroups;
+  const u32 sub = threadIdx.x % kLookupLanes;
+  const u64 group = (u64)blockIdx.x * kLookupGroups + threadIdx.x / kLookupLanes;
+  const u64 n_groups = (u64)gridDim.x * kLookupGroups;
   u32 missing = 0;
   for (u64 u0 = group; u0 < n_keys; u0 += n_groups * kProbeInFlight) {
-    u64 key[kProbeInFlight], line[kProbeInFlight], slot_key[kProbeInFlight];
+    u64 key[kProbeInFlight], line[kProbeInFlight];
+    ulonglong2 pair[kProbeInFlight];
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
       const u64 u = u0 + (u64)k * n_groups;
@@ -368,7 +398,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
       const u64 u = u0 + (u64)k * n_groups;
-      slot_key[k] = u < n_keys ? t.keys[line[k] * kSlotsPerLine + sub] : 0;
+      pair[k] = u < n_keys ? load_slot_pair(t, line[k], sub) : make_ulonglong2(0, 0);
     }
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
@@ -380,7 +410,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         if (MODE == 0 && sub == 0) rows[u] = kNoRow;
         continue;
       }
-      const u32 row = probe_find(t, key[k], sub, line[k], slot_key[k]);
+      const u32 row = probe_find4(t, key[k], sub, line[k], pair[k]);
       if (row == kNoRow && MODE != 3 && MODE != 0) ++missing;
       if (MODE == 0 && sub == 0) {
         rows[u] = row;
@@ -411,17 +441,17 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         }
       }
       if (MODE == 2 && row != kNoRow) {
-        for (u32 j = sub; j < t.dim; j += 8) store_w(t, row, j, w_in[u * t.dim + j]);
+        for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row, j, w_in[u * t.dim + j]);
         float* ar = t.acc + (u64)row * t.acc_len;
-        for (u32 j = sub; j < t.acc_len; j += 8)
+        for (u32 j = sub; j < t.acc_len; j += kLookupLanes)
           ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
       }
       if (MODE == 3) {
         if (sub == 0) found_out[u] = row != kNoRow;
         if (row != kNoRow) {
-          for (u32 j = sub; j < t.dim; j += 8) w_out[u * t.dim + j] = load_w(t, row, j);
+          for (u32 j = sub; j < t.dim; j += kLookupLanes) w_out[u * t.dim + j] = load_w(t, row, j);
           const float* ar = t.acc + (u64)row * t.acc_len;
-          for (u32 j = sub; j < t.acc_len; j += 8) acc_out[u * t.acc_len + j] = acc_value(ar[j]);
+          for (u32 j = sub; j < t.acc_len; j += kLookupLanes) acc_out[u * t.acc_len + j] = acc_value(ar[j]);
         }
       }
     }
