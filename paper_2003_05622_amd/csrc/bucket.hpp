@@ -372,38 +372,42 @@ region_sort(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __
   }
 
   // The sorted words stay in LDS to the end: sorted position j holds the place (inside the
-  // region) of its pair in the low 16 bits.  Stage 0 orders by the bits [lo, hb).  If two
-  // different keys then agree in all of those bits (rare), stage 1 orders by the bits below lo
-  // and stage 2, stable, by [lo, hb) again, so that all 64 bits count.  One sort loop serves
-  // all stages.  Afterwards the rounds are taken four at a time, so that few gathered keys
-  // are in registers at once.
+  // region) of its pair in the low 16 bits.  The region is ordered by the bits [lo, hb) first;
+  // if two different keys then agree in all of those bits (rare with 32 of them), it is
+  // ordered again, stably, piece by piece from the lowest bits up, so that all 64 bits count.
+  // One sort loop serves all pieces.  Afterwards the rounds are taken four at a time, so that
+  // few gathered keys are in registers at once.
 #pragma unroll
   for (int r = 0; r < ITEMS; ++r) {
     const u32 q = r * kChunkThreads + tid;
     if (q < cnt) L.words[q] = (((key[r] >> lo) & bit_mask) << 16) | q;
   }
+  __syncthreads();
   u32 head_bits = 0;       // bit k: the key at sorted position k * 512 + tid differs from the key before it
   const u32 last_j = cnt - 1;          // (cnt > 0 here) loads behind the region's end repeat its last pair
-  for (int stage = 0; stage < 3; ++stage) {
-    if (stage == 1) {
-#pragma unroll 1
-      for (int r = 0; r < ITEMS; ++r) {
-        const u32 q = r * kChunkThreads + tid;
-        if (q < cnt) L.words[q] = ((skeys[start + q] & ((1ull << lo) - 1)) << 16) | q;
-      }
-    } else if (stage == 2) {
+  // piece of the key the coming sort orders by: bits [piece_lo, piece_lo + piece_bits).  First
+  // [lo, hb); if that leaves different keys side by side (redo), the bits below lo from the
+  // bottom up, at most 32 at a time (a word has room for 32), and then [lo, hb) again.
+  int piece_lo = lo, piece_bits = n_bits;
+  bool redo = false;
+  while (true) {
+    lds_radix_sort_any<kChunkThreads, ITEMS, ORDERED>(L.words, cnt, 16, (piece_bits + 7) / 8, L.hist);
+    if (redo && piece_lo != lo) {
+      // a piece below lo is in order: the next piece, taken in the order reached so far
+      piece_lo += piece_bits;
+      piece_bits = piece_lo == lo ? n_bits : min(32, lo - piece_lo);
+      const u64 piece_mask = piece_bits == 64 ? ~0ull : (1ull << piece_bits) - 1;
 #pragma unroll 1
       for (int r = 0; r < ITEMS; ++r) {
         const u32 q = r * kChunkThreads + tid;
         if (q < cnt) {
           const u32 place = (u32)L.words[q] & 0xFFFFu;
-          L.words[q] = (((skeys[start + place] >> lo) & bit_mask) << 16) | place;
+          L.words[q] = (((skeys[start + place] >> piece_lo) & piece_mask) << 16) | place;
         }
       }
+      __syncthreads();
+      continue;
     }
-    __syncthreads();
-    lds_radix_sort_any<kChunkThreads, ITEMS, ORDERED>(L.words, cnt, 16, stage == 1 ? (lo + 7) / 8 : top_pass, L.hist);
-    if (stage == 1) continue;
     bool bad = false;
     head_bits = 0;
 #pragma unroll
@@ -436,7 +440,18 @@ region_sort(const u64* __restrict__ skeys, const u64* __restrict__ spay, u64* __
         }
       }
     }
-    if (!__syncthreads_or(bad && lo > 0 && stage == 0)) break;
+    if (redo || !__syncthreads_or(bad && lo > 0)) break;
+    // two different keys agreed in all of the bits [lo, hb): start over from the lowest bits,
+    // in the order the pairs arrived in
+    redo = true;
+    piece_lo = 0;
+    piece_bits = min(32, lo);
+#pragma unroll 1
+    for (int r = 0; r < ITEMS; ++r) {
+      const u32 q = r * kChunkThreads + tid;
+      if (q < cnt) L.words[q] = ((skeys[start + q] & ((1ull << piece_bits) - 1)) << 16) | q;
+    }
+    __syncthreads();
   }
 
   // heads up to each of this thread's positions: per round a wave ballot, and one scan over
