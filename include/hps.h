@@ -278,35 +278,6 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
  * so there is nothing valid to push (a later hps_push returns HPS_ESTATE). */
 hps_status hps_clear_error(hps_table* t, void* stream);
 
-/* Measurement aid, not part of the path: reads random 64-byte rows of d_rows (n_rows rows
- * of 64 bytes, device, 16-byte aligned) with the pooling kernel's access shape and grid,
- * about n_accesses of them (rounded up to a multiple of 8 per lane group: 65536 groups),
- * and writes one float per lane to d_sink (room for 262144 floats).  A benchmark times it
- * to learn the rate at which this GPU returns such rows, which bounds pooling and push. */
-hps_status hps_probe_random_rows(const void* d_rows, uint64_t n_rows, uint64_t n_accesses,
-                                 float* d_sink, void* stream);
-
-/* Stage timing for measurement.  Stages of one step: */
-enum {
-  HPS_STAGE_SORT = 0,    /* pull: order the key occurrences                        */
-  HPS_STAGE_UNIQUE = 1,  /* pull: unique keys, inverse, grouping                   */
-  HPS_STAGE_LOOKUP = 2,  /* pull: find or insert every unique key                  */
-  HPS_STAGE_POOL = 3,    /* pull: row gather + bag sums                            */
-  HPS_STAGE_PUSH = 4,    /* push: reduce by key + optimizer update                 */
-  HPS_N_STAGES = 5
-};
-
-/* While bit s of stage_mask is set, every pull/push brackets stage s with a pair
- * of HIP events recorded on the call's stream (at most 4096 pairs per stage are
- * kept between two hps_stage_times calls; later ones are dropped).  Setting the
- * mask discards pairs recorded so far. */
-hps_status hps_set_stage_timing(hps_table* t, uint32_t stage_mask);
-
-/* Waits for the recorded events and adds up, per stage, the elapsed milliseconds
- * (h_ms_sum[HPS_N_STAGES]) and the number of pairs (h_count[HPS_N_STAGES]); the
- * recorded pairs are then discarded.  Host arrays. */
-hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count);
-
 /* Frees the host object; device memory stays with the caller. */
 hps_status hps_destroy(hps_table* t);
 

@@ -83,7 +83,7 @@ def lib() -> ctypes.CDLL:
         L.hps_clear.restype = st
         L.hps_clear.argtypes = [vp, vp]
         L.hps_probe_random_rows.restype = st
-        L.hps_probe_random_rows.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, vp, vp]
+        L.hps_probe_random_rows.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint64, vp, vp]
         L.hps_set_stage_timing.restype = st
         L.hps_set_stage_timing.argtypes = [vp, u32]
         L.hps_stage_times.restype = st
@@ -118,11 +118,12 @@ def _ptr(t) -> Optional[int]:
 
 
 def probe_random_rows(rows, n_accesses: int, sink) -> None:
-    """Measurement aid: about n_accesses random reads of the 64-byte rows of `rows` (a float32
-    CUDA tensor of shape [n_rows, 16]); `sink` needs 262144 floats."""
-    assert rows.dim() == 2 and rows.shape[1] == 16 and sink.numel() >= 262144
-    _check(lib().hps_probe_random_rows(_ptr(rows), rows.shape[0], n_accesses, _ptr(sink), _stream()),
-           "hps_probe_random_rows")
+    """Measurement aid: about n_accesses random reads of the rows of `rows` (a float32 CUDA
+    tensor of shape [n_rows, 16] or [n_rows, 64]: 64- or 256-byte rows); `sink` needs 262144
+    floats."""
+    assert rows.dim() == 2 and rows.shape[1] in (16, 64) and sink.numel() >= 262144
+    _check(lib().hps_probe_random_rows(_ptr(rows), rows.shape[0], rows.shape[1] * 4, n_accesses,
+                                       _ptr(sink), _stream()), "hps_probe_random_rows")
 
 
 class HpsTable:

@@ -3,6 +3,7 @@
 // insert / pull / push / get / dump.  No device memory is allocated here.
 
 #include "../../include/hps.h"
+#include "../../include/hps_measure.h"
 
 #include <hip/hip_runtime.h>
 
@@ -1063,16 +1064,22 @@ hps_status hps_stage_times(hps_table* t, double* h_ms_sum, uint32_t* h_count) {
   return rc;
 }
 
-hps_status hps_probe_random_rows(const void* d_rows, uint64_t n_rows, uint64_t n_accesses,
-                                 float* d_sink, void* stream) {
+hps_status hps_probe_random_rows(const void* d_rows, uint64_t n_rows, uint32_t row_bytes,
+                                 uint64_t n_accesses, float* d_sink, void* stream) {
   if (!d_rows || !d_sink || n_rows == 0 || (uintptr_t)d_rows % 16) return HPS_EINVAL;
+  if (row_bytes != 64 && row_bytes != 256) return HPS_EINVAL;
   const unsigned blocks = kPoolMaxBlocks;
-  const uint64_t groups = (uint64_t)blocks * (kPoolThreads / 4);
+  const uint64_t groups = (uint64_t)blocks * (kPoolThreads / (row_bytes / 16));
   uint64_t per_group = (n_accesses + groups - 1) / groups;
   per_group = (per_group + kPoolInFlight - 1) / kPoolInFlight * kPoolInFlight;
   if (per_group == 0 || per_group > 0xFFFFFFF0ull) return HPS_EINVAL;
-  random_row_probe<<<blocks, kPoolThreads, 0, static_cast<hipStream_t>(stream)>>>(
-      static_cast<const float4*>(d_rows), n_rows, (u32)per_group, d_sink);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (row_bytes == 64)
+    random_row_probe<4><<<blocks, kPoolThreads, 0, s>>>(static_cast<const float4*>(d_rows), n_rows,
+                                                        (u32)per_group, d_sink);
+  else
+    random_row_probe<16><<<blocks, kPoolThreads, 0, s>>>(static_cast<const float4*>(d_rows), n_rows,
+                                                         (u32)per_group, d_sink);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 

@@ -93,15 +93,16 @@ pool_bags(TableView t, const i32* __restrict__ offsets, u32 n_bags, u32 n,
   else pool_bags_as<LPR, COLS, false>(t, offsets, n_bags, n, inverse, rows, pooled, inv_len);
 }
 
-// Measurement aid, not part of the path: reads random 64-byte rows of an array the way the
-// pooling kernel reads table rows (4 lanes x 16 bytes per row, eight rows in flight per
-// lane group, same block size and grid) and nothing else, so that a benchmark can time
+// Measurement aid, not part of the path: reads random rows of LPR * 16 bytes of an array the
+// way the pooling kernel reads table rows (LPR lanes x 16 bytes per row, eight rows in flight
+// per lane group, same block size and grid) and nothing else, so that a benchmark can time
 // the rate at which this GPU returns such rows.  Every lane group takes per_group rows
-// (a multiple of 8) at pseudo-random places; the sums go to sink[group * 4 + lane] only
+// (a multiple of 8) at pseudo-random places; the sums go to sink[group * LPR + lane] only
 // to keep the loads alive.
+template <int LPR>
 __global__ void __launch_bounds__(kPoolThreads)
 random_row_probe(const float4* __restrict__ rows, u64 n_rows, u32 per_group, float* __restrict__ sink) {
-  const u32 group = (blockIdx.x * kPoolThreads + threadIdx.x) / 4, sub = threadIdx.x % 4;
+  const u32 group = (blockIdx.x * kPoolThreads + threadIdx.x) / LPR, sub = threadIdx.x % LPR;
   u64 state = mix64((u64)group + 1);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (u32 i = 0; i < per_group; i += kPoolInFlight) {
@@ -109,12 +110,12 @@ random_row_probe(const float4* __restrict__ rows, u64 n_rows, u32 per_group, flo
 #pragma unroll
     for (int k = 0; k < kPoolInFlight; ++k) {
       state = state * 6364136223846793005ull + 1442695040888963407ull;
-      v[k] = rows[__umul64hi(state, n_rows) * 4 + sub];
+      v[k] = rows[__umul64hi(state, n_rows) * LPR + sub];
     }
 #pragma unroll
     for (int k = 0; k < kPoolInFlight; ++k) { acc.x += v[k].x; acc.y += v[k].y; acc.z += v[k].z; acc.w += v[k].w; }
   }
-  sink[(u64)group * 4 + sub] = acc.x + acc.y + acc.z + acc.w;
+  sink[(u64)group * LPR + sub] = acc.x + acc.y + acc.z + acc.w;
 }
 
 }  // namespace hps

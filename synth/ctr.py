@@ -157,7 +157,7 @@ CONFIGS = {
                            dim=16, n_examples=8192, n_slots=100, bag_kind="poisson",
                            bag_mean=5.0, zipf_s=1.05, fresh_frac=0.20, fresh_mode="counter",
                            lr=0.05, seed=3, steps=50),
-    "large": Config("large", n_prefill=1_000_000_000 - 16_000_000, capacity=1_000_000_000,
+    "large": Config("large", n_prefill=1_000_000_000 - 40_000_000, capacity=1_000_000_000,
                     dim=16, n_examples=16384, n_slots=200, bag_kind="poisson", bag_mean=3.0,
                     zipf_s=1.05, fresh_frac=0.05, fresh_mode="counter", lr=0.05, seed=4),
     "skewed": Config("skewed", n_prefill=1 << 28, capacity=1 << 28, dim=64,
