@@ -121,6 +121,7 @@ typedef struct {
                                because the keys did not suit the bucket form          */
   uint64_t n_full_fallbacks;  /* times the dedup's plain form went over to sorting by all
                                64 key bits for a while (keys in clusters far apart)   */
+  double load_factor;       /* size / n_slots                                      */
   int32_t error;            /* sticky device status (0 or a negative hps_status)   */
   int32_t pull_outstanding; /* 1 between a pull and its push                       */
 } hps_stats_t;
@@ -272,6 +273,13 @@ hps_status hps_dump_dirty(hps_table* t, uint64_t* d_keys_out, float* d_weights_o
 
 /* Waits for the stream and fills *h_out (host). */
 hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
+
+/* Section 4.1: the table is open-addressing with linear probing over lines of eight slots.
+ * Scans the whole slot array and reports how many lines a lookup reads to find a stored key
+ * (1 = the key sits in the line its hash names): the mean over all stored keys and the most for
+ * one key (0 and 0 for an empty table).  Waits for the stream.  A diagnostic: it reads every
+ * slot key, 8 bytes per slot. */
+hps_status hps_probe_lengths(hps_table* t, double* h_mean, uint64_t* h_max, void* stream);
 
 /* Clears the sticky device status and abandons the mini-batch between hps_prepare / a
  * pull and its push, if there is one: while the status was set its kernels did nothing,

@@ -14,7 +14,7 @@ ROWS_F32, ROWS_BF16 = 0, 1
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",
            "hps_push", "hps_set_pooling", "hps_accumulate", "hps_accumulate_static", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
-           "hps_stats", "hps_clear_error", "hps_clear", "hps_probe_random_rows",
+           "hps_stats", "hps_probe_lengths", "hps_clear_error", "hps_clear", "hps_probe_random_rows",
            "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
 
 STAGES = ("sort", "unique", "lookup", "pool", "push")
@@ -31,7 +31,7 @@ class Stats(ctypes.Structure):
                 ("n_slots", ctypes.c_uint64), ("last_n_keys", ctypes.c_uint64),
                 ("last_n_unique", ctypes.c_uint64), ("last_n_inserted", ctypes.c_uint64),
                 ("last_n_absent", ctypes.c_uint64), ("n_plain_fallbacks", ctypes.c_uint64),
-                ("n_full_fallbacks", ctypes.c_uint64),
+                ("n_full_fallbacks", ctypes.c_uint64), ("load_factor", ctypes.c_double),
                 ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
 
 
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.hps_accumulate_static.argtypes = [vp, vp, u64, vp, vp]
         L.hps_stats.restype = st
         L.hps_stats.argtypes = [vp, ctypes.POINTER(Stats), vp]
+        L.hps_probe_lengths.restype = st
+        L.hps_probe_lengths.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(u64), vp]
         L.hps_clear_error.restype = st
         L.hps_clear_error.argtypes = [vp, vp]
         L.hps_clear.restype = st
@@ -187,6 +189,11 @@ class HpsTable:
 
     def prepare(self, keys, offsets, n_examples: int, n_slots: int) -> None:
         assert offsets.numel() == n_examples * n_slots + 1
+        import torch
+        # the inputs may have been allocated on another stream than the one the dedup runs on
+        cur = torch.cuda.current_stream()
+        keys.record_stream(cur)
+        offsets.record_stream(cur)
         _check(lib().hps_prepare(self._h, _ptr(keys), keys.numel(), _ptr(offsets), n_examples,
                                  n_slots, _stream()), "hps_prepare")
         self._prepared = (keys.numel(), n_examples * n_slots, keys, offsets)
@@ -272,6 +279,13 @@ class HpsTable:
         cnt = (ctypes.c_uint32 * len(STAGES))()
         _check(lib().hps_stage_times(self._h, ms, cnt), "hps_stage_times")
         return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
+
+    def probe_lengths(self) -> Tuple[float, int]:
+        """(mean, maximum) number of lines a lookup reads to find a stored key."""
+        mean, most = ctypes.c_double(), ctypes.c_uint64()
+        _check(lib().hps_probe_lengths(self._h, ctypes.byref(mean), ctypes.byref(most), _stream()),
+               "hps_probe_lengths")
+        return mean.value, most.value
 
     def clear(self) -> None:
         """Empties the table (settings stay)."""

@@ -6,7 +6,8 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "hps.hip")
-LIB = os.path.join(_HERE, "libhps.so")
+# HPS_LIB: load this already built library instead (the sanitizer run of the host-side tests)
+LIB = os.environ.get("HPS_LIB") or os.path.join(_HERE, "libhps.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",

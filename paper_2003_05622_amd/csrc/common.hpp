@@ -39,6 +39,9 @@ struct TableState {
   u32 made_shard[kCountShards];
   u32 miss_overflow;            // the list of missing keys did not fit: scan instead
   u32 probe_bad;                // result word of probe_lane_order (written once, at creation)
+  // hps_probe_lengths: lines looked at to find each stored key, summed / the most for one key
+  unsigned long long probe_sum;
+  unsigned long long probe_max;
 };
 
 // Where a mini-batch's keys lie, estimated from a sample of them (sort_prepare).  The

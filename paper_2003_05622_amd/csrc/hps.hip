@@ -735,6 +735,7 @@ static bool mini_batch_ok(const hps_table* t, const uint64_t* d_keys, uint64_t n
                           const int32_t* d_offsets, uint32_t n_examples, uint32_t n_slots) {
   if (!t || !d_offsets || (n_keys && !d_keys)) return false;
   if (n_keys > t->max_keys || (uint64_t)n_examples * n_slots > t->max_bags) return false;
+  if (n_keys && (uint64_t)n_examples * n_slots == 0) return false;      // keys, but no bag to hold them
   return (uintptr_t)d_keys % 8 == 0 && (uintptr_t)d_offsets % 4 == 0;
 }
 
@@ -777,6 +778,10 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
   const ContextLayout& C = t->wl.c[c];
   PullCtx* ctx = t->ctx(c);
   if (hipStreamWaitEvent(s, cx.ready, 0) != hipSuccess) return HPS_EDEVICE;
+  // the lookup rewrites the work lists that both contexts share and the pooling reads rows: order
+  // them after the push of the mini-batch before, should that have run on another stream
+  const hps_table::Context& other = t->cx[1 - c];
+  if (other.released_set && hipStreamWaitEvent(s, other.released, 0) != hipSuccess) return HPS_EDEVICE;
   // a2: look up every unique key, create the missing ones
   stage_mark(t, HPS_STAGE_LOOKUP, s);
   if (cx.n_keys) {
@@ -825,7 +830,7 @@ hps_status hps_push(hps_table* t, const float* d_pooled_grads, void* stream) {
   if ((uintptr_t)d_pooled_grads % 16) return HPS_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   t->current = -1;
-  if (cx.n_keys) {
+  if (cx.n_keys && cx.n_bags) {
     PushArgs a;
     fill_push_args(t, c, d_pooled_grads,
                    t->opt.kind == HPS_OPT_ADAGRAD_ELEMENTWISE ? kStepElementwise : kStepRowwise, a);
@@ -880,7 +885,8 @@ hps_status hps_accumulate(hps_table* t, const uint64_t* d_keys, uint64_t n, cons
   if (t->current >= 0 || t->prepared >= 0) return HPS_ESTATE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hps_table::Context& cx = t->cx[0];
-  if (cx.released_set && hipStreamWaitEvent(s, cx.released, 0) != hipSuccess) return HPS_EDEVICE;
+  for (int k = 0; k < 2; ++k)      // after the last push of either context (shared work lists, table rows)
+    if (t->cx[k].released_set && hipStreamWaitEvent(s, t->cx[k].released, 0) != hipSuccess) return HPS_EDEVICE;
   if (t->scratch_set && hipStreamWaitEvent(s, t->scratch_free, 0) != hipSuccess) return HPS_EDEVICE;
   const hps_status rc = accumulate_launches(t, d_keys, n, d_values, s);
   if (rc != HPS_OK) return rc;
@@ -1029,8 +1035,24 @@ hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream) {
   h_out->last_n_absent = (uint64_t)st.absent;
   h_out->n_plain_fallbacks = t->n_fallbacks;
   h_out->n_full_fallbacks = t->n_full_fallbacks;
+  h_out->load_factor = (double)st.size / (double)t->n_slots;
   h_out->error = st.error;
   h_out->pull_outstanding = t->current >= 0 ? 1 : 0;
+  return HPS_OK;
+}
+
+hps_status hps_probe_lengths(hps_table* t, double* h_mean, uint64_t* h_max, void* stream) {
+  if (!t || !h_mean || !h_max) return HPS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  clear_probe_lengths<<<1, 1, 0, s>>>(t->view.st);
+  probe_length_scan<<<4096, 256, 0, s>>>(t->view);
+  if (!launch_ok()) return HPS_EDEVICE;
+  TableState st;
+  if (hipMemcpyAsync(&st, t->view.st, sizeof(st), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return HPS_EDEVICE;
+  *h_mean = st.size ? (double)st.probe_sum / (double)st.size : 0.0;
+  *h_max = st.probe_max;
   return HPS_OK;
 }
 

@@ -589,4 +589,32 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
   }
 }
 
+// How many lines a lookup reads to find each stored key (1 = the key sits in the line its
+// hash names): sum and maximum over all stored keys, into st->probe_sum / probe_max (zero on
+// entry).
+__global__ void __launch_bounds__(256) probe_length_scan(TableView t) {
+  __shared__ unsigned long long s_sum, s_max;
+  if (threadIdx.x == 0) { s_sum = 0; s_max = 0; }
+  __syncthreads();
+  const u64 n_slots = t.n_lines * kSlotsPerLine;
+  unsigned long long sum = 0, most = 0;
+  for (u64 s = (u64)blockIdx.x * blockDim.x + threadIdx.x; s < n_slots; s += (u64)gridDim.x * blockDim.x) {
+    const u64 key = t.keys[s];
+    if (key == kEmptyKey) continue;
+    const u64 home = __umul64hi(slot_hash(key), t.n_lines), line = s / kSlotsPerLine;
+    const u64 lines = (line >= home ? line - home : line + t.n_lines - home) + 1;
+    sum += lines;
+    most = max(most, (unsigned long long)lines);
+  }
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    sum += __shfl_xor(sum, d, kWave);
+    most = max(most, (unsigned long long)__shfl_xor(most, d, kWave));
+  }
+  if (lane_id() == 0) { atomicAdd(&s_sum, sum); atomicMax(&s_max, most); }
+  __syncthreads();
+  if (threadIdx.x == 0) { atomicAdd(&t.st->probe_sum, s_sum); atomicMax(&t.st->probe_max, s_max); }
+}
+__global__ void clear_probe_lengths(TableState* st) { st->probe_sum = 0; st->probe_max = 0; }
+
 }  // namespace hps

@@ -89,6 +89,9 @@ def test_create_rejects_bad_arguments_before_touching_the_device():
     assert L.hps_insert(None, None, 0, None, None, None) == hps.EINVAL
     assert L.hps_destroy(None) == hps.EINVAL
     assert L.hps_stats(None, None, None) == hps.EINVAL
+    assert L.hps_accumulate(None, None, 0, None, None) == hps.EINVAL
+    assert L.hps_accumulate_static(None, None, 0, None, None) == hps.EINVAL
+    assert L.hps_probe_random_rows(None, 0, 64, 0, None, None) == hps.EINVAL
 
 
 def test_no_cpu_fallback_without_gpu():

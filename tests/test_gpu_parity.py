@@ -301,6 +301,10 @@ def test_edge_cases():
     assert torch.equal(pooled, torch.zeros_like(pooled))
     assert gt.stats().last_n_unique == 0
     gt.push(zero_grads)
+    # keys without a single bag to hold them: refused on the host
+    with pytest.raises(hps.HpsError) as e:
+        gt.pull(dev_keys(pre[:8]), torch.zeros(1, dtype=torch.int32, device="cuda"), 0, 4)
+    assert e.value.status == hps.EINVAL
     # one key; all-equal keys; keys around 2^32 and 2^63; raw sequential (unmixed) keys
     cases = [
         np.array([pre[5]], dtype=np.uint64),
@@ -674,6 +678,25 @@ def test_dedup_two_clusters_far_apart(dedup_form):
         assert st.n_full_fallbacks >= 1 and st.n_plain_fallbacks >= 1
     else:
         assert st.n_full_fallbacks == 0 and st.n_plain_fallbacks == 0
+
+
+def test_load_factor_and_probe_lengths():
+    """The table's occupancy figures: load factor = stored keys / slots; every stored key is found
+    within a few lines of the one its hash names (lines of eight slots, load at most 0.7)."""
+    gt = hps.HpsTable(1_000_000, 8, 1000, 10)
+    assert gt.probe_lengths() == (0.0, 0)
+    keys = synth.mix64(np.arange(700_000, dtype=np.uint64))
+    gt.insert(dev_keys(keys))
+    st = gt.stats()
+    assert st.size == 700_000 and abs(st.load_factor - 700_000 / st.n_slots) < 1e-12
+    assert 0.45 < st.load_factor < 0.5            # slots = capacity / 0.7
+    mean, most = gt.probe_lengths()
+    assert 1.0 <= mean < 1.05 and 1 <= most <= 8, (mean, most)
+    # raw consecutive ids must spread as well as hashed ones (the table hashes its keys itself)
+    gt.clear()
+    gt.insert(dev_keys(np.arange(700_000, dtype=np.uint64)))
+    mean, most = gt.probe_lengths()
+    assert 1.0 <= mean < 1.05 and 1 <= most <= 8, (mean, most)
 
 
 def test_clear_and_rebuild_for_the_next_batch():
