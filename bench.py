@@ -10,7 +10,7 @@ already resident in HBM.  Prints ONE JSON line:
   roofline   the stage that takes the most time, its algorithmic HBM bytes per launch
              over its HIP-event duration, against the 8 TB/s peak
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload
-  others     the other workloads (tiny, mid, insert_heavy, skewed) in the same launch
+  others     the other workloads (tiny, mid, insert_heavy, skewed, skewed_shifted) in the same launch
              configuration, each with its own fresh table: ms per step, unique keys/s,
              fraction of peak, stage times; insert_heavy runs its 50 consecutive steps and
              reports the first, the last and the mean
@@ -35,7 +35,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-OTHER_WORKLOADS = "tiny,mid,insert_heavy,skewed"
+OTHER_WORKLOADS = "tiny,mid,insert_heavy,skewed,skewed_shifted"
 
 
 def measured_traffic(workload, stage):
