@@ -15,7 +15,9 @@ EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert",
            "hps_prepare", "hps_pull_prepared",
            "hps_push", "hps_set_pooling", "hps_accumulate", "hps_accumulate_static", "hps_last_unique", "hps_get", "hps_dump", "hps_dump_dirty",
            "hps_stats", "hps_probe_lengths", "hps_clear_error", "hps_clear", "hps_probe_random_rows",
-           "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times")
+           "hps_destroy", "hps_strerror", "hps_set_stage_timing", "hps_stage_times",
+           "hps_mem_create", "hps_mem_fetch", "hps_mem_store", "hps_mem_complete_batch",
+           "hps_mem_take_evicted", "hps_mem_list", "hps_mem_stats", "hps_mem_destroy")
 
 STAGES = ("sort", "unique", "lookup", "pool", "push")
 
@@ -33,6 +35,12 @@ class Stats(ctypes.Structure):
                 ("last_n_absent", ctypes.c_uint64), ("n_plain_fallbacks", ctypes.c_uint64),
                 ("n_full_fallbacks", ctypes.c_uint64), ("load_factor", ctypes.c_double),
                 ("error", ctypes.c_int32), ("pull_outstanding", ctypes.c_int32)]
+
+
+class MemStats(ctypes.Structure):
+    _fields_ = [("lru_size", ctypes.c_uint64), ("lfu_size", ctypes.c_uint64),
+                ("pinned", ctypes.c_uint64), ("evicted_waiting", ctypes.c_uint64),
+                ("hits", ctypes.c_uint64), ("misses", ctypes.c_uint64)]
 
 
 _lib = None
@@ -92,6 +100,22 @@ def lib() -> ctypes.CDLL:
         L.hps_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(u32)]
         L.hps_destroy.restype = st
         L.hps_destroy.argtypes = [vp]
+        L.hps_mem_create.restype = st
+        L.hps_mem_create.argtypes = [ctypes.POINTER(vp), u32, u32, u64, u64]
+        L.hps_mem_fetch.restype = st
+        L.hps_mem_fetch.argtypes = [vp, vp, u64, u64, vp, vp, vp]
+        L.hps_mem_store.restype = st
+        L.hps_mem_store.argtypes = [vp, vp, u64, vp, vp, u64, ctypes.c_int]
+        L.hps_mem_complete_batch.restype = st
+        L.hps_mem_complete_batch.argtypes = [vp, u64]
+        L.hps_mem_take_evicted.restype = st
+        L.hps_mem_take_evicted.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
+        L.hps_mem_list.restype = st
+        L.hps_mem_list.argtypes = [vp, ctypes.c_int, vp, u64, ctypes.POINTER(u64)]
+        L.hps_mem_stats.restype = st
+        L.hps_mem_stats.argtypes = [vp, ctypes.POINTER(MemStats)]
+        L.hps_mem_destroy.restype = st
+        L.hps_mem_destroy.argtypes = [vp]
         L.hps_strerror.restype = ctypes.c_char_p
         L.hps_strerror.argtypes = [st]
         _lib = L
@@ -299,3 +323,84 @@ class HpsTable:
         e = self.stats().error
         if e != 0:
             raise HpsError(e, what)
+
+
+class MemTier:
+    """The host-memory parameter cache behind the table (include/hps_mem.h).  numpy arrays in
+    host memory; needs no GPU."""
+
+    def __init__(self, dim: int, acc_len: int, lru_capacity: int, lfu_capacity: int):
+        self.dim, self.acc_len = dim, acc_len
+        self.lru_capacity, self.lfu_capacity = lru_capacity, lfu_capacity
+        self._h = None
+        h = ctypes.c_void_p()
+        _check(lib().hps_mem_create(ctypes.byref(h), dim, acc_len, lru_capacity, lfu_capacity),
+               "hps_mem_create")
+        self._h = h
+
+    def __del__(self):
+        if self._h:
+            lib().hps_mem_destroy(self._h)
+            self._h = None
+
+    @staticmethod
+    def _keys(keys):
+        import numpy as np
+        return np.ascontiguousarray(np.asarray(keys, dtype=np.uint64))
+
+    def fetch(self, keys, batch: int):
+        import numpy as np
+        k = self._keys(keys)
+        w = np.zeros((k.size, self.dim), np.float32)
+        a = np.zeros((k.size, self.acc_len), np.float32)
+        f = np.zeros(k.size, np.uint8)
+        _check(lib().hps_mem_fetch(self._h, k.ctypes.data, k.size, batch, w.ctypes.data, a.ctypes.data,
+                                   f.ctypes.data), "hps_mem_fetch")
+        return w, a, f.astype(bool)
+
+    def store(self, keys, w, a, batch: int, visit: bool) -> None:
+        import numpy as np
+        k = self._keys(keys)
+        w = np.ascontiguousarray(np.asarray(w, np.float32).reshape(k.size, self.dim))
+        a = np.ascontiguousarray(np.asarray(a, np.float32).reshape(k.size, self.acc_len))
+        _check(lib().hps_mem_store(self._h, k.ctypes.data, k.size, w.ctypes.data, a.ctypes.data, batch,
+                                   1 if visit else 0), "hps_mem_store")
+
+    def complete_batch(self, batch: int) -> None:
+        _check(lib().hps_mem_complete_batch(self._h, batch), "hps_mem_complete_batch")
+
+    def stats(self) -> MemStats:
+        s = MemStats()
+        _check(lib().hps_mem_stats(self._h, ctypes.byref(s)), "hps_mem_stats")
+        return s
+
+    def take_evicted_arrays(self):
+        """(keys, weights, accumulators) of everything collected so far."""
+        import numpy as np
+        n = self.stats().evicted_waiting
+        k = np.zeros(n, np.uint64)
+        w = np.zeros((n, self.dim), np.float32)
+        a = np.zeros((n, self.acc_len), np.float32)
+        got = ctypes.c_uint64()
+        _check(lib().hps_mem_take_evicted(self._h, k.ctypes.data, w.ctypes.data, a.ctypes.data, n,
+                                          ctypes.byref(got)), "hps_mem_take_evicted")
+        return k[:got.value], w[:got.value], a[:got.value]
+
+    def take_evicted(self):
+        k, w, a = self.take_evicted_arrays()
+        return [(int(k[i]), w[i], a[i]) for i in range(k.size)]
+
+    def _list(self, which: int):
+        import numpy as np
+        st = self.stats()
+        n = st.lru_size if which == 0 else st.lfu_size
+        k = np.zeros(max(n, 1), np.uint64)
+        got = ctypes.c_uint64()
+        _check(lib().hps_mem_list(self._h, which, k.ctypes.data, n, ctypes.byref(got)), "hps_mem_list")
+        return [int(x) for x in k[:got.value]]
+
+    def lru_keys(self):
+        return self._list(0)
+
+    def lfu_keys(self):
+        return self._list(1)

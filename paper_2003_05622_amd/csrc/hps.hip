@@ -4,6 +4,7 @@
 
 #include "../../include/hps.h"
 #include "../../include/hps_measure.h"
+#include "../../include/hps_mem.h"
 
 #include <hip/hip_runtime.h>
 
@@ -14,6 +15,8 @@
 #include <new>
 #include <vector>
 
+#include <algorithm>
+
 #include "common.hpp"
 #include "bucket.hpp"
 #include "dedup.hpp"
@@ -22,6 +25,7 @@
 #include "push.hpp"
 #include "sort.hpp"
 #include "table.hpp"
+#include "mem_tier.hpp"
 
 using namespace hps;
 
@@ -1112,6 +1116,73 @@ hps_status hps_clear_error(hps_table* t, void* stream) {
   // (row numbers above all) may be an earlier mini-batch's, and a push must not use it.
   t->current = t->prepared = -1;
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
+}
+
+// ---- the host-memory cache behind the table (include/hps_mem.h) --------------------------
+struct hps_mem {
+  hps::MemTier tier;
+  hps_mem(uint32_t dim, uint32_t acc_len, uint64_t lru, uint64_t lfu) : tier(dim, acc_len, lru, lfu) {}
+};
+
+hps_status hps_mem_create(hps_mem** out, uint32_t dim, uint32_t acc_len, uint64_t lru_capacity,
+                          uint64_t lfu_capacity) {
+  if (!out) return HPS_EINVAL;
+  *out = nullptr;
+  if (dim == 0 || dim > 1024 || (acc_len != 1 && acc_len != dim)) return HPS_EINVAL;
+  hps_mem* m = new (std::nothrow) hps_mem(dim, acc_len, lru_capacity, lfu_capacity);
+  if (!m) return HPS_ENOMEM;
+  *out = m;
+  return HPS_OK;
+}
+
+hps_status hps_mem_fetch(hps_mem* m, const uint64_t* h_keys, uint64_t n, uint64_t batch, float* h_w,
+                         float* h_acc, uint8_t* h_found) {
+  if (!m || (n && (!h_keys || !h_w || !h_acc || !h_found))) return HPS_EINVAL;
+  try { m->tier.fetch(h_keys, n, batch, h_w, h_acc, h_found); } catch (const std::bad_alloc&) { return HPS_ENOMEM; }
+  return HPS_OK;
+}
+
+hps_status hps_mem_store(hps_mem* m, const uint64_t* h_keys, uint64_t n, const float* h_w,
+                         const float* h_acc, uint64_t batch, int visit) {
+  if (!m || (n && (!h_keys || !h_w || !h_acc)) || (visit != 0 && visit != 1)) return HPS_EINVAL;
+  try { m->tier.store(h_keys, n, h_w, h_acc, batch, visit != 0); } catch (const std::bad_alloc&) { return HPS_ENOMEM; }
+  return HPS_OK;
+}
+
+hps_status hps_mem_complete_batch(hps_mem* m, uint64_t batch) {
+  if (!m) return HPS_EINVAL;
+  try { m->tier.complete_batch(batch); } catch (const std::bad_alloc&) { return HPS_ENOMEM; }
+  return HPS_OK;
+}
+
+hps_status hps_mem_take_evicted(hps_mem* m, uint64_t* h_keys, float* h_w, float* h_acc,
+                                uint64_t max_rows, uint64_t* h_n) {
+  if (!m || !h_n || (max_rows && (!h_keys || !h_w || !h_acc))) return HPS_EINVAL;
+  *h_n = m->tier.take_evicted(h_keys, h_w, h_acc, max_rows);
+  return m->tier.evicted_waiting() ? HPS_ENOMEM : HPS_OK;
+}
+
+hps_status hps_mem_list(hps_mem* m, int which, uint64_t* h_keys, uint64_t max, uint64_t* h_n) {
+  if (!m || !h_n || (which != 0 && which != 1) || (max && !h_keys)) return HPS_EINVAL;
+  *h_n = m->tier.list(which, h_keys, max);
+  return HPS_OK;
+}
+
+hps_status hps_mem_stats(hps_mem* m, hps_mem_stats_t* h_out) {
+  if (!m || !h_out) return HPS_EINVAL;
+  h_out->lru_size = m->tier.lru_size();
+  h_out->lfu_size = m->tier.lfu_size();
+  h_out->pinned = m->tier.pinned();
+  h_out->evicted_waiting = m->tier.evicted_waiting();
+  h_out->hits = m->tier.hits();
+  h_out->misses = m->tier.misses();
+  return HPS_OK;
+}
+
+hps_status hps_mem_destroy(hps_mem* m) {
+  if (!m) return HPS_EINVAL;
+  delete m;
+  return HPS_OK;
 }
 
 }  // extern "C"

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     names = set()
-    for header in ("hps.h", "hps_measure.h"):
+    for header in ("hps.h", "hps_measure.h", "hps_mem.h"):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(hps_[a-z_]+)\s*\(", text))

@@ -743,3 +743,73 @@ def test_clear_and_rebuild_for_the_next_batch():
         assert not gt.get(dev_keys(working[:100]))[2].any()
         kk, _, _ = gt.dump()
         assert kk.numel() == 0
+
+
+def test_outer_batches_through_the_memory_tier():
+    """Algorithm 1 with all three roles: an SSD stand-in (a dictionary), the host-memory cache
+    (hps_mem_*: LRU -> LFU with pinned batches) and the HBM table, rebuilt for every batch of the
+    outer loop from exactly its working parameters.  Three outer batches of three mini-batches
+    each with overlapping working sets, against ONE flat oracle table that never forgets
+    anything: pooled sums every mini-batch, and at the end every parameter ever touched,
+    wherever it has ended up (cache or dictionary)."""
+    dim, n_bags = 8, 64
+    kw = dict(lr=0.05, eps=1e-8, init_acc=0.1, init_range=0.01, init_seed=11)
+    gt = hps.HpsTable(8000, dim, 4096, n_bags, **kw)
+    ot = OracleTable(100000, dim, **kw)
+    mem = hps.MemTier(dim, 1, 1500, 1000)
+    ssd = {}
+    rng = np.random.default_rng(21)
+    seen = set()
+    for outer in range(3):
+        batches = []
+        for _ in range(3):
+            n = int(rng.integers(1500, 2500))
+            ids = np.minimum(rng.zipf(1.2, size=n), 6000) - 1 + 1500 * outer     # the hot ids move on
+            offsets = np.sort(np.concatenate([[0, n], rng.integers(0, n + 1, size=n_bags - 1)])).astype(np.int32)
+            batches.append((synth.mix64(ids.astype(np.uint64)), offsets,
+                            rng.normal(0, 1e-3, size=(n_bags, dim)).astype(np.float32)))
+        working = np.unique(np.concatenate([b[0] for b in batches]))
+        # pull the working parameters: cache, then the SSD stand-in, then (never seen) a new row
+        w, a, found = mem.fetch(working, outer)
+        miss = working[~found]
+        if miss.size:
+            mw = np.stack([ssd[int(k)][0] if int(k) in ssd else ot.init_row(int(k)) for k in miss])
+            ma = np.stack([ssd[int(k)][1] if int(k) in ssd else np.array([kw["init_acc"]], np.float32) for k in miss])
+            for k in miss:
+                ssd.pop(int(k), None)
+            mem.store(miss, mw, ma, outer, True)
+            w[~found], a[~found] = mw, ma
+        fresh = np.array([k for k in working if int(k) not in seen], dtype=np.uint64)
+        if fresh.size:
+            ot.insert(fresh)                      # the flat table creates them with their initial rows
+        seen.update(int(k) for k in working)
+        gt.insert(dev_keys(working), torch.from_numpy(w).cuda(), torch.from_numpy(a).cuda())
+        assert gt.stats().size == working.size
+        for keys, offsets, grads in batches:
+            pooled = gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
+            want = ot.pull(keys, offsets)
+            assert gt.stats().last_n_inserted == 0 and ot.n_inserted == 0     # the working set was complete
+            assert_close(pooled.cpu().numpy(), want, "pooled, outer batch %d" % outer)
+            gt.push(torch.from_numpy(grads).cuda())
+            ot.push(grads)
+        # collect the updates, update the cache, dump what it evicts
+        k, uw, ua = gt.dump(dirty=True)
+        mem.store(k.cpu().numpy().view(np.uint64), uw.cpu().numpy(), ua.cpu().numpy(), outer, False)
+        mem.complete_batch(outer)
+        st = mem.stats()
+        assert st.pinned == 0 and st.lru_size <= 1500 and st.lfu_size <= 1000
+        ek, ew, ea = mem.take_evicted_arrays()
+        for i in range(ek.size):
+            ssd[int(ek[i])] = (ew[i].copy(), ea[i].copy())
+        gt.clear()
+    # every parameter is in exactly one place, with the values of the flat table
+    everything = np.array(sorted(seen), dtype=np.uint64)
+    w, a, found = mem.fetch(everything, 99)
+    assert (st.lru_size + st.lfu_size) == int(found.sum()) and len(ssd) == int((~found).sum())
+    for i in np.nonzero(~found)[0]:
+        w[i], a[i] = ssd[int(everything[i])]
+    ow, oa, of = ot.get(everything)
+    assert of.all()
+    assert_close(w, ow, "weights through the tiers")
+    assert_close(a, oa, "accumulators through the tiers")
+    assert len(ssd) > 0 and st.lfu_size > 0            # all three places were in use
