@@ -24,6 +24,11 @@ constexpr int kErrInternal = -5;   // HPS_EDEVICE: a dedup's cross-workgroup wai
 // fix_mixed_runs can note; beyond that one workgroup puts the whole array in order.
 constexpr u32 kMaxEvidence = 1024;
 
+// Rows of the mini-batch's most frequent keys that every workgroup of the pooling kernel keeps
+// in LDS: at most kHotBytes of them (as float32) and at most kMaxHot keys.
+constexpr u32 kHotBytes = 16384;
+constexpr u32 kMaxHot = 512;
+
 constexpr int kCountShards = 64;   // counters that many blocks add to are spread over this many words
 
 // Lives in the table's storage for the table's whole life.
@@ -70,7 +75,7 @@ struct PullCtx {
   u32 med_count[kCountShards];   // keys the push handles with one wave each, per list shard
   KeyRange range;                // written by the dedup's first kernel for the later ones
   u32 n_slow_one_key;            // ... of n_slow, in regions that one key fills at least half of
-  u32 pad;
+  u32 n_hot;                     // keys listed for the pooling kernel's LDS-resident rows (pool.hpp)
 };
 
 // Keys that make up a large share of a mini-batch (bucket.hpp).  HeavySet: ascending,

@@ -73,7 +73,7 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len, i
 // Per pull context (two of them, so that the dedup of the next mini-batch can run
 // while the current one is still between pull and push).
 struct ContextLayout {
-  size_t ctx, uniq, rows, inverse, bagperm, seg_off, inv_len;
+  size_t ctx, uniq, rows, inverse, bagperm, seg_off, inv_len, hot_list;
 };
 
 struct WorkspaceLayout {
@@ -124,6 +124,7 @@ WorkspaceLayout workspace_layout(uint64_t n, uint64_t bags, uint32_t dim) {
     L.c[k].bagperm = o; o = align_up(o + n1 * 4);
     L.c[k].seg_off = o; o = align_up(o + (n1 + 1) * 4);
     L.c[k].inv_len = o; o = align_up(o + (bags ? bags : 1) * 4);    // mean pooling: 1 / bag length
+    L.c[k].hot_list = o; o = align_up(o + kMaxHot * 8);             // (unique index, row) of the most frequent keys
   }
   L.med_list = o;    o = align_up(o + (size_t)kCountShards * L.med_cap * 4);
   L.long_list = o;   o = align_up(o + L.max_long * 8);
@@ -233,6 +234,10 @@ struct hps_table {
   uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
   int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
   bool ordered_rank;   // the GPU's LDS atomics serve a wave's lanes in lane order (sort.hpp: digit_rank)
+  // The pooling kernel keeps the most frequent keys' rows in LDS (HPS_POOL=lds).  Off unless
+  // asked for: measured slower than reading them through L2 on every workload (the hash probe
+  // per occurrence costs more than the L2 hits it saves, and the LDS halves the occupancy).
+  bool hot_rows;
   uint64_t serial;     // number of dedups so far (status words carry it modulo kEpochMod)
   uint64_t plain_serial;   // ... of them in the plain form
   // Pinned host word the lookups report into (table.hpp: OftenLists::report).  When a dedup
@@ -291,19 +296,32 @@ void stage_mark(hps_table* t, int stage, hipStream_t s) {
 }
 }  // namespace
 
+// Rows of frequent keys the pooling kernel keeps in LDS: as many as fit kHotBytes.  A key is
+// listed by the lookup if it has at least n / (8 * cap) occurrences, so that at most 8 * cap
+// keys can qualify and usually far fewer do.
+static u32 hot_capacity(uint32_t dim) {
+  const u32 cap = kHotBytes / (dim * 4);
+  return cap < kMaxHot ? cap : kMaxHot;
+}
+
 template <int LPR>
 static void launch_pool(hps_table* t, int c, float* d_pooled, hipStream_t s) {
   const hps_table::Context& cx = t->cx[c];
   const unsigned blocks = grid_for(cx.n_bags, kPoolThreads / LPR, kPoolMaxBlocks);
   float* inv_len = cx.mean ? t->w<float>(t->wl.c[c].inv_len) : nullptr;
-  if (t->dim <= (uint32_t)LPR * 4)
-    pool_bags<LPR, 1><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
-                                                      (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
-                                                      t->w<u32>(t->wl.c[c].rows), d_pooled, inv_len);
-  else
-    pool_bags<LPR, 4><<<blocks, kPoolThreads, 0, s>>>(t->view, cx.d_offsets, (u32)cx.n_bags,
-                                                      (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),
-                                                      t->w<u32>(t->wl.c[c].rows), d_pooled, inv_len);
+  const u32 cap = hot_capacity(t->dim);
+  const bool hot = t->hot_rows && cap >= 8;
+#define HPS_POOL(COLS, HOT)                                                                     \
+  pool_bags<LPR, COLS, HOT><<<blocks, kPoolThreads, 0, s>>>(                                    \
+      t->view, cx.d_offsets, (u32)cx.n_bags, (u32)cx.n_keys, t->w<i32>(t->wl.c[c].inverse),     \
+      t->w<u32>(t->wl.c[c].rows), d_pooled, inv_len, t->w<uint2>(t->wl.c[c].hot_list),          \
+      &t->ctx(c)->n_hot, cap)
+  if (t->dim <= (uint32_t)LPR * 4) {
+    if (hot) HPS_POOL(1, true); else HPS_POOL(1, false);
+  } else {
+    if (hot) HPS_POOL(4, true); else HPS_POOL(4, false);
+  }
+#undef HPS_POOL
 }
 
 template <int LPR>
@@ -493,6 +511,12 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
   ++t->lookup_serial;
   often.heavy_raw = &t->w<HeavyRing>(t->wl.heavy_raw)->raw[t->lookup_serial % kHeavyRing];
   often.heavy_min = (u32)(n_keys / kHeavyShare > kHeavyMin ? n_keys / kHeavyShare : kHeavyMin);
+  often.hot_list = t->w<uint2>(C.hot_list);
+  often.hot_cap = hot_capacity(t->dim);
+  // at most 8 * cap keys can have this many occurrences; 0 occurrences never qualify
+  often.hot_min = ~0u;                       // nothing is listed
+  if (t->hot_rows && often.hot_cap >= 8)
+    often.hot_min = (u32)(n_keys / (8ull * often.hot_cap) > 8 ? n_keys / (8ull * often.hot_cap) : 8);
   often.report = t->report;
   often.serial = (u32)t->lookup_serial;
   const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
@@ -674,6 +698,10 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
     t->dedup_mode = !mode ? 0 : std::strcmp(mode, "radix") == 0 ? 1 : std::strcmp(mode, "bucket") == 0 ? 2 : 0;
   }
 
+  {
+    const char* pool = std::getenv("HPS_POOL");
+    t->hot_rows = pool && std::strcmp(pool, "lds") == 0;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   t->ordered_rank = lane_order_holds(t->view.st, s);
   fill_u64<<<4096, 256, 0, s>>>(t->view.keys, n_slots, kEmptyKey);

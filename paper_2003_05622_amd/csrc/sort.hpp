@@ -356,6 +356,7 @@ __device__ __forceinline__ void reset_ctx(PullCtx* ctx, u32 n, u32 by_id) {
     ctx->sort_error = 0;
     ctx->n_slow = 0;
     ctx->n_slow_one_key = 0;
+    ctx->n_hot = 0;
     ctx->n_total = n;
     ctx->by_id = by_id;
   }

@@ -118,6 +118,9 @@ struct OftenLists {
   uint2* chunk_items;   // (unique index, chunk number)
   HeavyRaw* heavy_raw;  // keys with at least heavy_min occurrences are listed for the next dedup
   u32 heavy_min;
+  uint2* hot_list;      // (unique index, row) of keys with at least hot_min occurrences, for the pooling kernel
+  u32 hot_min;
+  u32 hot_cap;
   // Host memory (or null) that receives serial | flags << 32 about the dedup before this
   // lookup: kReportBucket = it took the bucket form, kReportSlow = and more than 1/8 of
   // the occurrences lay in regions that had to be ordered through global memory,
@@ -242,6 +245,7 @@ __global__ void __launch_bounds__(64) set_ctx_empty(PullCtx* ctx, u32* seg_off) 
     ctx->sort_error = 0;
     ctx->n_slow = 0;
     ctx->n_slow_one_key = 0;
+    ctx->n_hot = 0;
     ctx->n_total = 0;
     ctx->by_id = 0;
     seg_off[0] = 0;
@@ -423,6 +427,10 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         if (len >= often.heavy_min) {
           const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
           if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = key[k];
+        }
+        if (len >= often.hot_min && row != kNoRow) {
+          const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
+          if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)u, row);
         }
         if (len > kMedSeg) {
           const u32 n_chunks = (len + kChunk - 1) / kChunk;

@@ -1,7 +1,7 @@
 """Randomised parity on the GPU: seeded random shapes (dim 4..260, 0..300 000 occurrences,
 ragged bags, empty batches), key mixes (hashed Zipf, raw consecutive ids, a handful of
 distinct keys, all distinct, one heavy key, long-tailed raw ids), options (both optimizers,
-sum / mean pooling, float32 / bfloat16 rows, interleaved accumulates, the serial and the
+sum / mean pooling, float32 / bfloat16 rows, pooling with the frequent keys' rows in LDS, interleaved accumulates, the serial and the
 pipelined schedule) and dedup forms; each case is a few pull+push steps checked against the
 oracle step by step and by a final dump."""
 import numpy as np
@@ -77,10 +77,16 @@ def run_case(seed, monkeypatch, sizes=(1, 50, 3000, 70000, 300000)):
     else:
         monkeypatch.setenv("HPS_DEDUP", form)       # read when the table is created
     universe = int(rng.choice([10, 1000, 100000, 10**7]))
+    # one case in four pools with the most frequent keys' rows held in LDS (off by default)
+    lds_rows = bool(rng.integers(0, 4) == 0)
+    if lds_rows:
+        monkeypatch.setenv("HPS_POOL", "lds")       # read when the table is created
+    else:
+        monkeypatch.delenv("HPS_POOL", raising=False)
     kw = dict(opt=opt, lr=0.05, eps=1e-8, init_acc=0.1, init_range=0.01,
               init_seed=int(rng.integers(0, 2**32)))
     print("seed", seed, "dim", dim, "max bags", n_bags_max, "max n", n_max, "opt", opt, "mean", mean,
-          "bf16", bf16, "form", form, "universe", universe, flush=True)
+          "bf16", bf16, "form", form, "universe", universe, "lds rows", lds_rows, flush=True)
     capacity = max(2_000_000, 6 * n_max)
     gt = hps.HpsTable(capacity, dim, n_max, n_bags_max,
                       row_format=hps.ROWS_BF16 if bf16 else hps.ROWS_F32, **kw)
