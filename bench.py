@@ -53,15 +53,16 @@ def measured_traffic(workload, stage):
     return None
 
 
-def stage_bytes(n, u, bags, d, wb=4):
+def stage_bytes(n, u, bags, d, wb=4, acc=1):
     """Algorithmic HBM bytes of one step, per stage: what the method itself has to move
     once, with 4-byte indices and each distinct row crossing HBM once per direction.
-    wb = bytes per stored weight (4, or 2 for bfloat16 rows)."""
+    wb = bytes per stored weight (4, or 2 for bfloat16 rows); acc = accumulators per row
+    (1, or d for the elementwise Adagrad)."""
     return {
         "dedup": 8 * n + 4 * n + 8 * u,                     # read keys, write inverse, write uniq
         "lookup": 8 * u + 4 * u,                            # one slot key per unique, row id
         "pool": wb * d * u + 4 * n + 4 * bags + 4 * d * bags,  # rows, inverse, offsets, pooled
-        "push": 4 * d * bags + 4 * n + 2 * (wb * d + 4) * u,  # grads, grouping, row+acc r/w
+        "push": 4 * d * bags + 4 * n + 2 * (wb * d + 4 * acc) * u,  # grads, grouping, row+acc r/w
     }
 
 
@@ -139,6 +140,7 @@ def run_workload(name, args, headline):
     import synth
 
     cfg = synth.CONFIGS[name]
+    elementwise = args.adagrad == "elementwise"
     whole_run = name == "insert_heavy"      # the workload IS its 50 consecutive steps
     steps = cfg.steps if whole_run else (args.steps if headline else min(args.steps, 20))
     warmup = 0 if whole_run else (args.warmup if headline else min(args.warmup, 3))
@@ -166,6 +168,7 @@ def run_workload(name, args, headline):
     table = hps.HpsTable(cfg.capacity, cfg.dim, n_max, cfg.n_bags, lr=cfg.lr, eps=cfg.eps,
                          init_acc=cfg.init_acc, init_range=cfg.init_range,
                          init_seed=cfg.init_seed,
+                         opt=hps.ADAGRAD_ELEMENTWISE if elementwise else hps.ADAGRAD_ROWWISE,
                          row_format=hps.ROWS_BF16 if args.rows == "bf16" else hps.ROWS_F32)
     chunk = 1 << 23
     for lo in range(0, cfg.n_prefill, chunk):
@@ -239,7 +242,8 @@ def run_workload(name, args, headline):
     sum_u = sum(uniques[i] for i in idx)
     sum_n = sum(host_batches[i].n_keys for i in idx)
     mean_n, mean_u = sum_n / steps, sum_u / steps
-    per_stage = stage_bytes(mean_n, mean_u, cfg.n_bags, cfg.dim, 2 if args.rows == "bf16" else 4)
+    per_stage = stage_bytes(mean_n, mean_u, cfg.n_bags, cfg.dim, 2 if args.rows == "bf16" else 4,
+                            cfg.dim if elementwise else 1)
     dom_ms = timed[dominant][0] / max(timed[dominant][1], 1)
     achieved = per_stage[dominant] / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     step_bytes = sum(per_stage.values())
@@ -307,6 +311,7 @@ def run_workload(name, args, headline):
                    "schedule": "serial: pull then push on one stream" if serial
                                else "dedup of batch i+1 overlaps push of batch i",
                    "table_keys": int(st.size), "capacity": cfg.capacity, "rows": args.rows,
+                   "adagrad": args.adagrad,
                    "dim": cfg.dim, "n_examples": cfg.n_examples, "n_slots": cfg.n_slots,
                    "keys_per_step": round(mean_n, 1), "unique_per_step": round(mean_u, 1),
                    "zipf_s": cfg.zipf_s, "fresh_frac": cfg.fresh_frac,
@@ -358,6 +363,7 @@ def run_workload(name, args, headline):
         ot = oracle.OracleTable(cfg.capacity, cfg.dim, lr=cfg.lr, eps=cfg.eps,
                                 init_acc=cfg.init_acc, init_range=cfg.init_range,
                                 init_seed=cfg.init_seed,
+                                opt=oracle.ADAGRAD_ELEMENTWISE if elementwise else oracle.ADAGRAD_ROWWISE,
                                 row_format=oracle.ROWS_BF16 if args.rows == "bf16" else oracle.ROWS_F32)
         ot.declare_resident(cfg.n_prefill)
         spent, done_u, done = 0.0, 0, 0
@@ -406,6 +412,8 @@ def main():
                          "command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     ap.add_argument("--rows", choices=("f32", "bf16"), default="f32",
                     help="how the table stores weights (the arithmetic is float32 either way)")
+    ap.add_argument("--adagrad", choices=("rowwise", "elementwise"), default="rowwise",
+                    help="one accumulator per row (the default) or one per element")
     ap.add_argument("--gather-rows", type=int, default=1,
                     help="0: skip the random-row ceiling and the library gather")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,

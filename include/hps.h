@@ -274,10 +274,12 @@ hps_status hps_dump_dirty(hps_table* t, uint64_t* d_keys_out, float* d_weights_o
 /* Waits for the stream and fills *h_out (host). */
 hps_status hps_stats(hps_table* t, hps_stats_t* h_out, void* stream);
 
-/* Section 4.1: the table is open-addressing with linear probing over lines of eight slots.
- * Scans the whole slot array and reports how many lines a lookup reads to find a stored key
- * (1 = the key sits in the line its hash names): the mean over all stored keys and the most for
- * one key (0 and 0 for an empty table).  Waits for the stream.  A diagnostic: it reads every
+/* Section 4.1: the table is open-addressing with linear probing over lines of eight slots; a
+ * key's sequence starts at an even line, so that its first two lines are one 128-byte memory
+ * line (a bucket of sixteen slots, which a lookup reads at once).
+ * Scans the whole slot array and reports how many buckets a lookup reads to find a stored key
+ * (1 = the key sits in the bucket its hash names): the mean over all stored keys and the most
+ * for one key (0 and 0 for an empty table).  Waits for the stream.  A diagnostic: it reads every
  * slot key, 8 bytes per slot. */
 hps_status hps_probe_lengths(hps_table* t, double* h_mean, uint64_t* h_max, void* stream);
 

@@ -305,7 +305,7 @@ class HpsTable:
         return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
 
     def probe_lengths(self) -> Tuple[float, int]:
-        """(mean, maximum) number of lines a lookup reads to find a stored key."""
+        """(mean, maximum) number of 128-byte buckets a lookup reads to find a stored key."""
         mean, most = ctypes.c_double(), ctypes.c_uint64()
         _check(lib().hps_probe_lengths(self._h, ctypes.byref(mean), ctypes.byref(most), _stream()),
                "hps_probe_lengths")

@@ -41,7 +41,8 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 uint64_t slots_for(uint64_t capacity) {
   uint64_t s = (uint64_t)((double)capacity / kLoadFactor) + 1;
   if (s < capacity + kSlotsPerLine) s = capacity + kSlotsPerLine;
-  return (s + kSlotsPerLine - 1) / kSlotsPerLine * kSlotsPerLine;
+  // a whole number of 128-byte memory lines (two lines of slots each)
+  return (s + 2 * kSlotsPerLine - 1) / (2 * kSlotsPerLine) * (2 * kSlotsPerLine);
 }
 
 bool valid_opt(const hps_optimizer* o) {
@@ -57,14 +58,32 @@ bool valid_shape(uint64_t capacity, uint32_t dim) {
 
 struct StorageLayout {
   size_t keys, w, acc, state, total;
+  uint32_t w_pitch, acc_pitch;     // bytes from one row to the next
 };
+
+// Weights and accumulators of a row side by side (table.hpp: TableView)?
+bool rows_side_by_side(uint32_t dim, uint32_t acc_len, int row_format) {
+  const uint32_t pair = 8 * dim;
+  const char* env = std::getenv("HPS_ROWS");          // "apart": always two arrays (for comparison)
+  if (env && std::strcmp(env, "apart") == 0) return false;
+  return row_format == HPS_ROWS_F32 && acc_len == dim && (pair % 128 == 0 || 128 % pair == 0);
+}
 
 StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len, int row_format) {
   StorageLayout L;
   size_t o = 0;
   L.keys = o;  o = align_up(o + n_slots * sizeof(uint64_t));
-  L.w = o;     o = align_up(o + n_slots * (size_t)dim * (row_format == HPS_ROWS_BF16 ? 2 : sizeof(float)));
-  L.acc = o;   o = align_up(o + n_slots * (size_t)acc_len * sizeof(float));
+  const uint32_t w_bytes = dim * (row_format == HPS_ROWS_BF16 ? 2 : 4), acc_bytes = acc_len * 4;
+  if (rows_side_by_side(dim, acc_len, row_format)) {
+    L.w = o;   L.acc = o + w_bytes;
+    L.w_pitch = L.acc_pitch = w_bytes + acc_bytes;
+    o = align_up(o + n_slots * (size_t)(w_bytes + acc_bytes));
+  } else {
+    L.w = o;   o = align_up(o + n_slots * (size_t)w_bytes);
+    L.acc = o; o = align_up(o + n_slots * (size_t)acc_bytes);
+    L.w_pitch = w_bytes;
+    L.acc_pitch = acc_bytes;
+  }
   L.state = o; o = align_up(o + sizeof(TableState));
   L.total = o;
   return L;
@@ -498,7 +517,7 @@ static void launch_dedup(hps_table* t, int c, const uint64_t* d_keys, u32 n,
 
 // a2 without creating anything, for context c: rows of the unique keys (kNoRow for a
 // key the table does not hold) and the push's work lists.
-static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
+static void launch_lookup(hps_table* t, int c, uint64_t n_keys, bool create, hipStream_t s) {
   const ContextLayout& C = t->wl.c[c];
   PullCtx* ctx = t->ctx(c);
   OftenLists often;
@@ -519,11 +538,11 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, hipStream_t s) {
     often.hot_min = (u32)(n_keys / (8ull * often.hot_cap) > 8 ? n_keys / (8ull * often.hot_cap) : 8);
   often.report = t->report;
   often.serial = (u32)t->lookup_serial;
-  const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
-  lookup_keys<0><<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0, &ctx->n_unique,
-                                                        t->w<u32>(C.rows), nullptr, nullptr, nullptr,
-                                                        nullptr, nullptr, t->w<u32>(t->wl.miss_list),
-                                                        (u32)t->wl.shard_cap, often);
+  const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kPullInFlight, kProbeMaxBlocks);
+  pull_lookup<kPullInFlight><<<probe_blocks, kProbeThreads, 0, s>>>(
+      t->view, t->w<u64>(C.uniq), &ctx->n_unique, t->w<u32>(C.rows), t->w<u32>(t->wl.miss_list),
+      (u32)t->wl.shard_cap, create ? 1u : 0u, often);
+
 }
 
 static void fill_push_args(hps_table* t, int c, const float* d_rows, int kind, PushArgs& a) {
@@ -644,8 +663,10 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
   t->opt = *opt;
   char* base = static_cast<char*>(d_storage);
   t->view.keys = reinterpret_cast<u64*>(base + sl.keys);
-  t->view.w = reinterpret_cast<float*>(base + sl.w);
-  t->view.acc = reinterpret_cast<float*>(base + sl.acc);
+  t->view.w = base + sl.w;
+  t->view.acc = base + sl.acc;
+  t->view.w_pitch = sl.w_pitch;
+  t->view.acc_pitch = sl.acc_pitch;
   t->view.st = reinterpret_cast<TableState*>(base + sl.state);
   t->view.n_lines = n_slots / kSlotsPerLine;
   t->view.capacity = capacity_keys;
@@ -751,11 +772,11 @@ hps_status hps_insert(hps_table* t, const uint64_t* d_keys, uint64_t n, const fl
   const unsigned lookup_blocks = grid_for(n, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
   if (n) {
     if (d_weights)
-      lookup_keys<2><<<lookup_blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
-                                                      d_acc, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
+      lookup_keys<2><<<lookup_blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, d_weights, d_acc,
+                                                             nullptr, nullptr, nullptr);
     else
       lookup_keys<1><<<lookup_blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                      nullptr, nullptr, nullptr, nullptr, nullptr, 0, OftenLists());
+                                                             nullptr, nullptr, nullptr);
     insert_missing<<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, d_weights,
                                                     d_acc, nullptr, 0);
   }
@@ -820,7 +841,7 @@ hps_status hps_pull_prepared(hps_table* t, float* d_pooled, void* stream) {
     const unsigned probe_blocks = grid_for(cx.n_keys, kProbeGroups * kProbeInFlight, kProbeMaxBlocks);
     u32* miss_list = t->w<u32>(t->wl.miss_list);
     const u32 shard_cap = (u32)t->wl.shard_cap;
-    launch_lookup(t, c, cx.n_keys, s);
+    launch_lookup(t, c, cx.n_keys, true, s);
     insert_missing<<<probe_blocks, kProbeThreads, 0, s>>>(t->view, t->w<u64>(C.uniq), 0,
                                                           &ctx->n_unique, t->w<u32>(C.rows), nullptr,
                                                           nullptr, miss_list, shard_cap);
@@ -896,7 +917,7 @@ static hps_status accumulate_launches(hps_table* t, const uint64_t* d_keys, uint
   // the push kernels sum each group's value rows and add the sum onto the row
   launch_dedup(t, c, d_keys, (u32)n, nullptr, (u32)n, s);
   if (n) {
-    launch_lookup(t, c, n, s);
+    launch_lookup(t, c, n, false, s);
     commit_absent<<<1, 256, 0, s>>>(t->view.st, t->w<HeavyRing>(t->wl.heavy_raw),
                                    (u32)(t->lookup_serial % kHeavyRing));
     PushArgs a;
@@ -1010,8 +1031,7 @@ hps_status hps_get(hps_table* t, const uint64_t* d_keys, uint64_t n, float* d_we
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned blocks = grid_for(n, kLookupGroups * kProbeInFlight, kProbeMaxBlocks);
   lookup_keys<3><<<blocks, kProbeThreads, 0, s>>>(t->view, d_keys, n, nullptr, nullptr, nullptr,
-                                                  nullptr, d_weights_out, d_acc_out, d_found_out,
-                                                  nullptr, 0, OftenLists());
+                                                  d_weights_out, d_acc_out, d_found_out);
   return launch_ok() ? HPS_OK : HPS_EDEVICE;
 }
 

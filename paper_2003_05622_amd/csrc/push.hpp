@@ -71,7 +71,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
       }
     }
     if (sub == 0) {
-      float* G = t.acc + (u64)r * t.acc_len;
+      float* G = acc_row(t, r);
       *G = acc_marked(*G);
     }
   } else if (kind == kStepRowwise) {
@@ -81,7 +81,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
       if (sub + c * LPR < dim4) ss += g[c].x * g[c].x + g[c].y * g[c].y + g[c].z * g[c].z + g[c].w * g[c].w;
 #pragma unroll
     for (int d = LPR / 2; d > 0; d >>= 1) ss += __shfl_xor(ss, d, kWave);
-    float* G = t.acc + (u64)r;
+    float* G = acc_row(t, r);
     const float Gn = acc_value(*G) + ss / (float)t.dim;
     const float scale = lr / (sqrtf(Gn) + eps);
 #pragma unroll
@@ -95,7 +95,7 @@ __device__ __forceinline__ void adagrad_row(const TableView& t, u32 r, const flo
     }
     if (sub == 0) *G = acc_marked(Gn);
   } else {
-    float4* G = reinterpret_cast<float4*>(t.acc + (u64)r * t.dim);
+    float4* G = reinterpret_cast<float4*>(acc_row(t, r));
 #pragma unroll
     for (int c = 0; c < COLS; ++c) {
       const u32 col = sub + c * LPR;

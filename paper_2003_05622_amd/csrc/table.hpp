@@ -21,8 +21,16 @@ namespace hps {
 
 struct TableView {
   u64* keys;
-  float* w;
-  float* acc;
+  // Row r's weights start w_pitch * r bytes after w, its accumulator(s) acc_pitch * r bytes
+  // after acc.  Two layouts: weights and accumulators in arrays of their own, or (float32
+  // rows with one accumulator per element, where a row's 8 * dim bytes divide the 128-byte
+  // memory line or are a multiple of it) side by side, acc = w + 4 * dim and both pitches
+  // 8 * dim: the push then finds a row's accumulators in the line(s) it fetched for the
+  // weights, and the pooling fetches a full line per 64-byte row either way.
+  char* w;
+  char* acc;
+  u32 w_pitch;
+  u32 acc_pitch;
   TableState* st;
   u64 n_lines;      // n_slots / 8
   u64 capacity;
@@ -43,14 +51,19 @@ __device__ __forceinline__ u32 bf16_nearest(float f) {
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;     // NaN stays NaN
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
+__device__ __forceinline__ char* w_row(const TableView& t, u64 row) { return t.w + row * t.w_pitch; }
+// The accumulator(s) of row `row`.
+__device__ __forceinline__ float* acc_row(const TableView& t, u64 row) {
+  return reinterpret_cast<float*>(t.acc + row * t.acc_pitch);
+}
 // Element j of row `row`.
 __device__ __forceinline__ float load_w(const TableView& t, u64 row, u32 j) {
-  if (t.bf16) return bf16_value(reinterpret_cast<const unsigned short*>(t.w)[row * t.dim + j]);
-  return t.w[row * t.dim + j];
+  if (t.bf16) return bf16_value(reinterpret_cast<const unsigned short*>(w_row(t, row))[j]);
+  return reinterpret_cast<const float*>(w_row(t, row))[j];
 }
 __device__ __forceinline__ void store_w(const TableView& t, u64 row, u32 j, float v) {
-  if (t.bf16) reinterpret_cast<unsigned short*>(t.w)[row * t.dim + j] = (unsigned short)bf16_nearest(v);
-  else t.w[row * t.dim + j] = v;
+  if (t.bf16) reinterpret_cast<unsigned short*>(w_row(t, row))[j] = (unsigned short)bf16_nearest(v);
+  else reinterpret_cast<float*>(w_row(t, row))[j] = v;
 }
 // Elements 4*col4 .. 4*col4+3 of row `row` (dim is a multiple of 4: one 16- or 8-byte access).
 // Loops that keep several loads in flight take the format as a template argument and
@@ -70,9 +83,8 @@ template <> struct StoredW4<true> {
 };
 template <bool BF16>
 __device__ __forceinline__ StoredW4<BF16> load_stored_w4(const TableView& t, u64 row, u32 col4) {
-  const u64 at = row * (t.dim >> 2) + col4;
   StoredW4<BF16> s;
-  s.raw = reinterpret_cast<const decltype(s.raw)*>(t.w)[at];
+  s.raw = reinterpret_cast<const decltype(s.raw)*>(w_row(t, row))[col4];
   return s;
 }
 template <bool BF16>
@@ -83,12 +95,11 @@ __device__ __forceinline__ float4 load_w4(const TableView& t, u64 row, u32 col4)
   return t.bf16 ? load_w4_as<true>(t, row, col4) : load_w4_as<false>(t, row, col4);
 }
 __device__ __forceinline__ void store_w4(const TableView& t, u64 row, u32 col4, float4 v) {
-  const u64 at = row * (t.dim >> 2) + col4;
   if (t.bf16)
-    reinterpret_cast<uint2*>(t.w)[at] = make_uint2(bf16_nearest(v.x) | (bf16_nearest(v.y) << 16),
+    reinterpret_cast<uint2*>(w_row(t, row))[col4] = make_uint2(bf16_nearest(v.x) | (bf16_nearest(v.y) << 16),
                                                    bf16_nearest(v.z) | (bf16_nearest(v.w) << 16));
   else
-    reinterpret_cast<float4*>(t.w)[at] = v;
+    reinterpret_cast<float4*>(w_row(t, row))[col4] = v;
 }
 
 constexpr int kProbeThreads = 256;
@@ -98,8 +109,12 @@ constexpr int kProbeInFlight = 8;                             // keys a group pr
 // 16-byte load: a wave's load instruction then asks for sixteen lines instead of eight, and
 // the rate at which lines come back follows the lines asked for per instruction.
 constexpr int kLookupLanes = 4;
+// Keys a group of the pull's lookup has in flight (two, four and eight were measured: two and
+// four run alike, eight needs too many registers for enough waves per SIMD).
+constexpr int kPullInFlight = 4;
 constexpr int kLookupGroups = kProbeThreads / kLookupLanes;
 constexpr int kProbeMaxBlocks = 1024;
+constexpr u32 kNoSlot = ~0u;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
 constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
 constexpr u32 kShortSeg = 16;            // occurrences handled serially by one lane group
@@ -301,6 +316,12 @@ __device__ __forceinline__ u32 probe_find(const TableView& t, u64 key, u32 sub, 
   return kNoRow;
 }
 
+// Where a key's probe sequence starts: an even line (n_lines is even), so that a 128-byte
+// memory line holds the first two lines of the sequence.
+__device__ __forceinline__ u64 home_line(const TableView& t, u64 key) {
+  return 2 * __umul64hi(slot_hash(key), t.n_lines >> 1);
+}
+
 // The same for a group of kLookupLanes lanes: lane `sub` holds slots 2 * sub and 2 * sub + 1 of
 // the line in `pair`.
 __device__ __forceinline__ u32 group4_bits(u64 ballot) {
@@ -351,40 +372,48 @@ __device__ __forceinline__ u32 probe_find_or_claim(const TableView& t, u64 key, 
   return kNoRow;
 }
 
-// MODE 0  pull: rows[u] = slot or kNoRow, missing keys counted
+// For a group of kLookupLanes lanes, after probe_find4 has returned kNoRow: claims a free slot
+// for the key, starting at `line` (whose slots `pair` holds; they may be out of date, the
+// compare-and-swap decides).  No other group creates the same key at the same time (the
+// keys of a pull are distinct), so only the free slot is raced for.  `seen` is what a first
+// compare-and-swap on slot `target` of the line returned (issued by the caller, so that
+// several keys' first attempts are in flight together).
+__device__ __forceinline__ u32 claim_after4(const TableView& t, u64 key, u32 sub, u64 line, u32 target,
+                                            u64 seen) {
+  if (seen == kEmptyKey) return (u32)(line * kSlotsPerLine + target);
+  for (u64 step = 0; step < 2 * t.n_lines; ++step) {
+    // another key took the slot, or the line is full: look at the line as it is now
+    const u64 x = load_slot_key(&t.keys[line * kSlotsPerLine + 2 * sub]);
+    const u64 y = load_slot_key(&t.keys[line * kSlotsPerLine + 2 * sub + 1]);
+    const u32 free_slots = group4_bits(__ballot(x == kEmptyKey)) | (group4_bits(__ballot(y == kEmptyKey)) << 4);
+    if (!free_slots) { line = line + 1 == t.n_lines ? 0 : line + 1; continue; }
+    const u32 b = __ffs(free_slots) - 1;
+    const u32 slot = 2 * (b & 3u) + (b >> 2);
+    u64 got = 0;
+    if (sub == (b & 3u))
+      got = atomicCAS((unsigned long long*)&t.keys[line * kSlotsPerLine + slot],
+                      (unsigned long long)kEmptyKey, (unsigned long long)key);
+    got = __shfl(got, (int)((lane_id() & ~3u) + (b & 3u)), kWave);
+    if (got == kEmptyKey) return (u32)(line * kSlotsPerLine + slot);
+  }
+  return kNoRow;
+}
+
 // MODE 1  bulk insert, initial rows: missing keys counted, nothing written
 // MODE 2  bulk insert with values: present keys overwritten, missing keys counted
 // MODE 3  get: copy the row out, found flags
-// n_keys is read from *n_keys_dev when that pointer is not null (the pull's U lives
-// on the device).  MODE 0 also lists the missing keys' indices: block b appends to
-// shard b % 64 of miss_list (shard_cap entries each); if a list does not fit, the
-// overflow flag makes insert_missing scan all keys instead.
+// (The pull has a kernel of its own: pull_lookup.)
 template <int MODE>
 __global__ void __launch_bounds__(kProbeThreads)
 lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
-            const u32* __restrict__ n_keys_dev, u32* __restrict__ rows,
+            const u32* __restrict__ n_keys_dev,
             const float* __restrict__ w_in, const float* __restrict__ acc_in,
             float* __restrict__ w_out, float* __restrict__ acc_out,
-            uint8_t* __restrict__ found_out, u32* __restrict__ miss_list, u32 shard_cap,
-            OftenLists often) {
-  __shared__ u32 s_missing, s_base, s_med, s_med_base;
-  __shared__ u32 s_list[MODE == 0 ? kMissLdsCap : 1];
-  __shared__ u32 s_med_list[MODE == 0 ? kMedLdsCap : 1];
+            uint8_t* __restrict__ found_out) {
+  __shared__ u32 s_missing;
   const u64 n_keys = n_keys_dev ? (u64)*n_keys_dev : n_keys_host;
-  if (MODE == 0 && often.report && blockIdx.x == 0 && threadIdx.x == 0) {
-    const PullCtx* c = often.ctx;
-    const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u) |
-                      ((u64)c->n_slow_one_key * 2 >= c->n_slow ? kReportOneKey : 0u) |
-                      (!c->by_id && c->n_evidence > kMaxEvidence ? kReportMixed : 0u);
-    __hip_atomic_store(often.report, (unsigned long long)often.serial | ((unsigned long long)flags << 32),
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-  }
-  if (MODE == 0 && often.ctx->sort_error != 0) {     // the dedup before this lookup failed
-    if (threadIdx.x == 0) raise_error(t.st, kErrInternal);
-    return;
-  }
   if (load_error(t.st) != 0) return;
-  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; }
+  if (threadIdx.x == 0) s_missing = 0;
   __syncthreads();
   const u32 sub = threadIdx.x % kLookupLanes;
   const u64 group = (u64)blockIdx.x * kLookupGroups + threadIdx.x / kLookupLanes;
@@ -397,7 +426,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
     for (int k = 0; k < kProbeInFlight; ++k) {
       const u64 u = u0 + (u64)k * n_groups;
       key[k] = u < n_keys ? keys[u] : 0;
-      line[k] = __umul64hi(slot_hash(key[k]), t.n_lines);
+      line[k] = home_line(t, key[k]);
     }
 #pragma unroll
     for (int k = 0; k < kProbeInFlight; ++k) {
@@ -411,46 +440,13 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
       if (key[k] == kEmptyKey) {
         if (MODE != 3) raise_error(t.st, kErrReserved);
         if (MODE == 3 && sub == 0) found_out[u] = 0;
-        if (MODE == 0 && sub == 0) rows[u] = kNoRow;
         continue;
       }
       const u32 row = probe_find4(t, key[k], sub, line[k], pair[k]);
-      if (row == kNoRow && MODE != 3 && MODE != 0) ++missing;
-      if (MODE == 0 && sub == 0) {
-        rows[u] = row;
-        if (row == kNoRow) {
-          const u32 at = atomicAdd(&s_missing, 1u);
-          if (at < kMissLdsCap) s_list[at] = (u32)u;
-        }
-        // sort the key into the push's work lists by its number of occurrences
-        const u32 len = often.seg_off[u + 1] - often.seg_off[u];
-        if (len >= often.heavy_min) {
-          const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
-          if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = key[k];
-        }
-        if (len >= often.hot_min && row != kNoRow) {
-          const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
-          if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)u, row);
-        }
-        if (len > kMedSeg) {
-          const u32 n_chunks = (len + kChunk - 1) / kChunk;
-          const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
-          often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
-          for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
-        } else if (len > kShortSeg) {
-          const u32 at = atomicAdd(&s_med, 1u);
-          if (at < kMedLdsCap) {
-            s_med_list[at] = (u32)u;
-          } else {      // buffer full: append straight to the shard
-            const u32 shard = blockIdx.x % kCountShards;
-            const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
-            if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)u;
-          }
-        }
-      }
+      if (row == kNoRow && MODE != 3) ++missing;
       if (MODE == 2 && row != kNoRow) {
         for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row, j, w_in[u * t.dim + j]);
-        float* ar = t.acc + (u64)row * t.acc_len;
+        float* ar = acc_row(t, row);
         for (u32 j = sub; j < t.acc_len; j += kLookupLanes)
           ar[j] = acc_in ? acc_value(acc_in[u * t.acc_len + j]) : t.init_acc;
       }
@@ -458,7 +454,7 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
         if (sub == 0) found_out[u] = row != kNoRow;
         if (row != kNoRow) {
           for (u32 j = sub; j < t.dim; j += kLookupLanes) w_out[u * t.dim + j] = load_w(t, row, j);
-          const float* ar = t.acc + (u64)row * t.acc_len;
+          const float* ar = acc_row(t, row);
           for (u32 j = sub; j < t.acc_len; j += kLookupLanes) acc_out[u * t.acc_len + j] = acc_value(ar[j]);
         }
       }
@@ -469,29 +465,211 @@ lookup_keys(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
     __syncthreads();
     if (threadIdx.x == 0 && s_missing) atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], s_missing);
   }
-  if (MODE == 0) {
-    __syncthreads();
-    const u32 n_med = min(s_med, kMedLdsCap);
-    if (n_med) {
-      const u32 shard = blockIdx.x % kCountShards;
-      if (threadIdx.x == 0) s_med_base = atomicAdd(&often.ctx->med_count[shard], n_med);
-      __syncthreads();
-      for (u32 i = threadIdx.x; i < n_med; i += kProbeThreads)
-        if (s_med_base + i < often.med_cap)
-          often.med_list[(u64)shard * often.med_cap + s_med_base + i] = s_med_list[i];
-    }
-    const u32 cnt = s_missing;
-    if (cnt == 0) return;
-    if (threadIdx.x == 0) s_base = atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], cnt);
-    __syncthreads();
-    const u32 base = s_base;
-    if (cnt > kMissLdsCap || base + cnt > shard_cap) {
-      if (threadIdx.x == 0) t.st->miss_overflow = 1;
-      return;
-    }
-    u32* dst = miss_list + (u64)(blockIdx.x % kCountShards) * shard_cap + base;
-    for (u32 i = threadIdx.x; i < cnt; i += kProbeThreads) dst[i] = s_list[i];
+}
+
+// ---- the pull's lookup -------------------------------------------------------------------
+// A key's probe sequence starts at an even line, so that its first two lines are one 128-byte
+// memory line (what a miss fetches anyway): four lanes look at those 16 slots at once.
+struct BucketSlots {
+  ulonglong2 a, b;      // lane sub: slots 2 sub and 2 sub + 1 of the even line (a) and of the odd one (b)
+};
+__device__ __forceinline__ BucketSlots load_bucket(const TableView& t, u64 line, u32 sub) {
+  BucketSlots s;
+  s.a = load_slot_pair(t, line, sub);
+  s.b = load_slot_pair(t, line + 1, sub);
+  return s;
+}
+// Bit b of the result: slot 2 * (b & 3) + (b >> 2) of the line holds `what`.
+__device__ __forceinline__ u32 line_bits(const ulonglong2& p, u64 what) {
+  return group4_bits(__ballot(p.x == what)) | (group4_bits(__ballot(p.y == what)) << 4);
+}
+__device__ __forceinline__ u32 slot_of_bit(u32 b) { return 2 * (b & 3u) + (b >> 2); }
+
+// rows[u] = the slot of unique key u, for u < *n_keys_dev.  Keys the table does not hold:
+//  - create == 0 (accumulate): rows[u] = kNoRow, counted in st->miss_shard;
+//  - create != 0 and the table has room for all the keys even if every one of them is new: the
+//    key is created right here, with its initial row (the line is at hand, and so are its free
+//    slots), counted in st->made_shard;
+//  - create != 0 otherwise (a pull that might overfill the table): rows[u] = kNoRow and the key
+//    is listed for insert_missing, which creates all the listed keys or none: block b appends to
+//    shard b % 64 of miss_list (shard_cap entries each); if a list does not fit, the overflow
+//    flag makes insert_missing scan all keys instead.
+// Every phase runs for all K keys a group has in flight before the next phase starts: a wave
+// waits for memory once per phase and round, not once per key (16 groups share a wave, and
+// nearly always one of them has a key that needs the next bucket, or has to be created).
+// Also sorts the keys into the push's work lists by their number of occurrences.
+template <int K>
+__global__ void __launch_bounds__(kProbeThreads)
+pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n_keys_dev,
+            u32* __restrict__ rows, u32* __restrict__ miss_list, u32 shard_cap, u32 create,
+            OftenLists often) {
+  __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made;
+  __shared__ u32 s_list[kMissLdsCap];
+  __shared__ u32 s_med_list[kMedLdsCap];
+  const u64 n_keys = *n_keys_dev;
+  if (often.report && blockIdx.x == 0 && threadIdx.x == 0) {
+    const PullCtx* c = often.ctx;
+    const u32 flags = (c->by_id ? kReportBucket : 0u) | ((u64)c->n_slow * 8 > c->n_total ? kReportSlow : 0u) |
+                      ((u64)c->n_slow_one_key * 2 >= c->n_slow ? kReportOneKey : 0u) |
+                      (!c->by_id && c->n_evidence > kMaxEvidence ? kReportMixed : 0u);
+    __hip_atomic_store(often.report, (unsigned long long)often.serial | ((unsigned long long)flags << 32),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
+  if (often.ctx->sort_error != 0) {     // the dedup before this lookup failed
+    if (threadIdx.x == 0) raise_error(t.st, kErrInternal);
+    return;
+  }
+  if (load_error(t.st) != 0) return;
+  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; s_made = 0; }
+  __syncthreads();
+  // (the size does not change while this kernel runs: every thread decides the same)
+  const bool create_here = create && t.st->size + n_keys <= t.capacity;
+  const u32 sub = threadIdx.x % kLookupLanes;
+  const u32 lane0 = lane_id() & ~3u;          // the group's first lane
+  const u64 group = (u64)blockIdx.x * kLookupGroups + threadIdx.x / kLookupLanes;
+  const u64 n_groups = (u64)gridDim.x * kLookupGroups;
+  u32 made = 0;
+  for (u64 u0 = group; u0 < n_keys; u0 += n_groups * K) {
+    u64 key[K], line[K];
+    BucketSlots slots[K];
+    u32 len[K], row[K];
+    u32 open = 0;                 // bit k: key k is still being searched for
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const u64 u = u0 + (u64)k * n_groups;
+      key[k] = u < n_keys ? keys[u] : kEmptyKey;
+      len[k] = u < n_keys ? often.seg_off[u + 1] - often.seg_off[u] : 0u;
+      line[k] = home_line(t, key[k]);
+      row[k] = kNoRow;
+      if (key[k] != kEmptyKey) open |= 1u << k;
+      else if (u < n_keys) raise_error(t.st, kErrReserved);
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+      if (open >> k & 1u) slots[k] = load_bucket(t, line[k], sub);
+    // rounds: look at the buckets at hand, fetch the next ones for the keys not settled
+    u32 to_create = 0;            // bit k: key k is absent; free[k] names the slot for it
+    u32 free_at[K];               // bits 0..2: slot, bit 3: in the bucket's odd line
+    for (u64 step = 0; step < t.n_lines; step += 2) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        if (!(open >> k & 1u)) continue;
+        const u32 hit_a = line_bits(slots[k].a, key[k]), hit_b = line_bits(slots[k].b, key[k]);
+        const u32 free_a = line_bits(slots[k].a, kEmptyKey), free_b = line_bits(slots[k].b, kEmptyKey);
+        // (a key sits in the first line of its sequence that had a free slot when it came: if
+        // the even line has a free slot the key is not in the odd one)
+        if (hit_a) {
+          row[k] = (u32)(line[k] * kSlotsPerLine + slot_of_bit(__ffs(hit_a) - 1));
+          open &= ~(1u << k);
+        } else if (free_a) {
+          free_at[k] = slot_of_bit(__ffs(free_a) - 1);
+          to_create |= 1u << k;
+          open &= ~(1u << k);
+        } else if (hit_b) {
+          row[k] = (u32)((line[k] + 1) * kSlotsPerLine + slot_of_bit(__ffs(hit_b) - 1));
+          open &= ~(1u << k);
+        } else if (free_b) {
+          free_at[k] = 8u | slot_of_bit(__ffs(free_b) - 1);
+          to_create |= 1u << k;
+          open &= ~(1u << k);
+        } else {
+          line[k] = line[k] + 2 >= t.n_lines ? 0 : line[k] + 2;
+        }
+      }
+      if (!__any(open != 0)) break;
+#pragma unroll
+      for (int k = 0; k < K; ++k)
+        if (open >> k & 1u) slots[k] = load_bucket(t, line[k], sub);
+    }
+    // keys to create: all first attempts in flight together, then whatever is left of each
+    if (create_here && __any(to_create != 0)) {
+      u64 seen[K];
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        seen[k] = 0;
+        if (!(to_create >> k & 1u)) continue;
+        const u32 slot = free_at[k] & 7u;
+        line[k] += free_at[k] >> 3;
+        if (sub == slot >> 1)
+          seen[k] = atomicCAS((unsigned long long*)&t.keys[line[k] * kSlotsPerLine + slot],
+                              (unsigned long long)kEmptyKey, (unsigned long long)key[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        if (!(to_create >> k & 1u)) continue;
+        const u32 slot = free_at[k] & 7u;
+        const u64 got = __shfl(seen[k], (int)(lane0 + (slot >> 1)), kWave);
+        row[k] = claim_after4(t, key[k], sub, line[k], slot, got);
+        if (row[k] == kNoRow) {
+          raise_error(t.st, kErrInternal);            // (cannot happen: the table has room)
+        } else {
+          if (sub == 0) ++made;
+          const u64 base = mix64(key[k] ^ t.init_seed);
+          for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row[k], j, init_weight(base, j, t.init_range));
+          float* ar = acc_row(t, row[k]);
+          for (u32 j = sub; j < t.acc_len; j += kLookupLanes) ar[j] = t.init_acc;
+        }
+      }
+    }
+    if (sub != 0) continue;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const u64 u = u0 + (u64)k * n_groups;
+      if (u >= n_keys) continue;
+      rows[u] = row[k];
+      if (key[k] == kEmptyKey) continue;
+      if (row[k] == kNoRow) {
+        const u32 at = atomicAdd(&s_missing, 1u);
+        if (at < kMissLdsCap) s_list[at] = (u32)u;
+      }
+      if (len[k] >= often.heavy_min) {
+        const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
+        if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = key[k];
+      }
+      if (len[k] >= often.hot_min && row[k] != kNoRow) {
+        const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
+        if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)u, row[k]);
+      }
+      if (len[k] > kMedSeg) {
+        const u32 n_chunks = (len[k] + kChunk - 1) / kChunk;
+        const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
+        often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
+        for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
+      } else if (len[k] > kShortSeg) {
+        const u32 at = atomicAdd(&s_med, 1u);
+        if (at < kMedLdsCap) {
+          s_med_list[at] = (u32)u;
+        } else {      // buffer full: append straight to the shard
+          const u32 shard = blockIdx.x % kCountShards;
+          const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
+          if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)u;
+        }
+      }
+    }
+  }
+  if (made) atomicAdd(&s_made, made);
+  __syncthreads();
+  if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
+  const u32 n_med = min(s_med, kMedLdsCap);
+  if (n_med) {
+    const u32 shard = blockIdx.x % kCountShards;
+    if (threadIdx.x == 0) s_med_base = atomicAdd(&often.ctx->med_count[shard], n_med);
+    __syncthreads();
+    for (u32 i = threadIdx.x; i < n_med; i += kProbeThreads)
+      if (s_med_base + i < often.med_cap)
+        often.med_list[(u64)shard * often.med_cap + s_med_base + i] = s_med_list[i];
+  }
+  const u32 cnt = s_missing;
+  if (cnt == 0) return;
+  if (threadIdx.x == 0) s_base = atomicAdd(&t.st->miss_shard[blockIdx.x % kCountShards], cnt);
+  __syncthreads();
+  const u32 base = s_base;
+  if (cnt > kMissLdsCap || base + cnt > shard_cap) {
+    if (threadIdx.x == 0) t.st->miss_overflow = 1;
+    return;
+  }
+  u32* dst = miss_list + (u64)(blockIdx.x % kCountShards) * shard_cap + base;
+  for (u32 i = threadIdx.x; i < cnt; i += kProbeThreads) dst[i] = s_list[i];
 }
 
 // Creates the keys lookup_keys found missing, if the table has room for all of them
@@ -541,14 +719,14 @@ insert_missing(TableView t, const u64* __restrict__ keys, u64 n_keys_host,
     if (!listed && rows && rows[u] != kNoRow) continue;
     const u64 key = keys[u];
     if (key == kEmptyKey) continue;
-    const u64 line = __umul64hi(slot_hash(key), t.n_lines);
+    const u64 line = home_line(t, key);
     const u64 slot_key = load_slot_key(&t.keys[line * kSlotsPerLine + sub]);
     bool created;
     const u32 row = probe_find_or_claim(t, key, sub, line, slot_key, &created);
     if (rows && sub == 0) rows[u] = row;
     if (!created) continue;
     ++made;
-    float* ar = t.acc + (u64)row * t.acc_len;
+    float* ar = acc_row(t, row);
     if (w_in) {
       for (u32 j = sub; j < t.dim; j += 8) store_w(t, row, j, w_in[u * t.dim + j]);
       for (u32 j = sub; j < t.acc_len; j += 8)
@@ -579,7 +757,7 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
     const u64 s = round * 256 + threadIdx.x;
     const u64 key = s < n_slots ? t.keys[s] : kEmptyKey;
     bool used = key != kEmptyKey;
-    if (DIRTY && used) used = acc_is_marked(t.acc[s * t.acc_len]);
+    if (DIRTY && used) used = acc_is_marked(*acc_row(t, s));
     u32 total;
     const u32 before = block_excl_sum<256>(used ? 1u : 0u, scratch, &total);
     if (threadIdx.x == 0 && total) s_base = atomicAdd(counter, (unsigned long long)total);
@@ -589,16 +767,16 @@ dump_rows(TableView t, u64* __restrict__ keys_out, float* __restrict__ w_out,
       if (o < max_rows) {
         keys_out[o] = key;
         for (u32 j = 0; j < t.dim; ++j) w_out[o * t.dim + j] = load_w(t, s, j);
-        for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = acc_value(t.acc[s * t.acc_len + j]);
-        if (DIRTY) t.acc[s * t.acc_len] = acc_value(t.acc[s * t.acc_len]);
+        for (u32 j = 0; j < t.acc_len; ++j) acc_out[o * t.acc_len + j] = acc_value(acc_row(t, s)[j]);
+        if (DIRTY) *acc_row(t, s) = acc_value(*acc_row(t, s));
       }
     }
     __syncthreads();
   }
 }
 
-// How many lines a lookup reads to find each stored key (1 = the key sits in the line its
-// hash names): sum and maximum over all stored keys, into st->probe_sum / probe_max (zero on
+// How many buckets (pairs of lines: 128 bytes) a lookup reads to find each stored key (1 = the
+// key sits in the bucket its hash names): sum and maximum over all stored keys, into st->probe_sum / probe_max (zero on
 // entry).
 __global__ void __launch_bounds__(256) probe_length_scan(TableView t) {
   __shared__ unsigned long long s_sum, s_max;
@@ -609,8 +787,8 @@ __global__ void __launch_bounds__(256) probe_length_scan(TableView t) {
   for (u64 s = (u64)blockIdx.x * blockDim.x + threadIdx.x; s < n_slots; s += (u64)gridDim.x * blockDim.x) {
     const u64 key = t.keys[s];
     if (key == kEmptyKey) continue;
-    const u64 home = __umul64hi(slot_hash(key), t.n_lines), line = s / kSlotsPerLine;
-    const u64 lines = (line >= home ? line - home : line + t.n_lines - home) + 1;
+    const u64 home = home_line(t, key), line = s / kSlotsPerLine;
+    const u64 lines = (line >= home ? line - home : line + t.n_lines - home) / 2 + 1;
     sum += lines;
     most = max(most, (unsigned long long)lines);
   }
