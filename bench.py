@@ -146,7 +146,8 @@ def run_workload(name, args, headline):
     warmup = 0 if whole_run else (args.warmup if headline else min(args.warmup, 3))
     extra_steps = 5 if headline else 0      # all-stage timing run after the timed region
     serial = not args.pipelined
-    other_steps = 8 if headline else 0      # the other schedule afterwards, for comparison
+    # the other schedule afterwards, for comparison
+    other_steps = 8 if headline and not args.one_schedule else 0
     n_batches = args.batches or min(steps + warmup + extra_steps + other_steps, 64)
     if whole_run:
         n_batches = steps                   # never reused: every step inserts fresh keys
@@ -406,6 +407,10 @@ def main():
     ap.add_argument("--pipelined", action="store_true",
                     help="time hps_prepare of the next mini-batch on a second stream while the "
                          "current one is pushed (default: plain hps_pull + hps_push per step)")
+    ap.add_argument("--one-schedule", action="store_true",
+                    help="skip the few steps of the other schedule that the headline workload runs "
+                         "after its timed region for comparison (for profiles: every dispatch of a "
+                         "kernel then belongs to the same schedule)")
     ap.add_argument("--serial", action="store_true", help="the default schedule (kept for old command lines)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a counter run of this "

@@ -539,7 +539,7 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, bool create, hip
   often.report = t->report;
   often.serial = (u32)t->lookup_serial;
   const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kPullInFlight, kProbeMaxBlocks);
-  pull_lookup<kPullInFlight><<<probe_blocks, kProbeThreads, 0, s>>>(
+  pull_lookup<<<probe_blocks, kProbeThreads, 0, s>>>(
       t->view, t->w<u64>(C.uniq), &ctx->n_unique, t->w<u32>(C.rows), t->w<u32>(t->wl.miss_list),
       (u32)t->wl.shard_cap, create ? 1u : 0u, often);
 

@@ -25,7 +25,7 @@
 namespace hps {
 
 constexpr int kPushThreads = 256;
-constexpr int kPushShortBlocks = 1024;   // fixed grids: groups, waves and blocks loop
+constexpr int kPushShortBlocks = 1024;   // fixed grids: groups, waves and blocks loop (more short blocks measured slower)
 constexpr int kPushMediumBlocks = 512;   // a multiple of kCountShards
 constexpr int kPushChunkBlocks = 512;
 constexpr int kPushLongBlocks = 256;

@@ -109,9 +109,9 @@ constexpr int kProbeInFlight = 8;                             // keys a group pr
 // 16-byte load: a wave's load instruction then asks for sixteen lines instead of eight, and
 // the rate at which lines come back follows the lines asked for per instruction.
 constexpr int kLookupLanes = 4;
-// Keys a group of the pull's lookup has in flight (two, four and eight were measured: two and
-// four run alike, eight needs too many registers for enough waves per SIMD).
-constexpr int kPullInFlight = 4;
+// Keys a group of the pull's lookup has in flight: one per lane (two, four and eight were
+// measured: two and four run alike, eight needs too many registers for enough waves per SIMD).
+constexpr int kPullInFlight = kLookupLanes;
 constexpr int kLookupGroups = kProbeThreads / kLookupLanes;
 constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kNoSlot = ~0u;
@@ -479,11 +479,42 @@ __device__ __forceinline__ BucketSlots load_bucket(const TableView& t, u64 line,
   s.b = load_slot_pair(t, line + 1, sub);
   return s;
 }
-// Bit b of the result: slot 2 * (b & 3) + (b >> 2) of the line holds `what`.
-__device__ __forceinline__ u32 line_bits(const ulonglong2& p, u64 what) {
-  return group4_bits(__ballot(p.x == what)) | (group4_bits(__ballot(p.y == what)) << 4);
-}
 __device__ __forceinline__ u32 slot_of_bit(u32 b) { return 2 * (b & 3u) + (b >> 2); }
+
+// Data movement inside a group of four lanes (a quad): full-rate DPP moves, no LDS.
+template <int CTRL> __device__ __forceinline__ u32 quad_perm(u32 v) {
+  return (u32)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, true);
+}
+// The value lane k of the quad holds (k = 0..3, a constant after unrolling).
+__device__ __forceinline__ u32 quad_lane(u32 v, int k) {
+  switch (k) {
+    case 0: return quad_perm<0x00>(v);
+    case 1: return quad_perm<0x55>(v);
+    case 2: return quad_perm<0xAA>(v);
+    default: return quad_perm<0xFF>(v);
+  }
+}
+__device__ __forceinline__ u64 quad_lane(u64 v, int k) {
+  return (u64)quad_lane((u32)v, k) | ((u64)quad_lane((u32)(v >> 32), k) << 32);
+}
+// Bitwise or over the quad, in every lane.
+__device__ __forceinline__ u32 quad_or(u32 v) {
+  v |= quad_perm<0xB1>(v);      // lanes 1 0 3 2
+  v |= quad_perm<0x4E>(v);      // lanes 2 3 0 1
+  return v;
+}
+
+// What a bucket holds for a key, as one word in every lane of the group: byte 0 = slots of the
+// even line that hold the key, byte 1 = free slots of the even line, bytes 2 and 3 the same for
+// the odd line; within a byte, bit b stands for slot 2 * (b & 3) + (b >> 2) (slot_of_bit).
+__device__ __forceinline__ u32 bucket_bits(const BucketSlots& s, u64 key, u32 sub) {
+  const u32 lo = 1u << sub, hi = 16u << sub;
+  u32 m = (s.a.x == key ? lo : 0u) | (s.a.y == key ? hi : 0u);
+  m |= (s.a.x == kEmptyKey ? lo << 8 : 0u) | (s.a.y == kEmptyKey ? hi << 8 : 0u);
+  m |= (s.b.x == key ? lo << 16 : 0u) | (s.b.y == key ? hi << 16 : 0u);
+  m |= (s.b.x == kEmptyKey ? lo << 24 : 0u) | (s.b.y == kEmptyKey ? hi << 24 : 0u);
+  return quad_or(m);
+}
 
 // rows[u] = the slot of unique key u, for u < *n_keys_dev.  Keys the table does not hold:
 //  - create == 0 (accumulate): rows[u] = kNoRow, counted in st->miss_shard;
@@ -494,15 +525,19 @@ __device__ __forceinline__ u32 slot_of_bit(u32 b) { return 2 * (b & 3u) + (b >> 
 //    is listed for insert_missing, which creates all the listed keys or none: block b appends to
 //    shard b % 64 of miss_list (shard_cap entries each); if a list does not fit, the overflow
 //    flag makes insert_missing scan all keys instead.
-// Every phase runs for all K keys a group has in flight before the next phase starts: a wave
-// waits for memory once per phase and round, not once per key (16 groups share a wave, and
-// nearly always one of them has a key that needs the next bucket, or has to be created).
 // Also sorts the keys into the push's work lists by their number of occurrences.
-template <int K>
+//
+// A group of four lanes looks at a bucket at once and has four keys in flight, one per lane:
+// each lane loads and hashes its own key and, at the end, stores its own key's row and lists it
+// (one key per lane: full waves); in between the group goes through its four keys together.
+// Every phase runs for all four keys before the next phase starts: a wave waits for memory once
+// per phase and round, not once per key (16 groups share a wave, and nearly always one of them
+// has a key that needs the next bucket, or has to be created).
 __global__ void __launch_bounds__(kProbeThreads)
 pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n_keys_dev,
             u32* __restrict__ rows, u32* __restrict__ miss_list, u32 shard_cap, u32 create,
             OftenLists often) {
+  constexpr int K = kLookupLanes;
   __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made;
   __shared__ u32 s_list[kMissLdsCap];
   __shared__ u32 s_med_list[kMedLdsCap];
@@ -529,33 +564,39 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
   const u64 group = (u64)blockIdx.x * kLookupGroups + threadIdx.x / kLookupLanes;
   const u64 n_groups = (u64)gridDim.x * kLookupGroups;
   u32 made = 0;
+  // (the bound is the same for all lanes of a group, so a group stays together)
   for (u64 u0 = group; u0 < n_keys; u0 += n_groups * K) {
+    // this lane's own key: number `sub` of the group's four
+    const u64 my_u = u0 + (u64)sub * n_groups;
+    const bool my_valid = my_u < n_keys;
+    const u64 my_key = my_valid ? keys[my_u] : kEmptyKey;
+    const u32 my_len = my_valid ? often.seg_off[my_u + 1] - often.seg_off[my_u] : 0u;
+    const u64 my_line = home_line(t, my_key);
+    if (my_valid && my_key == kEmptyKey) raise_error(t.st, kErrReserved);
     u64 key[K], line[K];
     BucketSlots slots[K];
-    u32 len[K], row[K];
+    u32 row[K];
     u32 open = 0;                 // bit k: key k is still being searched for
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const u64 u = u0 + (u64)k * n_groups;
-      key[k] = u < n_keys ? keys[u] : kEmptyKey;
-      len[k] = u < n_keys ? often.seg_off[u + 1] - often.seg_off[u] : 0u;
-      line[k] = home_line(t, key[k]);
+      key[k] = quad_lane(my_key, k);
+      line[k] = quad_lane(my_line, k);
       row[k] = kNoRow;
       if (key[k] != kEmptyKey) open |= 1u << k;
-      else if (u < n_keys) raise_error(t.st, kErrReserved);
     }
 #pragma unroll
     for (int k = 0; k < K; ++k)
       if (open >> k & 1u) slots[k] = load_bucket(t, line[k], sub);
     // rounds: look at the buckets at hand, fetch the next ones for the keys not settled
-    u32 to_create = 0;            // bit k: key k is absent; free[k] names the slot for it
+    u32 to_create = 0;            // bit k: key k is absent; free_at[k] names the slot for it
     u32 free_at[K];               // bits 0..2: slot, bit 3: in the bucket's odd line
     for (u64 step = 0; step < t.n_lines; step += 2) {
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         if (!(open >> k & 1u)) continue;
-        const u32 hit_a = line_bits(slots[k].a, key[k]), hit_b = line_bits(slots[k].b, key[k]);
-        const u32 free_a = line_bits(slots[k].a, kEmptyKey), free_b = line_bits(slots[k].b, kEmptyKey);
+        const u32 bits = bucket_bits(slots[k], key[k], sub);
+        const u32 hit_a = bits & 0xFFu, free_a = (bits >> 8) & 0xFFu;
+        const u32 hit_b = (bits >> 16) & 0xFFu, free_b = bits >> 24;
         // (a key sits in the first line of its sequence that had a free slot when it came: if
         // the even line has a free slot the key is not in the odd one)
         if (hit_a) {
@@ -611,39 +652,38 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
         }
       }
     }
-    if (sub != 0) continue;
+    // back to one key per lane: its row, and the push's work lists
+    u32 my_row = row[0];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const u64 u = u0 + (u64)k * n_groups;
-      if (u >= n_keys) continue;
-      rows[u] = row[k];
-      if (key[k] == kEmptyKey) continue;
-      if (row[k] == kNoRow) {
-        const u32 at = atomicAdd(&s_missing, 1u);
-        if (at < kMissLdsCap) s_list[at] = (u32)u;
-      }
-      if (len[k] >= often.heavy_min) {
-        const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
-        if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = key[k];
-      }
-      if (len[k] >= often.hot_min && row[k] != kNoRow) {
-        const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
-        if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)u, row[k]);
-      }
-      if (len[k] > kMedSeg) {
-        const u32 n_chunks = (len[k] + kChunk - 1) / kChunk;
-        const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
-        often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
-        for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
-      } else if (len[k] > kShortSeg) {
-        const u32 at = atomicAdd(&s_med, 1u);
-        if (at < kMedLdsCap) {
-          s_med_list[at] = (u32)u;
-        } else {      // buffer full: append straight to the shard
-          const u32 shard = blockIdx.x % kCountShards;
-          const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
-          if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)u;
-        }
+    for (int k = 1; k < K; ++k) my_row = sub == (u32)k ? row[k] : my_row;
+    if (!my_valid) continue;
+    rows[my_u] = my_row;
+    if (my_key == kEmptyKey) continue;
+    if (my_row == kNoRow) {
+      const u32 at = atomicAdd(&s_missing, 1u);
+      if (at < kMissLdsCap) s_list[at] = (u32)my_u;
+    }
+    if (my_len >= often.heavy_min) {
+      const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
+      if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = my_key;
+    }
+    if (my_len >= often.hot_min && my_row != kNoRow) {
+      const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
+      if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)my_u, my_row);
+    }
+    if (my_len > kMedSeg) {
+      const u32 n_chunks = (my_len + kChunk - 1) / kChunk;
+      const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
+      often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)my_u, first);
+      for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)my_u, c);
+    } else if (my_len > kShortSeg) {
+      const u32 at = atomicAdd(&s_med, 1u);
+      if (at < kMedLdsCap) {
+        s_med_list[at] = (u32)my_u;
+      } else {      // buffer full: append straight to the shard
+        const u32 shard = blockIdx.x % kCountShards;
+        const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
+        if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)my_u;
       }
     }
   }
