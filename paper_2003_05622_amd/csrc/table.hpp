@@ -109,13 +109,16 @@ constexpr int kProbeInFlight = 8;                             // keys a group pr
 // 16-byte load: a wave's load instruction then asks for sixteen lines instead of eight, and
 // the rate at which lines come back follows the lines asked for per instruction.
 constexpr int kLookupLanes = 4;
-// Keys a group of the pull's lookup has in flight: one per lane (two, four and eight were
-// measured: two and four run alike, eight needs too many registers for enough waves per SIMD).
-constexpr int kPullInFlight = kLookupLanes;
+// Keys a group of the pull's lookup has in flight, a multiple of the lanes of a group (two, four
+// and eight were measured: two and four run alike, eight needs too many registers: 158, three
+// waves per SIMD, a third slower; forcing five or six waves per SIMD by spilling gains nothing).
+constexpr int kPullInFlight = 4;
+static_assert(kPullInFlight % kLookupLanes == 0, "every lane of a group owns the same number of keys");
 constexpr int kLookupGroups = kProbeThreads / kLookupLanes;
 constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kNoSlot = ~0u;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
+constexpr u32 kNewLdsCap = 1024;         // created keys a block lists for its common initialisation
 constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
 constexpr u32 kShortSeg = 16;            // occurrences handled serially by one lane group
 constexpr u32 kMedSeg = 512;             // occurrences handled by one wave
@@ -537,10 +540,13 @@ __global__ void __launch_bounds__(kProbeThreads)
 pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n_keys_dev,
             u32* __restrict__ rows, u32* __restrict__ miss_list, u32 shard_cap, u32 create,
             OftenLists often) {
-  constexpr int K = kLookupLanes;
-  __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made;
+  constexpr int K = kPullInFlight;            // keys a group has in flight
+  constexpr int OWN = K / kLookupLanes;       // of which each lane owns this many
+  __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made, s_new;
   __shared__ u32 s_list[kMissLdsCap];
   __shared__ u32 s_med_list[kMedLdsCap];
+  __shared__ u64 s_new_key[kNewLdsCap];       // keys created by this block, and their rows
+  __shared__ u32 s_new_row[kNewLdsCap];
   const u64 n_keys = *n_keys_dev;
   if (often.report && blockIdx.x == 0 && threadIdx.x == 0) {
     const PullCtx* c = often.ctx;
@@ -555,7 +561,7 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
     return;
   }
   if (load_error(t.st) != 0) return;
-  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; s_made = 0; }
+  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; s_made = 0; s_new = 0; }
   __syncthreads();
   // (the size does not change while this kernel runs: every thread decides the same)
   const bool create_here = create && t.st->size + n_keys <= t.capacity;
@@ -566,130 +572,172 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
   u32 made = 0;
   // (the bound is the same for all lanes of a group, so a group stays together)
   for (u64 u0 = group; u0 < n_keys; u0 += n_groups * K) {
-    // this lane's own key: number `sub` of the group's four
-    const u64 my_u = u0 + (u64)sub * n_groups;
-    const bool my_valid = my_u < n_keys;
-    const u64 my_key = my_valid ? keys[my_u] : kEmptyKey;
-    const u32 my_len = my_valid ? often.seg_off[my_u + 1] - often.seg_off[my_u] : 0u;
-    const u64 my_line = home_line(t, my_key);
-    if (my_valid && my_key == kEmptyKey) raise_error(t.st, kErrReserved);
-    u64 key[K], line[K];
-    BucketSlots slots[K];
-    u32 row[K];
-    u32 open = 0;                 // bit k: key k is still being searched for
+    // Key k of the group's K is owned by lane k % 4 (as its number k / 4): that lane keeps the
+    // key, where its search stands and its row; the group fetches them from it when needed.
+    u64 my_key[OWN], my_line[OWN];
+    u32 my_len[OWN], my_row[OWN], my_free[OWN];
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      key[k] = quad_lane(my_key, k);
-      line[k] = quad_lane(my_line, k);
-      row[k] = kNoRow;
-      if (key[k] != kEmptyKey) open |= 1u << k;
+    for (int o = 0; o < OWN; ++o) {
+      const u64 u = u0 + (u64)(o * kLookupLanes + sub) * n_groups;
+      my_key[o] = u < n_keys ? keys[u] : kEmptyKey;
+      my_len[o] = u < n_keys ? often.seg_off[u + 1] - often.seg_off[u] : 0u;
+      if (u < n_keys && my_key[o] == kEmptyKey) raise_error(t.st, kErrReserved);
     }
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-      if (open >> k & 1u) slots[k] = load_bucket(t, line[k], sub);
+    for (int o = 0; o < OWN; ++o) {
+      my_line[o] = home_line(t, my_key[o]);
+      my_row[o] = kNoRow;
+      my_free[o] = 0;
+    }
+    u32 open = 0;                 // bit k: key k is still being searched for
+    BucketSlots slots[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const u64 key = quad_lane(my_key[k / kLookupLanes], k % kLookupLanes);
+      const u64 line = quad_lane(my_line[k / kLookupLanes], k % kLookupLanes);
+      if (key != kEmptyKey) {
+        open |= 1u << k;
+        slots[k] = load_bucket(t, line, sub);
+      }
+    }
     // rounds: look at the buckets at hand, fetch the next ones for the keys not settled
-    u32 to_create = 0;            // bit k: key k is absent; free_at[k] names the slot for it
-    u32 free_at[K];               // bits 0..2: slot, bit 3: in the bucket's odd line
+    u32 to_create = 0;            // bit k: key k is absent; its owner's my_free names the slot for it
     for (u64 step = 0; step < t.n_lines; step += 2) {
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         if (!(open >> k & 1u)) continue;
-        const u32 bits = bucket_bits(slots[k], key[k], sub);
+        const int o = k / kLookupLanes;
+        const bool mine = sub == (u32)(k % kLookupLanes);
+        const u64 key = quad_lane(my_key[o], k % kLookupLanes);
+        const u32 bits = bucket_bits(slots[k], key, sub);
         const u32 hit_a = bits & 0xFFu, free_a = (bits >> 8) & 0xFFu;
         const u32 hit_b = (bits >> 16) & 0xFFu, free_b = bits >> 24;
         // (a key sits in the first line of its sequence that had a free slot when it came: if
         // the even line has a free slot the key is not in the odd one)
         if (hit_a) {
-          row[k] = (u32)(line[k] * kSlotsPerLine + slot_of_bit(__ffs(hit_a) - 1));
+          if (mine) my_row[o] = (u32)(my_line[o] * kSlotsPerLine + slot_of_bit(__ffs(hit_a) - 1));
           open &= ~(1u << k);
         } else if (free_a) {
-          free_at[k] = slot_of_bit(__ffs(free_a) - 1);
+          if (mine) my_free[o] = slot_of_bit(__ffs(free_a) - 1);
           to_create |= 1u << k;
           open &= ~(1u << k);
         } else if (hit_b) {
-          row[k] = (u32)((line[k] + 1) * kSlotsPerLine + slot_of_bit(__ffs(hit_b) - 1));
+          if (mine) my_row[o] = (u32)((my_line[o] + 1) * kSlotsPerLine + slot_of_bit(__ffs(hit_b) - 1));
           open &= ~(1u << k);
         } else if (free_b) {
-          free_at[k] = 8u | slot_of_bit(__ffs(free_b) - 1);
+          if (mine) my_free[o] = 8u | slot_of_bit(__ffs(free_b) - 1);
           to_create |= 1u << k;
           open &= ~(1u << k);
-        } else {
-          line[k] = line[k] + 2 >= t.n_lines ? 0 : line[k] + 2;
+        } else if (mine) {
+          my_line[o] = my_line[o] + 2 >= t.n_lines ? 0 : my_line[o] + 2;
         }
       }
       if (!__any(open != 0)) break;
 #pragma unroll
-      for (int k = 0; k < K; ++k)
-        if (open >> k & 1u) slots[k] = load_bucket(t, line[k], sub);
+      for (int k = 0; k < K; ++k) {
+        const u64 line = quad_lane(my_line[k / kLookupLanes], k % kLookupLanes);
+        if (open >> k & 1u) slots[k] = load_bucket(t, line, sub);
+      }
     }
     // keys to create: all first attempts in flight together, then whatever is left of each
     if (create_here && __any(to_create != 0)) {
       u64 seen[K];
 #pragma unroll
+      for (int o = 0; o < OWN; ++o) my_line[o] += my_free[o] >> 3;        // the line of the free slot
+#pragma unroll
       for (int k = 0; k < K; ++k) {
+        const int o = k / kLookupLanes;
+        const u64 key = quad_lane(my_key[o], k % kLookupLanes);
+        const u64 line = quad_lane(my_line[o], k % kLookupLanes);
+        const u32 slot = quad_lane(my_free[o], k % kLookupLanes) & 7u;
         seen[k] = 0;
-        if (!(to_create >> k & 1u)) continue;
-        const u32 slot = free_at[k] & 7u;
-        line[k] += free_at[k] >> 3;
-        if (sub == slot >> 1)
-          seen[k] = atomicCAS((unsigned long long*)&t.keys[line[k] * kSlotsPerLine + slot],
-                              (unsigned long long)kEmptyKey, (unsigned long long)key[k]);
+        if ((to_create >> k & 1u) && sub == slot >> 1)
+          seen[k] = atomicCAS((unsigned long long*)&t.keys[line * kSlotsPerLine + slot],
+                              (unsigned long long)kEmptyKey, (unsigned long long)key);
       }
 #pragma unroll
       for (int k = 0; k < K; ++k) {
+        const int o = k / kLookupLanes;
+        const u64 key = quad_lane(my_key[o], k % kLookupLanes);
+        const u64 line = quad_lane(my_line[o], k % kLookupLanes);
+        const u32 slot = quad_lane(my_free[o], k % kLookupLanes) & 7u;
         if (!(to_create >> k & 1u)) continue;
-        const u32 slot = free_at[k] & 7u;
         const u64 got = __shfl(seen[k], (int)(lane0 + (slot >> 1)), kWave);
-        row[k] = claim_after4(t, key[k], sub, line[k], slot, got);
-        if (row[k] == kNoRow) {
+        const u32 row = claim_after4(t, key, sub, line, slot, got);
+        if (row == kNoRow) {
           raise_error(t.st, kErrInternal);            // (cannot happen: the table has room)
-        } else {
-          if (sub == 0) ++made;
-          const u64 base = mix64(key[k] ^ t.init_seed);
-          for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row[k], j, init_weight(base, j, t.init_range));
-          float* ar = acc_row(t, row[k]);
+          continue;
+        }
+        // The new row's initial values are left to the end of the kernel, where all lanes of
+        // the block share the work (here four lanes of the wave would do it while sixty wait);
+        // only a key that finds the block's list full gets them right away.
+        u32 at = 0;
+        if (sub == (u32)(k % kLookupLanes)) {
+          my_row[o] = row;
+          ++made;
+          at = atomicAdd(&s_new, 1u);
+          if (at < kNewLdsCap) { s_new_key[at] = key; s_new_row[at] = row; }
+        }
+        if (quad_lane(at, k % kLookupLanes) >= kNewLdsCap) {
+          const u64 base = mix64(key ^ t.init_seed);
+          for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row, j, init_weight(base, j, t.init_range));
+          float* ar = acc_row(t, row);
           for (u32 j = sub; j < t.acc_len; j += kLookupLanes) ar[j] = t.init_acc;
         }
       }
     }
-    // back to one key per lane: its row, and the push's work lists
-    u32 my_row = row[0];
+    // every lane: the rows of its own keys, and the push's work lists
 #pragma unroll
-    for (int k = 1; k < K; ++k) my_row = sub == (u32)k ? row[k] : my_row;
-    if (!my_valid) continue;
-    rows[my_u] = my_row;
-    if (my_key == kEmptyKey) continue;
-    if (my_row == kNoRow) {
-      const u32 at = atomicAdd(&s_missing, 1u);
-      if (at < kMissLdsCap) s_list[at] = (u32)my_u;
-    }
-    if (my_len >= often.heavy_min) {
-      const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
-      if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = my_key;
-    }
-    if (my_len >= often.hot_min && my_row != kNoRow) {
-      const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
-      if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)my_u, my_row);
-    }
-    if (my_len > kMedSeg) {
-      const u32 n_chunks = (my_len + kChunk - 1) / kChunk;
-      const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
-      often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)my_u, first);
-      for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)my_u, c);
-    } else if (my_len > kShortSeg) {
-      const u32 at = atomicAdd(&s_med, 1u);
-      if (at < kMedLdsCap) {
-        s_med_list[at] = (u32)my_u;
-      } else {      // buffer full: append straight to the shard
-        const u32 shard = blockIdx.x % kCountShards;
-        const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
-        if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)my_u;
+    for (int o = 0; o < OWN; ++o) {
+      const u64 u = u0 + (u64)(o * kLookupLanes + sub) * n_groups;
+      if (u >= n_keys) continue;
+      rows[u] = my_row[o];
+      if (my_key[o] == kEmptyKey) continue;
+      if (my_row[o] == kNoRow) {
+        const u32 at = atomicAdd(&s_missing, 1u);
+        if (at < kMissLdsCap) s_list[at] = (u32)u;
+      }
+      const u32 len = my_len[o];
+      if (len >= often.heavy_min) {
+        const u32 at = atomicAdd(&often.heavy_raw->count, 1u);
+        if (at < (u32)kMaxHeavy) often.heavy_raw->keys[at] = my_key[o];
+      }
+      if (len >= often.hot_min && my_row[o] != kNoRow) {
+        const u32 at = atomicAdd(&often.ctx->n_hot, 1u);
+        if (at < often.hot_cap) often.hot_list[at] = make_uint2((u32)u, my_row[o]);
+      }
+      if (len > kMedSeg) {
+        const u32 n_chunks = (len + kChunk - 1) / kChunk;
+        const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
+        often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
+        for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
+      } else if (len > kShortSeg) {
+        const u32 at = atomicAdd(&s_med, 1u);
+        if (at < kMedLdsCap) {
+          s_med_list[at] = (u32)u;
+        } else {      // buffer full: append straight to the shard
+          const u32 shard = blockIdx.x % kCountShards;
+          const u32 pos = atomicAdd(&often.ctx->med_count[shard], 1u);
+          if (pos < often.med_cap) often.med_list[(u64)shard * often.med_cap + pos] = (u32)u;
+        }
       }
     }
   }
   if (made) atomicAdd(&s_made, made);
   __syncthreads();
   if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
+  // the initial rows of the keys created above: one float4 of one row per lane and turn
+  const u32 n_new = min(s_new, kNewLdsCap);
+  const u32 dim4 = t.dim >> 2;
+  for (u32 e = threadIdx.x; e < n_new * dim4; e += kProbeThreads) {
+    const u32 i = e / dim4, col = e % dim4;
+    const u64 base = mix64(s_new_key[i] ^ t.init_seed);
+    store_w4(t, s_new_row[i], col,
+             make_float4(init_weight(base, 4 * col, t.init_range), init_weight(base, 4 * col + 1, t.init_range),
+                         init_weight(base, 4 * col + 2, t.init_range), init_weight(base, 4 * col + 3, t.init_range)));
+  }
+  for (u32 e = threadIdx.x; e < n_new * t.acc_len; e += kProbeThreads)
+    acc_row(t, s_new_row[e / t.acc_len])[e % t.acc_len] = t.init_acc;
   const u32 n_med = min(s_med, kMedLdsCap);
   if (n_med) {
     const u32 shard = blockIdx.x % kCountShards;
