@@ -349,14 +349,24 @@ def run_workload(name, args, headline):
         ceiling, lib_rate = random_row_ceiling(hps, torch, cfg.dim)
         pp_ms = stages["pool"]["ms"] + stages["push"]["ms"]
         path_rate = (3 * mean_u + mean_n) / (pp_ms * 1e-3)
+        # What the two kernels issue: pooling reads a row per OCCURRENCE (a frequent key's row
+        # is fetched again unless L2 still holds it), the push reads a gradient row per
+        # occurrence and reads and writes the weights and the accumulator(s) of every unique
+        # key (two places unless they lie side by side: the elementwise Adagrad's layout).
+        per_unique = 2 if elementwise and args.rows == "f32" else 4
+        issued_rate = (2 * mean_n + per_unique * mean_u) / (pp_ms * 1e-3)
         res["random_row_access"] = {
             "what": "random %d-byte row accesses per second; pooling + push need at least 3U + N "
-                    "of them per step; ceiling = a kernel that only reads random rows of a 4 GiB "
+                    "of them per step (path_per_s) and issue 2N + %dU (issued_per_s: a row per "
+                    "occurrence in pooling, reads and writes of weights and accumulators in the "
+                    "push); ceiling = a kernel that only reads random rows of a 4 GiB "
                     "array (hps_probe_random_rows); library = torch.index_select over the same "
-                    "array" % (4 * cfg.dim),
+                    "array" % (4 * cfg.dim, per_unique),
             "row_bytes": 4 * cfg.dim,
             "path_per_s": round(path_rate, 1), "ceiling_per_s": round(ceiling, 1),
-            "frac": round(path_rate / ceiling, 3), "library_per_s": round(lib_rate, 1)}
+            "frac": round(path_rate / ceiling, 3),
+            "issued_per_s": round(issued_rate, 1), "issued_frac": round(issued_rate / ceiling, 3),
+            "library_per_s": round(lib_rate, 1)}
 
     # ---- CPU oracle on a bounded sample of the same workload ------------------------------
     if headline and args.cpu_seconds > 0:

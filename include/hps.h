@@ -47,17 +47,28 @@
  *     does not touch the table and may run on another stream; the library orders it
  *     against the calls that share its buffers with HIP events.
  *   - Do not capture hps_prepare / hps_pull / hps_accumulate into a HIP graph for replay:
- *     every dedup carries a sequence number, chosen on the host when the call is made,
- *     that tells its kernels which of the workspace's hand-off words are theirs; a
- *     replay would reuse the number of the captured call.
+ *     three things about a dedup are chosen on the host when the call is made and would be
+ *     frozen by a capture: which of the three lists of frequent keys its kernels read and
+ *     which one the lookup after it fills (a ring, so that a dedup on another stream never
+ *     reads a list that is still being written), which form the dedup takes (below), and,
+ *     in the plain form, the sequence number that tells its kernels which of the
+ *     workspace's hand-off words are theirs.
  *   - The key dedup has two forms with identical results; the library picks one per call
- *     from the mini-batch's size and the table's history (its third and later dedups use
- *     the keys that earlier lookups found frequent; the lookups report back, into pinned
- *     host memory that nobody waits for, when the keys did not suit that form, and the next
- *     dedups then take the other one, sorting by all 64 key bits if need be:
- *     hps_stats().n_plain_fallbacks, .n_full_fallbacks).  The environment
- *     variable HPS_DEDUP, read by hps_create, pins the form: "radix" or "bucket" (tests,
- *     comparison runs).
+ *     from the mini-batch's size and the table's history.  A table's third and later dedups
+ *     use the keys that earlier lookups found frequent and run without any waits between
+ *     workgroups (counts per tile, a scan, a scatter; then every region of the array is put
+ *     in order inside one workgroup).  The lookups report back, into pinned host memory that
+ *     nobody waits for, when the keys did not suit that form, and the next dedups then take
+ *     the plain form (radix passes with look-back between tiles), sorting by all 64 key
+ *     bits if need be: hps_stats().n_plain_fallbacks, .n_full_fallbacks.
+ *   - Environment variables, read by hps_create, for tests and comparison runs:
+ *     HPS_DEDUP = "radix" | "bucket" pins the dedup's form; HPS_RANK = "ballot" ranks the
+ *     elements of a sort tile with wave ballots even where the GPU's LDS atomics would
+ *     serve (the faster way; hps_create checks on every GPU that they answer the lanes of
+ *     an instruction in lane order, and uses ballots where they do not); HPS_POOL = "lds"
+ *     makes the pooling kernel keep the most frequent keys' rows in LDS (measured slower);
+ *     HPS_ROWS = "apart" keeps weights and accumulators in arrays of their own also where
+ *     the library would put them side by side (float32 rows, elementwise Adagrad).
  */
 #ifndef HPS_H_
 #define HPS_H_

@@ -1,19 +1,20 @@
-// Key dedup, the short way: two radix passes by bucket id, then every chunk of the
-// array is finished inside one workgroup.
+// Key dedup, bucket form, part 2: every region of the array is finished inside one workgroup.
 //
-// After the passes (sort.hpp, by_id mode) the occurrences are ordered by bucket id:
-// buckets of keys that share their leading bits (a few hundred occurrences each, in
-// occurrence order) and, between them, one bucket per heavy key.  chunk_sort_emit
-// cuts the array into regions at bucket borders (about kChunkSpan positions each; a
-// heavy key's bucket may be cut anywhere, it holds one key), orders each region by
-// full key in LDS -- stable, so equal keys keep their occurrence order -- and writes
-// the dedup's outputs directly:
+// After the partition (partition.hpp) the occurrences are ordered by bucket id: buckets of
+// keys that share their place in the key range (a few hundred occurrences each, in
+// occurrence order) and, between them, one bucket per heavy key.  region_borders has cut the
+// array into regions at bucket borders (about kChunkSpan positions each; a heavy key's bucket
+// may be cut anywhere, it holds one key).  Two launches, neither waits for another workgroup:
+//   region_sort   orders each region by full key in LDS -- stable, so equal keys keep their
+//                 occurrence order -- and leaves, per region, the order (one word per
+//                 position), how many group heads (distinct keys) it holds, and how it was
+//                 ordered; per group of 64 regions, the heads of the group;
+//   region_emit   adds up the heads of earlier groups and regions and writes the dedup's
+//                 outputs:
 //   uniq[U]      ascending unique keys
 //   inverse[N]   rank of each occurrence's key among them
 //   bagperm[N]   bag of each occurrence, occurrences grouped by key, bit 31 on group heads
 //   seg_off[U+1] start of each key's group in bagperm
-// The number of unique keys in earlier regions comes from the grouped look-back over
-// status words (sort.hpp).
 //
 // Which keys are heavy is a hint, taken from an earlier mini-batch (the lookup lists
 // the keys that occurred often, the kernel after it puts them in order; common.hpp).  Hot keys of click

@@ -13,15 +13,14 @@
 //                   wave ballots; the tile is staged in LDS and each digit's run is
 //                   written contiguously.
 //
-// What the passes sort by comes in two forms.
-//   Bucket ids (by_id plans; the usual form): one or two passes by a 16-bit id made of the
-//   key's leading bits and its place among the heavy keys (bucket_id below); the rest of
-//   the ordering happens per region inside one workgroup (bucket.hpp).
-//   Key bits (plain plans): the top 8 * n_pass bits of the key's place in the range the
-//   mini-batch's keys span (for hashed keys: of the key).  Mini-batch keys are hashed
-//   feature ids, so these bits separate almost all distinct keys; the rare runs that
-//   still mix different keys are found and put right afterwards (dedup.hpp).  With
-//   eight passes every bit is sorted and nothing is left to put right.
+// These passes are the plain form of the dedup: they sort by the top 8 * n_pass bits of the
+// key's place in the range the mini-batch's keys span (for hashed keys: of the key).
+// Mini-batch keys are hashed feature ids, so these bits separate almost all distinct keys;
+// the rare runs that still mix different keys are found and put right afterwards
+// (dedup.hpp).  With eight passes every bit is sorted and nothing is left to put right.
+// The usual form, by bucket ids (bucket_id below), has passes of its own without any waits
+// between workgroups (partition.hpp) and finishes per region (bucket.hpp); it shares this
+// file's key range, bucket ids and ranking helpers.
 // Either way the dedup's result is exact for any input.
 //
 // Cross-tile counts without a serial chain: tiles are grouped, `group` consecutive
@@ -56,10 +55,11 @@ constexpr int kPrepThreads = 256;
 constexpr int kHistShards = 16;
 constexpr int kHistWords = kHistShards * kMaxPasses * kRadix;   // one pull's histograms
 
-// A wait for another workgroup's status word gives up after this long (100 MHz ticks: one
-// minute).  Nothing legitimate comes near: the slowest producer is a workgroup that sorts
-// one oversized bucket through global memory (bucket.hpp), seconds at the very worst.
-constexpr u64 kWaitTicks = 6000000000ull;
+// A wait for another workgroup's status word gives up after this long (100 MHz ticks: five
+// seconds).  Nothing legitimate comes near: only the plain form's passes wait, a tile for
+// the counts of tiles with smaller tickets, which are running and need microseconds each
+// (the bucket form has no waits between workgroups at all).
+constexpr u64 kWaitTicks = 500000000ull;
 constexpr u32 kRangeSamples = 2048;    // keys sampled for the key range (sort_prepare)
 constexpr u32 kEpochMod = 4095;        // epochs run 1..4095
 constexpr u32 kMaxTileGroup = 64;      // tiles per group at most (count fits 19 bits)
