@@ -253,6 +253,9 @@ struct hps_table {
   uint64_t lookup_serial;   // lookups so far; lookup s lists its frequent keys in ring slot s % 3
   int dedup_mode;      // 0: by size and history; 1: plain radix passes always; 2: bucket path whenever it can
   bool ordered_rank;   // the GPU's LDS atomics serve a wave's lanes in lane order (sort.hpp: digit_rank)
+  // How much of pull_lookup's per-block list of created keys is used: all of it, unless
+  // HPS_LOOKUP_NEW_LIST says less (tests of what happens when it is full).
+  u32 lookup_new_cap;
   // The pooling kernel keeps the most frequent keys' rows in LDS (HPS_POOL=lds).  Off unless
   // asked for: measured slower than reading them through L2 on every workload (the hash probe
   // per occurrence costs more than the L2 hits it saves, and the LDS halves the occupancy).
@@ -541,7 +544,7 @@ static void launch_lookup(hps_table* t, int c, uint64_t n_keys, bool create, hip
   const unsigned probe_blocks = grid_for(n_keys, kLookupGroups * kPullInFlight, kProbeMaxBlocks);
   pull_lookup<<<probe_blocks, kProbeThreads, 0, s>>>(
       t->view, t->w<u64>(C.uniq), &ctx->n_unique, t->w<u32>(C.rows), t->w<u32>(t->wl.miss_list),
-      (u32)t->wl.shard_cap, create ? 1u : 0u, often);
+      (u32)t->wl.shard_cap, create ? 1u : 0u, t->lookup_new_cap, often);
 
 }
 
@@ -719,6 +722,11 @@ hps_status hps_create(hps_table** out, uint64_t capacity_keys, uint32_t dim,
     t->dedup_mode = !mode ? 0 : std::strcmp(mode, "radix") == 0 ? 1 : std::strcmp(mode, "bucket") == 0 ? 2 : 0;
   }
 
+  t->lookup_new_cap = kNewLdsCap;
+  if (const char* cap = std::getenv("HPS_LOOKUP_NEW_LIST")) {
+    const unsigned n = (unsigned)std::strtoul(cap, nullptr, 10);
+    t->lookup_new_cap = n < kNewLdsCap ? n : kNewLdsCap;
+  }
   {
     const char* pool = std::getenv("HPS_POOL");
     t->hot_rows = pool && std::strcmp(pool, "lds") == 0;

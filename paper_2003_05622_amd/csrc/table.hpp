@@ -539,7 +539,9 @@ __device__ __forceinline__ u32 bucket_bits(const BucketSlots& s, u64 key, u32 su
 __global__ void __launch_bounds__(kProbeThreads)
 pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n_keys_dev,
             u32* __restrict__ rows, u32* __restrict__ miss_list, u32 shard_cap, u32 create,
-            OftenLists often) {
+            u32 new_cap, OftenLists often) {
+  // new_cap <= kNewLdsCap: how much of the block's list of created keys is used (all of it,
+  // except in tests of what happens when it is full)
   constexpr int K = kPullInFlight;            // keys a group has in flight
   constexpr int OWN = K / kLookupLanes;       // of which each lane owns this many
   __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made, s_new;
@@ -676,9 +678,9 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
           my_row[o] = row;
           ++made;
           at = atomicAdd(&s_new, 1u);
-          if (at < kNewLdsCap) { s_new_key[at] = key; s_new_row[at] = row; }
+          if (at < new_cap) { s_new_key[at] = key; s_new_row[at] = row; }
         }
-        if (quad_lane(at, k % kLookupLanes) >= kNewLdsCap) {
+        if (quad_lane(at, k % kLookupLanes) >= new_cap) {
           const u64 base = mix64(key ^ t.init_seed);
           for (u32 j = sub; j < t.dim; j += kLookupLanes) store_w(t, row, j, init_weight(base, j, t.init_range));
           float* ar = acc_row(t, row);
@@ -727,7 +729,7 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
   __syncthreads();
   if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
   // the initial rows of the keys created above: one float4 of one row per lane and turn
-  const u32 n_new = min(s_new, kNewLdsCap);
+  const u32 n_new = min(s_new, new_cap);
   const u32 dim4 = t.dim >> 2;
   for (u32 e = threadIdx.x; e < n_new * dim4; e += kProbeThreads) {
     const u32 i = e / dim4, col = e % dim4;

@@ -118,6 +118,18 @@ def test_tiny_config_full_size():
     run_steps(synth.CONFIGS["tiny"], steps=3)
 
 
+@pytest.mark.parametrize("room", ["0", "5"])
+def test_lookup_with_its_list_of_created_keys_full(room, monkeypatch):
+    """The pull's lookup notes the keys it creates in a list per block and writes their initial
+    rows at its end, all lanes together.  With room for only a few entries (or none) the keys
+    that find the list full get their rows on the spot: same results."""
+    monkeypatch.setenv("HPS_LOOKUP_NEW_LIST", room)          # read when the table is created
+    cfg = synth.scaled(synth.CONFIGS["insert_heavy"], n_prefill=40_000, n_examples=128, n_slots=40, steps=4)
+    run_steps(cfg, steps=4)
+    cfg = synth.scaled(synth.CONFIGS["mid"], n_prefill=3000, n_examples=64, n_slots=20, steps=3)
+    run_steps(cfg, steps=3, opt=hps.ADAGRAD_ELEMENTWISE)
+
+
 @pytest.mark.parametrize("name,n_prefill,n_examples,n_slots", [
     ("mid", 200_000, 128, 100),            # ~64k occurrences: several sort tiles, ragged tail
     ("insert_heavy", 50_000, 64, 100),
