@@ -119,6 +119,7 @@ constexpr int kProbeMaxBlocks = 1024;
 constexpr u32 kNoSlot = ~0u;
 constexpr u32 kMissLdsCap = 2048;        // missing keys a block can list per lookup
 constexpr u32 kNewLdsCap = 1024;         // created keys a block lists for its common initialisation
+constexpr u32 kLongLdsCap = 64;          // very frequent keys whose chunk items a block writes together
 constexpr u32 kMedLdsCap = 512;          // medium keys a block buffers before it appends
 constexpr u32 kShortSeg = 16;            // occurrences handled serially by one lane group
 constexpr u32 kMedSeg = 512;             // occurrences handled by one wave
@@ -544,7 +545,8 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
   // except in tests of what happens when it is full)
   constexpr int K = kPullInFlight;            // keys a group has in flight
   constexpr int OWN = K / kLookupLanes;       // of which each lane owns this many
-  __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made, s_new;
+  __shared__ u32 s_missing, s_base, s_med, s_med_base, s_made, s_new, s_long;
+  __shared__ uint4 s_long_list[kLongLdsCap];  // (key, first chunk item, chunks) of the block's very frequent keys
   __shared__ u32 s_list[kMissLdsCap];
   __shared__ u32 s_med_list[kMedLdsCap];
   __shared__ u64 s_new_key[kNewLdsCap];       // keys created by this block, and their rows
@@ -563,7 +565,7 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
     return;
   }
   if (load_error(t.st) != 0) return;
-  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; s_made = 0; s_new = 0; }
+  if (threadIdx.x == 0) { s_missing = 0; s_med = 0; s_made = 0; s_new = 0; s_long = 0; }
   __syncthreads();
   // (the size does not change while this kernel runs: every thread decides the same)
   const bool create_here = create && t.st->size + n_keys <= t.capacity;
@@ -712,7 +714,14 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
         const u32 n_chunks = (len + kChunk - 1) / kChunk;
         const u32 first = atomicAdd(&often.ctx->n_chunk_items, n_chunks);
         often.long_list[atomicAdd(&often.ctx->n_long, 1u)] = make_uint2((u32)u, first);
-        for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
+        // the key's chunk items are written at the end of the kernel by all lanes of the block
+        // (a key that fills thousands of chunks would keep this lane, and its wave, for long)
+        const u32 at = atomicAdd(&s_long, 1u);
+        if (at < kLongLdsCap) {
+          s_long_list[at] = make_uint4((u32)u, first, n_chunks, 0u);
+        } else {
+          for (u32 c = 0; c < n_chunks; ++c) often.chunk_items[first + c] = make_uint2((u32)u, c);
+        }
       } else if (len > kShortSeg) {
         const u32 at = atomicAdd(&s_med, 1u);
         if (at < kMedLdsCap) {
@@ -728,6 +737,13 @@ pull_lookup(TableView t, const u64* __restrict__ keys, const u32* __restrict__ n
   if (made) atomicAdd(&s_made, made);
   __syncthreads();
   if (threadIdx.x == 0 && s_made) atomicAdd(&t.st->made_shard[blockIdx.x % kCountShards], s_made);
+  {
+    const u32 n_long_here = min(s_long, kLongLdsCap);
+    for (u32 e = 0; e < n_long_here; ++e) {
+      const uint4 it = s_long_list[e];
+      for (u32 c = threadIdx.x; c < it.z; c += kProbeThreads) often.chunk_items[it.y + c] = make_uint2(it.x, c);
+    }
+  }
   // the initial rows of the keys created above: one float4 of one row per lane and turn
   const u32 n_new = min(s_new, new_cap);
   const u32 dim4 = t.dim >> 2;
