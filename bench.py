@@ -144,7 +144,9 @@ def run_workload(name, args, headline):
     whole_run = name == "insert_heavy"      # the workload IS its 50 consecutive steps
     steps = cfg.steps if whole_run else (args.steps if headline else min(args.steps, 20))
     warmup = 0 if whole_run else (args.warmup if headline else min(args.warmup, 3))
-    extra_steps = 5 if headline else 0      # all-stage timing run after the timed region
+    # all-stage timing run after the timed region (insert_heavy is its 50 consecutive steps and
+    # nothing else: its stages are timed inside them)
+    extra_steps = 0 if whole_run else 5
     serial = not args.pipelined
     # the other schedule afterwards, for comparison
     other_steps = 8 if headline and not args.one_schedule else 0
@@ -170,7 +172,7 @@ def run_workload(name, args, headline):
                          init_acc=cfg.init_acc, init_range=cfg.init_range,
                          init_seed=cfg.init_seed,
                          opt=hps.ADAGRAD_ELEMENTWISE if elementwise else hps.ADAGRAD_ROWWISE,
-                         row_format=hps.ROWS_BF16 if args.rows == "bf16" else hps.ROWS_F32)
+                         row_format={"bf16": hps.ROWS_BF16, "f32wide": hps.ROWS_F32_WIDE}.get(args.rows, hps.ROWS_F32))
     chunk = 1 << 23
     for lo in range(0, cfg.n_prefill, chunk):
         table.insert(dev_keys(synth.prefill_keys(lo, min(lo + chunk, cfg.n_prefill))))
@@ -220,9 +222,10 @@ def run_workload(name, args, headline):
         dominant = "dedup"
     else:
         dominant = max(calib, key=lambda s: calib[s][0])
-    # the headline run times its dominant stage only inside the timed region (fewer events on
-    # the stream); the others time every stage of every step
-    table.set_stage_timing(STAGE_BITS[dominant] if headline else 0b11111)
+    # inside the timed region only the dominant stage is timed (fewer events on the stream),
+    # and for the workloads beside the headline one nothing; all stages are timed in a few
+    # further steps afterwards
+    table.set_stage_timing(0b11111 if whole_run else STAGE_BITS[dominant] if headline else 0)
 
     # ---- timed region --------------------------------------------------------------------
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if whole_run else None
@@ -345,7 +348,7 @@ def run_workload(name, args, headline):
     # measured here with a kernel that does nothing but read random rows of a 4 GiB array in
     # the pooling kernel's access shape (hps_probe_random_rows), and, for comparison, with a
     # plain library gather (torch.index_select) over the same array.
-    if headline and args.gather_rows and cfg.dim in (16, 64) and args.rows == "f32":
+    if headline and args.gather_rows and cfg.dim in (16, 64) and args.rows != "bf16":
         ceiling, lib_rate = random_row_ceiling(hps, torch, cfg.dim)
         pp_ms = stages["pool"]["ms"] + stages["push"]["ms"]
         path_rate = (3 * mean_u + mean_n) / (pp_ms * 1e-3)
@@ -353,7 +356,7 @@ def run_workload(name, args, headline):
         # is fetched again unless L2 still holds it), the push reads a gradient row per
         # occurrence and reads and writes the weights and the accumulator(s) of every unique
         # key (two places unless they lie side by side: the elementwise Adagrad's layout).
-        per_unique = 2 if elementwise and args.rows == "f32" else 4
+        per_unique = 2 if (elementwise and args.rows == "f32") or args.rows == "f32wide" else 4
         issued_rate = (2 * mean_n + per_unique * mean_u) / (pp_ms * 1e-3)
         res["random_row_access"] = {
             "what": "random %d-byte row accesses per second; pooling + push need at least 3U + N "
@@ -425,7 +428,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, so that a counter run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
-    ap.add_argument("--rows", choices=("f32", "bf16"), default="f32",
+    ap.add_argument("--rows", choices=("f32", "bf16", "f32wide"), default="f32",
                     help="how the table stores weights (the arithmetic is float32 either way)")
     ap.add_argument("--adagrad", choices=("rowwise", "elementwise"), default="rowwise",
                     help="one accumulator per row (the default) or one per element")

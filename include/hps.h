@@ -68,7 +68,10 @@
  *     an instruction in lane order, and uses ballots where they do not); HPS_POOL = "lds"
  *     makes the pooling kernel keep the most frequent keys' rows in LDS (measured slower);
  *     HPS_ROWS = "apart" keeps weights and accumulators in arrays of their own also where
- *     the library would put them side by side (float32 rows, elementwise Adagrad).
+ *     the library would put them side by side (float32 rows, elementwise Adagrad);
+ *     HPS_LOOKUP_NEW_LIST = n makes the pull's lookup use only n entries of the list in
+ *     which a workgroup notes the keys it creates (a key that finds it full gets its initial
+ *     row on the spot: the test of that path).
  */
 #ifndef HPS_H_
 #define HPS_H_
@@ -107,7 +110,13 @@ typedef enum {
  * rounded to the nearest bfloat16 (ties to even) when it is stored, nothing else changes. */
 typedef enum {
   HPS_ROWS_F32 = 0,
-  HPS_ROWS_BF16 = 1
+  HPS_ROWS_BF16 = 1,
+  /* float32 rows with each row's accumulator(s) behind its weights, one record per row, the
+   * records padded to whole 128-byte memory lines (dim 16, one accumulator per row: 128 bytes
+   * per row instead of 68).  Same values as HPS_ROWS_F32; trades HBM capacity for requests:
+   * the push finds a row's accumulator in the line it fetches for the weights instead of in a
+   * line of its own (this GPU fetches 128 bytes for any part of a line). */
+  HPS_ROWS_F32_WIDE = 2
 } hps_row_format;
 
 typedef struct {

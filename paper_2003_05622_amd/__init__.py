@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     ADAGRAD_ELEMENTWISE,
     ROWS_F32,
     ROWS_BF16,
+    ROWS_F32_WIDE,
     OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM,
     EXPORTS,
     STAGES,

@@ -9,7 +9,7 @@ from .build import ensure_built
 
 OK, EINVAL, EFULL, ERESERVED, ESTATE, EDEVICE, ENOMEM = 0, -1, -2, -3, -4, -5, -6
 ADAGRAD_ROWWISE, ADAGRAD_ELEMENTWISE = 0, 1
-ROWS_F32, ROWS_BF16 = 0, 1
+ROWS_F32, ROWS_BF16, ROWS_F32_WIDE = 0, 1, 2
 
 EXPORTS = ("hps_table_bytes", "hps_workspace_bytes", "hps_create", "hps_insert", "hps_pull",
            "hps_prepare", "hps_pull_prepared",

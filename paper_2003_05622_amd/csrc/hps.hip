@@ -47,7 +47,8 @@ uint64_t slots_for(uint64_t capacity) {
 
 bool valid_opt(const hps_optimizer* o) {
   return o && (o->kind == HPS_OPT_ADAGRAD_ROWWISE || o->kind == HPS_OPT_ADAGRAD_ELEMENTWISE) &&
-         (o->row_format == HPS_ROWS_F32 || o->row_format == HPS_ROWS_BF16) &&
+         (o->row_format == HPS_ROWS_F32 || o->row_format == HPS_ROWS_BF16 ||
+          o->row_format == HPS_ROWS_F32_WIDE) &&
          o->init_range >= 0.f && o->eps >= 0.f && o->init_acc >= 0.f;
 }
 
@@ -74,7 +75,13 @@ StorageLayout storage_layout(uint64_t n_slots, uint32_t dim, uint32_t acc_len, i
   size_t o = 0;
   L.keys = o;  o = align_up(o + n_slots * sizeof(uint64_t));
   const uint32_t w_bytes = dim * (row_format == HPS_ROWS_BF16 ? 2 : 4), acc_bytes = acc_len * 4;
-  if (rows_side_by_side(dim, acc_len, row_format)) {
+  if (row_format == HPS_ROWS_F32_WIDE) {
+    // one record per row, whole memory lines
+    const uint32_t pitch = (w_bytes + acc_bytes + 127) / 128 * 128;
+    L.w = o;   L.acc = o + w_bytes;
+    L.w_pitch = L.acc_pitch = pitch;
+    o = align_up(o + n_slots * (size_t)pitch);
+  } else if (rows_side_by_side(dim, acc_len, row_format)) {
     L.w = o;   L.acc = o + w_bytes;
     L.w_pitch = L.acc_pitch = w_bytes + acc_bytes;
     o = align_up(o + n_slots * (size_t)(w_bytes + acc_bytes));

@@ -71,18 +71,20 @@ def ot_init_acc(ot):
 
 def make_pair(cfg, max_keys, opt=hps.ADAGRAD_ROWWISE, row_format=hps.ROWS_F32):
     kw = dict(lr=cfg.lr, eps=cfg.eps, init_acc=cfg.init_acc, init_range=cfg.init_range,
-              init_seed=cfg.init_seed, row_format=row_format)
-    gt = hps.HpsTable(cfg.capacity, cfg.dim, max_keys, cfg.n_bags, opt=opt, **kw)
-    ot = OracleTable(cfg.capacity, cfg.dim, opt=opt, **kw)
+              init_seed=cfg.init_seed)
+    gt = hps.HpsTable(cfg.capacity, cfg.dim, max_keys, cfg.n_bags, opt=opt, row_format=row_format, **kw)
+    # (the wide format is a layout of float32 rows: the same values)
+    ot = OracleTable(cfg.capacity, cfg.dim, opt=opt, **kw,
+                     row_format=oracle.ROWS_BF16 if row_format == hps.ROWS_BF16 else oracle.ROWS_F32)
     ot._init_acc = cfg.init_acc
     return gt, ot
 
 
-def run_steps(cfg, steps, opt=hps.ADAGRAD_ROWWISE, check_every=1, mean=False):
+def run_steps(cfg, steps, opt=hps.ADAGRAD_ROWWISE, check_every=1, mean=False, row_format=hps.ROWS_F32):
     stream = synth.BatchStream(cfg)
     mean_bag = cfg.bag_mean if cfg.bag_kind == "poisson" else cfg.bag_hi
     max_keys = int(cfg.n_bags * mean_bag * 1.5) + 4096
-    gt, ot = make_pair(cfg, max_keys, opt)
+    gt, ot = make_pair(cfg, max_keys, opt, row_format)
     pre = synth.prefill_keys(0, cfg.n_prefill)
     gt.insert(dev_keys(pre))
     ot.insert(pre)
@@ -116,6 +118,38 @@ def run_steps(cfg, steps, opt=hps.ADAGRAD_ROWWISE, check_every=1, mean=False):
 
 def test_tiny_config_full_size():
     run_steps(synth.CONFIGS["tiny"], steps=3)
+
+
+@pytest.mark.parametrize("opt", [hps.ADAGRAD_ROWWISE, hps.ADAGRAD_ELEMENTWISE])
+@pytest.mark.parametrize("name,n_prefill,n_examples,n_slots", [
+    ("mid", 60_000, 96, 50),               # dim 16: a row and its accumulator(s) in one or two lines
+    ("skewed", 40_000, 128, 32),           # dim 64: records of three (row-wise) or four lines
+    ("tiny", 20_000, 64, 20),              # dim 8
+])
+def test_wide_rows(name, n_prefill, n_examples, n_slots, opt):
+    """HPS_ROWS_F32_WIDE: every row's accumulators behind its weights, records padded to whole
+    128-byte lines.  A layout only: the same results as with plain float32 rows, to the same
+    bar; get / dump / dump_dirty / accumulate / clear go through the same row accessors."""
+    cfg = synth.scaled(synth.CONFIGS[name], n_prefill=n_prefill, n_examples=n_examples,
+                       n_slots=n_slots, steps=4)
+    gt, ot = run_steps(cfg, steps=4, opt=opt, row_format=hps.ROWS_F32_WIDE)
+    rng = np.random.default_rng(5)
+    k, w, a = gt.dump()
+    k = host_keys(k)
+    pick = k[rng.integers(0, k.size, size=min(k.size, 2000))]
+    v = rng.normal(0, 1e-3, size=(pick.size, cfg.dim)).astype(np.float32)
+    gt.accumulate(dev_keys(pick), torch.from_numpy(v).cuda())
+    ot.accumulate(pick, v)
+    compare_tables(gt, ot, "wide rows after accumulate", pick)
+    gw, ga, found = gt.get(dev_keys(pick[:100]))
+    ow, oa, of = ot.get(pick[:100])
+    assert found.cpu().numpy().all() and of.all()
+    assert_close(gw.cpu().numpy(), ow, "get weights")
+    assert_close(ga.cpu().numpy(), oa, "get accumulators")
+    dk, dw, da = gt.dump(dirty=True)
+    assert np.array_equal(np.sort(host_keys(dk)), ot.dump_dirty()[0])
+    gt.clear()
+    assert gt.stats().size == 0
 
 
 @pytest.mark.parametrize("room", ["0", "5"])
