@@ -81,7 +81,8 @@ struct PullCtx {
 // Keys that make up a large share of a mini-batch (bucket.hpp).  HeavySet: ascending,
 // padded with all-ones.  HeavyRaw: the keys the last lookup saw often, in arrival
 // order; only a hint, readers cope with any content.
-constexpr int kMaxHeavy = 1023;
+constexpr int kMaxHeavy = 4095;
+constexpr int kSmallHeavy = 1023;    // lists up to this long are copied to LDS by the kernels that look keys up in them
 constexpr int kHeavyTopBits = 10;
 struct HeavySet {
   u32 count;

@@ -144,9 +144,11 @@ __device__ __forceinline__ KeyRange make_range(u64 lo, u64 hi, const SortPlan& p
 // heavy key lies between them, and a heavy key shares its id with nothing.
 
 // The heavy keys in LDS, with their spans per value of the top bits, so that a lookup
-// costs one LDS read unless heavy keys share the key's top bits.
+// costs one LDS read unless heavy keys share the key's top bits.  A list of more than
+// kSmallHeavy keys (rare) stays in global memory: `keys` points to it instead of `lds_keys`.
 struct HeavyLds {
-  u64 keys[kMaxHeavy + 1];
+  u64 lds_keys[kSmallHeavy + 1];
+  const u64* keys;
   u32 span[1 << kHeavyTopBits];
   KeyRange range;
   u32 max_heavy;     // only the max_heavy smallest heavy keys get buckets of their own
@@ -155,9 +157,16 @@ struct HeavyLds {
 // All threads of the block; the caller's next barrier makes the copy visible.  H.range is
 // the caller's to fill.
 __device__ __forceinline__ void load_heavy(HeavyLds& H, const HeavySet* set, u32 max_heavy) {
-  for (u32 i = threadIdx.x; i <= (u32)kMaxHeavy; i += blockDim.x) H.keys[i] = set->keys[i];
+  // (only the listed keys are ever looked at: the spans index nothing behind them)
+  const u32 count = min(set->count, (u32)kMaxHeavy);
+  const bool small = count <= (u32)kSmallHeavy;
+  if (small)
+    for (u32 i = threadIdx.x; i < count; i += blockDim.x) H.lds_keys[i] = set->keys[i];
   for (u32 i = threadIdx.x; i < (1u << kHeavyTopBits); i += blockDim.x) H.span[i] = set->span[i];
-  if (threadIdx.x == 0) H.max_heavy = max_heavy;
+  if (threadIdx.x == 0) {
+    H.max_heavy = max_heavy;
+    H.keys = small ? H.lds_keys : set->keys;
+  }
 }
 
 // *heavy tells whether the key is one of the heavy keys (that count: see max_heavy;
@@ -166,10 +175,15 @@ __device__ __forceinline__ u32 bucket_id(u64 key, const HeavyLds& H, bool* heavy
   const u32 sp = H.span[(u32)(key >> (64 - kHeavyTopBits))];
   u32 m = sp & 0xFFFFu;
   const u32 end = m + (sp >> 16);
-  while (m < end && H.keys[m] < key) ++m;
-  *heavy = m < end && m < H.max_heavy && H.keys[m] == key;
+  bool is_heavy = false;
+  if (m < end) {                       // (most keys: no heavy key shares their top bits)
+    const u64* hk = H.keys;
+    while (m < end && hk[m] < key) ++m;
+    is_heavy = m < end && m < H.max_heavy && hk[m] == key;
+  }
+  *heavy = is_heavy;
   m = min(m, H.max_heavy);
-  return natural_bucket(key, H.range) + 2 * m + (*heavy ? 1u : 0u);
+  return natural_bucket(key, H.range) + 2 * m + (is_heavy ? 1u : 0u);
 }
 
 // ---- status words -------------------------------------------------------------------

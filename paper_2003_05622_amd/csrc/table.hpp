@@ -166,35 +166,102 @@ __device__ __forceinline__ bool acc_is_marked(float stored) {
   return (__float_as_uint(stored) & 0x80000000u) != 0;
 }
 
-// Called by all threads of one block (exactly 256) once lookup `slot`'s list of frequent
-// keys is complete: orders it into the ring's set and empties the next list.
-__device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
-  constexpr u32 kSize = kMaxHeavy + 1;             // a power of two
-  __shared__ u64 sorted[kSize];
+// One step of a bitonic sorting network over words[0, size), size a power of two; all threads
+// of a block of 256, a barrier before every step.  GLOBAL: the words live in global memory
+// and are read and written with device-scope accesses, so that what one wave wrote before the
+// barrier is what another reads after it.
+template <bool GLOBAL>
+__device__ __forceinline__ void bitonic_sort_256(u64* words, u32 size) {
   const u32 tid = threadIdx.x;
-  const HeavyRaw& raw = ring->raw[slot];
-  HeavySet& set = ring->set[slot];
-  const u32 count = min(raw.count, (u32)kMaxHeavy);
-  for (u32 i = tid; i < kSize; i += 256) sorted[i] = i < count ? raw.keys[i] : ~0ull;
-  // bitonic sorting network over the smallest power of two that holds the listed keys
-  // (the order of equal keys does not matter; everything behind is all-ones already)
-  u32 size = 2;
-  while (size < count) size <<= 1;
   for (u32 k = 2; k <= size; k <<= 1) {
     for (u32 j = k >> 1; j > 0; j >>= 1) {
+      if (GLOBAL) __threadfence();
       __syncthreads();
       for (u32 i = tid; i < size; i += 256) {
         const u32 partner = i ^ j;
         if (partner > i) {
-          const u64 x = sorted[i], y = sorted[partner];
+          u64 x, y;
+          if (GLOBAL) {
+            x = __hip_atomic_load(words + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            y = __hip_atomic_load(words + partner, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          } else {
+            x = words[i];
+            y = words[partner];
+          }
           const bool up = (i & k) == 0;
-          if ((x > y) == up) { sorted[i] = y; sorted[partner] = x; }
+          if ((x > y) == up) {
+            if (GLOBAL) {
+              __hip_atomic_store(words + i, y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              __hip_atomic_store(words + partner, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+              words[i] = y;
+              words[partner] = x;
+            }
+          }
         }
       }
     }
   }
+  if (GLOBAL) __threadfence();
   __syncthreads();
-  for (u32 i = tid; i < kSize; i += 256) set.keys[i] = sorted[i];
+}
+
+// Called by all threads of one block (exactly 256) once lookup `slot`'s list of frequent
+// keys is complete: orders it into the ring's set and empties the next list.  A list of fewer
+// than kHalfHeavy keys (nearly always) is put in order in LDS in one go; a longer one as two halves,
+// each ordered in LDS and parked in the raw list's own storage (which nobody reads again before
+// it is refilled), then merged: every element finds its place by a binary search in the other
+// half.
+constexpr u32 kHalfHeavy = (kMaxHeavy + 1) / 2;
+__device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
+  constexpr u32 kSize = kMaxHeavy + 1;             // a power of two
+  __shared__ u64 sorted[kHalfHeavy];
+  const u32 tid = threadIdx.x;
+  HeavyRaw& raw = ring->raw[slot];
+  HeavySet& set = ring->set[slot];
+  const u32 count = min(raw.count, (u32)kMaxHeavy);
+  const bool small = count < kHalfHeavy;
+  if (small) {
+    // the smallest power of two that holds the listed keys (the order of equal keys does not
+    // matter; everything behind is all-ones already)
+    u32 size = 2;
+    while (size < count) size <<= 1;
+    for (u32 i = tid; i < kHalfHeavy; i += 256) sorted[i] = i < count ? raw.keys[i] : ~0ull;
+    bitonic_sort_256<false>(sorted, size);
+    for (u32 i = tid; i < kSize; i += 256) set.keys[i] = i < kHalfHeavy ? sorted[i] : ~0ull;
+  } else {
+    for (u32 half = 0; half < 2; ++half) {
+      u64* part = raw.keys + half * kHalfHeavy;
+      for (u32 i = tid; i < kHalfHeavy; i += 256) sorted[i] = half * kHalfHeavy + i < count ? part[i] : ~0ull;
+      bitonic_sort_256<false>(sorted, kHalfHeavy);
+      for (u32 i = tid; i < kHalfHeavy; i += 256) part[i] = sorted[i];
+      __syncthreads();
+    }
+    __threadfence();
+    __syncthreads();
+    // merge: an element's place = its index in its own half + the number of elements of the
+    // other half before it (equal elements: those of the first half first)
+    for (u32 e = tid; e < kSize; e += 256) {
+      const bool second = e >= kHalfHeavy;
+      const u32 i = second ? e - kHalfHeavy : e;
+      const u64* mine = raw.keys + (second ? kHalfHeavy : 0);
+      const u64* other = raw.keys + (second ? 0 : kHalfHeavy);
+      const u64 x = __hip_atomic_load(mine + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      u32 m = 0;
+#pragma unroll
+      for (u32 step = kHalfHeavy / 2; step >= 1; step >>= 1) {
+        const u64 y = __hip_atomic_load(other + m + step - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (second ? y <= x : y < x) m += step;
+      }
+      // (m counts the elements other[0 .. m) that go before x; at most kHalfHeavy - 1 can be
+      // found this way, the last one is looked at separately)
+      const u64 last = __hip_atomic_load(other + kHalfHeavy - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (m == kHalfHeavy - 1 && (second ? last <= x : last < x)) m = kHalfHeavy;
+      set.keys[i + m] = x;
+    }
+    __threadfence();
+    __syncthreads();
+  }
   // spans: thread t takes top-bit values 4t .. 4t+3
   u32 first[5];
 #pragma unroll
@@ -204,9 +271,15 @@ __device__ __forceinline__ void finalize_heavy(HeavyRing* ring, u32 slot) {
     if (v < (1u << kHeavyTopBits)) {
       const u64 bound = (u64)v << (64 - kHeavyTopBits);
       m = 0;
+      if (small) {
 #pragma unroll
-      for (u32 step = (kMaxHeavy + 1) / 2; step >= 1; step >>= 1)
-        if (sorted[m + step - 1] < bound) m += step;     // the all-ones padding is never below
+        for (u32 step = kHalfHeavy / 2; step >= 1; step >>= 1)     // the all-ones padding is never below
+          if (sorted[m + step - 1] < bound) m += step;
+      } else {
+#pragma unroll
+        for (u32 step = kSize / 2; step >= 1; step >>= 1)
+          if (__hip_atomic_load(set.keys + m + step - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bound) m += step;
+      }
     }
     first[e] = m;
   }

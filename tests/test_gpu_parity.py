@@ -599,11 +599,22 @@ def test_dedup_only_batches_with_shifting_hot_keys(dedup_form):
         (390_000, list(range(100, 2100)), [0.0004] * 2000),   # frequent keys than the hint can list
         (390_000, list(range(100, 2100)), [0.0004] * 2000),
     ]
-    for case in cases:
-        keys = batch(*case)
+    def batch_many(n, n_hot, per_key):
+        """n_hot keys of per_key occurrences each among cold ones."""
+        keys = ids[rng.integers(0, 400_000, size=n)]
+        at = rng.choice(n, size=n_hot * per_key, replace=False)
+        keys[at] = np.repeat(ids[400_000 + np.arange(n_hot)], per_key)
+        return keys
+
+    # 3000 frequent keys: the list of frequent keys is put in order as two halves and merged,
+    # and the kernels that consult it read it from global memory; 5000: more than it can hold
+    many = [(390_000, 3000, 100)] * 3 + [(390_000, 5000, 70)] * 3 + [(300_000, 2047, 100), (300_000, 2048, 100),
+                                                                      (300_000, 2049, 100), (300_000, 2049, 100)]
+    for case in cases + many:
+        keys = batch_many(*case) if case in many else batch(*case)
         n = keys.size
         offsets = np.minimum(np.arange(n_bags + 1, dtype=np.int64) * ((n + n_bags - 1) // n_bags), n).astype(np.int32)
-        print("dedup case", case[:3], "n", n, flush=True)
+        print("dedup case", case[:3] if case not in many else ("many",) + case, "n", n, flush=True)
         gt.pull(dev_keys(keys), torch.from_numpy(offsets).cuda(), n_bags, 1)
         ou, oi = oracle.dedup(keys)
         uniq, inv = gt.last_unique()
